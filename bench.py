@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: fused forward + JVP of the relaxed top-k operator.
+
+A step is one pass of the whole path (load, sort, isotonic solve, un-sort scatter, JVP) over one
+batch of the chosen synthetic workload, through the C ABI.  Inputs are resident in HBM before the
+timed region.  Two regimes are timed with HIP events on the launch stream:
+
+  cold : the steps rotate over enough distinct buffer sets (> 512 MiB) that no step finds its
+         inputs in the 256 MiB Infinity Cache -- this is `value` and the roofline figure;
+  warm : every step uses the same buffers (reported in `warm`, an "effective" rate).
+
+Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W [--workload NAME]`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published peak
+BYTES_PER_ELEMENT = 16            # read theta, read tangent, write mask, write JVP (fp32 each)
+METRIC = "rows/s and GB/s (% HBM peak) for topkmask fwd+JVP, 16384x64 k=2 p=2"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="moe_router")
+    ap.add_argument("--mode", choices=["graph", "stream"], default="graph",
+                    help="graph: the K launches are captured once in a HIP graph and replayed; "
+                         "stream: K plain launches from Python")
+    ap.add_argument("--cold-mib", type=int, default=640, help="footprint of the rotating buffer sets")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=4.0)
+    return ap.parse_args()
+
+
+class Runner:
+    """Pre-marshalled calls into the C ABI (no allocation, no tensor checks in the timed loop)."""
+
+    def __init__(self, w, sets, device):
+        import ctypes
+        import torch
+        from paper_2302_01425_amd import binding
+        self.torch = torch
+        self.lib = binding.load()
+        self.w = w
+        x, t = w.inputs()
+        xd, td = torch.from_numpy(x).to(device), torch.from_numpy(t).to(device)
+        self.bufs = []
+        for _ in range(sets):
+            self.bufs.append((xd.clone(), td.clone(), torch.empty_like(xd), torch.empty_like(xd)))
+        op = binding.TOPK_OP_MASK_JVP if w.op == "mask" else binding.TOPK_OP_MAG_JVP
+        binding.ensure_workspace(op, w.rows, w.n, w.k, w.p, device)
+        self.fn = self.lib.topk_mask_jvp if w.op == "mask" else self.lib.topkmag_jvp
+        self.args = [(ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()),
+                      ctypes.c_int64(w.rows), ctypes.c_int64(w.n), ctypes.c_int64(w.k),
+                      ctypes.c_double(w.p), ctypes.c_double(w.lam),
+                      ctypes.c_void_p(c.data_ptr()), ctypes.c_void_p(d.data_ptr()))
+                     for (a, b, c, d) in self.bufs]
+        self.ctypes = ctypes
+
+    def launch(self, i, stream_ptr):
+        rc = self.fn(*self.args[i % len(self.args)], stream_ptr)
+        if rc != 0:
+            raise RuntimeError(f"library call failed: {rc}")
+
+    def timed(self, steps, warmup, mode, rotate):
+        """Returns milliseconds for exactly `steps` steps (HIP events on the launch stream)."""
+        torch = self.torch
+        nsets = len(self.args) if rotate else 1
+        stream = torch.cuda.Stream()
+        sp = self.ctypes.c_void_p(stream.cuda_stream)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            for i in range(warmup):
+                self.launch(i % nsets, sp)
+            stream.synchronize()
+            graph = None
+            if mode == "graph":
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=stream):
+                    for i in range(steps):
+                        self.launch(i % nsets, sp)
+                graph.replay()                      # one untimed replay (upload, page-in)
+                stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            if graph is not None:
+                graph.replay()
+            else:
+                for i in range(steps):
+                    self.launch(i % nsets, sp)
+            e1.record(stream)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+
+def cpu_baseline(w, seconds):
+    """The float64 oracle, as it stands, on this machine's host cores (OpenMP over rows)."""
+    import oracle
+    oracle.build()
+    x, t = w.inputs()
+    fn = oracle.topk_mask if w.op == "mask" else oracle.topkmag
+    rows_cap = w.rows
+    if w.rows * w.n > (1 << 22):                       # bounded sample of very large workloads
+        rows_cap = max(1, (1 << 22) // w.n)
+    xs, ts = x[:rows_cap], t[:rows_cap]
+    if w.rows == 1 and w.n > (1 << 22):                # a single giant row: a prefix of it
+        xs, ts = x[:, : 1 << 22], t[:, : 1 << 22]
+    k = min(w.k, xs.shape[1]) if xs.shape[1] == w.n else max(1, xs.shape[1] // 10)
+    fn(xs, k, w.p, w.lam, tangent=ts)                  # warm the library and the caches
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        fn(xs, k, w.p, w.lam, tangent=ts)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= seconds:
+            break
+    rows_done = reps * xs.shape[0]
+    threads = oracle.max_threads() if xs.shape[0] > 1 else 1
+    return {
+        "value": rows_done / dt, "unit": "rows/s", "cores": threads, "kind": "oracle",
+        "sample": f"{reps} x ({xs.shape[0]} rows x {xs.shape[1]}) of the workload, fwd+JVP, "
+                  f"{dt:.1f} s wall",
+        "elements_per_s": rows_done * xs.shape[1] / dt,
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (rows are independent; nothing here "
+              "uses a second GPU). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2302_01425_amd.workloads import WORKLOADS
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = WORKLOADS[a.workload]
+    algo_bytes = BYTES_PER_ELEMENT * w.rows * w.n
+    set_bytes = 4 * 4 * w.rows * w.n
+    sets = max(2, -(-a.cold_mib * (1 << 20) // set_bytes))
+    r = Runner(w, sets, "cuda:0")
+
+    ms_cold = r.timed(a.steps, a.warmup, a.mode, rotate=True)
+    ms_warm = r.timed(a.steps, a.warmup, a.mode, rotate=False)
+
+    per_cold = ms_cold / a.steps
+    per_warm = ms_warm / a.steps
+    gbps_cold = algo_bytes / (per_cold * 1e-3) / 1e9
+    gbps_warm = algo_bytes / (per_warm * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(a.workload)
+
+    line = {
+        "metric": METRIC if a.workload == "moe_router" else f"rows/s for {w.op} fwd+JVP, {a.workload}",
+        "value": w.rows / (per_cold * 1e-3),
+        "unit": "rows/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": per_cold,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: {w.rows} rows x n={w.n}, k={w.k}, p={w.p:.6g}, "
+                        f"lambda={w.lam}, {w.op} forward + JVP fused, fp32 in/out",
+            "regime": f"cold: {sets} rotating buffer sets, {sets * set_bytes >> 20} MiB",
+            "launch": a.mode,
+            "solve_arithmetic": "f64",
+        },
+        "elements_per_s": w.rows * w.n / (per_cold * 1e-3),
+        "gbps": gbps_cold,
+        "pct_hbm_peak": 100.0 * gbps_cold / HBM_PEAK_GBPS,
+        "warm": {"ms_per_step": per_warm, "rows_per_s": w.rows / (per_warm * 1e-3),
+                 "effective_gbps": gbps_warm},
+        "roofline": {
+            "bound": "hbm", "achieved": gbps_cold, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": gbps_cold / HBM_PEAK_GBPS, "traffic": traffic,
+            "algorithmic_bytes_per_launch": algo_bytes,
+        },
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,127 @@
+/*
+ * sparse_topk.h -- C ABI of the MI355X (gfx950) library for the p-norm-regularised, differentiable
+ * and sparse top-k operators of "Fast, Differentiable and Sparse Top-k: a Convex Analysis
+ * Perspective" (Sander, Puigcerver, Djolonga, Peyre, Blondel; ICML 2023).
+ *
+ * The operators (paper Sec. 4, "Differentiable and sparse top-k operators"), per row x in R^n:
+ *
+ *   relaxed top-k mask          y = grad_1 f_{phi,R}(x, 1_k)  with phi(x) = x
+ *   relaxed top-k in magnitude  y = grad_1 f_{phi,R}(x, 1_k)  with phi(x) = x^2 / 2
+ *
+ * where 1_k = (1,..,1,0,..,0) has k ones (Eq. (topk_mask)), R(y) = (lambda / p) * sum_i |y_i|^p,
+ * and by Prop. 2 (relaxed operator)  y = grad R*(x - u*),  u* = argmin_u R*(x - u) + f_phi(u, 1_k).
+ * u* is obtained exactly through the reduction to isotonic optimisation (Prop. 5 for phi = x,
+ * Prop. 6 for phi = x^2/2): sort x (or |x|) in descending order, solve
+ *     v* = argmin_{v_1 >= ... >= v_n} sum_i r*(s_i - v_i) + w_i phi(v_i)       (Eq. (isotonic_separable))
+ * and un-permute (times sign(x) for the magnitude operator).  The Jacobian-vector products use
+ * the closed form of Prop. 7 (differentiation).  Only p = 2 and p = 4/3 have closed-form pooling
+ * steps (Sec. 7, "Sensitivity to the choice of p") and only those are accepted.
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is a DEVICE pointer (HBM of the current HIP device), owned by the
+ *     caller, to a row-major contiguous [rows][n] array: float for values, int32_t for
+ *     permutations.  Outputs must not alias inputs or each other.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on that stream; they never synchronise with the host and never allocate.
+ *   - Sorting is descending; equal values keep ascending original index; -0.0f counts as +0.0f.
+ *   - Merges of the pool-adjacent-violators partition happen on strict violations only, so at a
+ *     kink of the p = 2 operator the derivative taken is the one of the un-merged side.
+ *   - 1 <= n < 2^30, 0 <= k <= n, lambda > 0 and finite, rows >= 0 (rows == 0 is a no-op).
+ *     k == 0 gives all zeros; k == n gives all ones (mask) or x / (1 + lambda) (magnitude, p = 2).
+ *   - NaN or infinite inputs are a precondition violation (the output is then unspecified, but
+ *     no out-of-bounds access happens).
+ *   - Return value: TOPK_OK, or a negative TOPK_ERR_* code, in which case nothing was enqueued.
+ *   - Rows with n > TOPK_SHORT_ROW_MAX are sorted through HBM and need caller-provided scratch
+ *     memory: query topk_workspace_bytes(), hand the buffer over with topk_set_workspace().
+ *     The workspace is process-global: calls that use it must not overlap in time (different
+ *     streams, or host threads) -- they would race on it.
+ */
+#ifndef SPARSE_TOPK_H_
+#define SPARSE_TOPK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  TOPK_OK = 0,
+  TOPK_ERR_INVALID = -1,        /* rows < 0, n < 1, n >= 2^30, k < 0, k > n, lambda <= 0 or non-finite */
+  TOPK_ERR_NULL = -2,           /* a required pointer is NULL */
+  TOPK_ERR_UNSUPPORTED_P = -3,  /* p is neither 2 nor 4/3, or the (operator, p) pair has no kernel */
+  TOPK_ERR_WORKSPACE = -4,      /* long rows and the registered workspace is missing or too small */
+  TOPK_ERR_LAUNCH = -5          /* the HIP runtime refused a launch (see hipGetLastError) */
+};
+
+/* Operator codes for topk_workspace_bytes(). */
+enum {
+  TOPK_OP_MASK_FWD = 0,
+  TOPK_OP_MASK_JVP = 1,
+  TOPK_OP_MAG_FWD = 2,
+  TOPK_OP_MAG_JVP = 3,
+  TOPK_OP_ARGSORT = 4
+};
+
+/* Rows up to this length are handled by one wavefront in registers (no workspace needed). */
+#define TOPK_SHORT_ROW_MAX 1024
+
+/*
+ * Relaxed top-k mask, forward (phi(x) = x; Prop. 2 + Prop. 5; pooling steps from Sec. 5
+ * "Example" for p = 2 and App. "Subproblem derivation" for p = 4/3).
+ *   theta [rows][n] in,  out [rows][n] out: values in [0, 1] summing to k per row, with exact
+ *   0.0f below the pooled block and exact 1.0f above it.
+ *   p: 2.0 or 4.0/3.0 (matched with a small tolerance).  lambda: regularisation strength.
+ */
+int topk_mask_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double p, double lambda,
+                  float* out, void* stream);
+
+/*
+ * Jacobian-vector product of the relaxed top-k mask (Prop. 7, differentiation), fused with the
+ * forward pass: jvp_out = (d y / d theta) . tangent.  `out` may be NULL (JVP only); when given it
+ * receives the same values as topk_mask_fwd.  The sort and the block are recomputed (the call is
+ * stateless).
+ */
+int topk_mask_jvp(const float* theta, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                  double p, double lambda, float* out, float* jvp_out, void* stream);
+
+/*
+ * Relaxed top-k in magnitude, forward (phi(x) = x^2/2; Prop. 2 + Prop. 6): sort |x|, solve on the
+ * non-negative monotone cone, restore the signs.  Pruned entries are +0.0f.  sign(0) = 0.
+ * Supported: p = 2 (pooling step of Sec. 5 "Example").  p = 4/3 returns TOPK_ERR_UNSUPPORTED_P.
+ */
+int topkmag_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p, double lambda,
+                float* out, void* stream);
+
+/* JVP of the relaxed top-k in magnitude (Prop. 7, case phi = x^2/2), fused with the forward pass;
+ * `out` may be NULL. */
+int topkmag_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                double p, double lambda, float* out, float* jvp_out, void* stream);
+
+/*
+ * The sorting permutation itself (Sec. 3, argsort): perm_out[r][i] = original index of the i-th
+ * largest value of row r (0-based).  This is the permutation the operators above use.
+ */
+int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm_out, void* stream);
+
+/*
+ * Scratch memory (bytes) that `op` (a TOPK_OP_* code) needs for this shape; 0 when rows fit one
+ * wavefront (n <= TOPK_SHORT_ROW_MAX).  Returns 0 for invalid arguments as well.
+ */
+size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p);
+
+/*
+ * Register caller-owned device scratch memory (256-byte aligned) for later calls; the library
+ * never frees it.  dev_ptr == NULL (with bytes == 0) unregisters.  Returns TOPK_OK or
+ * TOPK_ERR_INVALID (misaligned pointer, or NULL with bytes != 0).
+ */
+int topk_set_workspace(void* dev_ptr, size_t bytes);
+
+/* Static, human-readable text for a return code. */
+const char* topk_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_TOPK_H_ */

@@ -115,9 +115,10 @@ double cubic_root(const double* s, int64_t lo, int64_t hi, double lambda, double
     if (F > 0.0) b = g; else a = g;
     double gn = (D > 0.0) ? g - F / D : 0.5 * (a + b);
     if (!(gn > a && gn < b)) gn = 0.5 * (a + b);   // Newton left the bracket: bisect
-    if (gn == g || !(b - a > 0.0)) return gn;
-    if (std::fabs(gn - g) <= 1e-17 * std::max(1.0, std::fabs(g))) return gn;
+    bool done = (gn == g) || !(b - a > 0.0) ||
+                std::fabs(gn - g) <= 1e-17 * std::max(1.0, std::fabs(g));
     g = gn;
+    if (done) break;
   }
   return g;
 }
@@ -146,6 +147,25 @@ struct Block {
   double S, W, gamma;
 };
 
+// The strict test  gamma_prev < gamma_top  of the PAV loop.  For p = 2 the pooled values are closed
+// forms and are compared directly.  For p = 4/3 a pooled value is the root of a strictly increasing
+// cubic F (the derivative of the block's strictly convex objective), so
+//     gamma_prev < gamma_top  <=>  F_top(gamma_prev) < 0  <=>  F_prev(gamma_top) > 0,
+// and when one side is a singleton with a closed-form minimiser the test is made through the other
+// side's F at that exact value: an exact tie (F == 0) is then seen as a tie instead of being
+// decided by the last bit of a root finder.
+bool violates(const Problem& P, const double* s, const Block& prev, const Block& top) {
+  if (P.p == P_2) return prev.gamma < top.gamma;
+  const bool times_g = (P.phi == PHI_HALF_SQ);
+  const double l3 = P.lambda * P.lambda * P.lambda;
+  const bool prev_closed = (prev.hi - prev.lo == 1) && (!times_g || prev.W == 0.0);
+  const bool top_closed = (top.hi - top.lo == 1) && (!times_g || top.W == 0.0);
+  if (prev_closed && top_closed) return prev.gamma < top.gamma;   // two closed forms
+  if (prev_closed) return cubic_F(s, top.lo, top.hi, prev.gamma, l3 * top.W, times_g, nullptr) < 0.0;
+  if (top_closed) return cubic_F(s, prev.lo, prev.hi, top.gamma, l3 * prev.W, times_g, nullptr) > 0.0;
+  return prev.gamma < top.gamma;
+}
+
 void pav(const Problem& P, const double* s, const double* w, int64_t n, double* v,
          int64_t* blk_lo, int64_t* blk_hi) {
   std::vector<Block> st;
@@ -153,7 +173,7 @@ void pav(const Problem& P, const double* s, const double* w, int64_t n, double* 
   for (int64_t i = 0; i < n; ++i) {
     Block top{i, i + 1, s[i], w[i], 0.0};
     top.gamma = pool(P, s, top.lo, top.hi, top.S, top.W);
-    while (!st.empty() && st.back().gamma < top.gamma) {
+    while (!st.empty() && violates(P, s, st.back(), top)) {
       Block& prev = st.back();
       top.lo = prev.lo;
       top.S += prev.S;

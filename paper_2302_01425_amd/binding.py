@@ -1,0 +1,168 @@
+"""Thin ctypes binding over the C ABI of ``libsparse_topk.so`` (see ``include/sparse_topk.h``).
+
+Argument marshalling only: torch supplies device memory and the current stream, every step of the
+operators runs in the HIP kernels.  There is no fallback: if the library has not been built, or a
+tensor is not a contiguous float32 tensor on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
+
+TOPK_OP_MASK_FWD, TOPK_OP_MASK_JVP, TOPK_OP_MAG_FWD, TOPK_OP_MAG_JVP, TOPK_OP_ARGSORT = range(5)
+
+EXPORTS = (
+    "topk_mask_fwd", "topk_mask_jvp", "topkmag_fwd", "topkmag_jvp", "topk_argsort_desc",
+    "topk_workspace_bytes", "topk_set_workspace", "topk_strerror",
+)
+
+_lib = None
+
+
+class TopkError(RuntimeError):
+    pass
+
+
+def load() -> ctypes.CDLL:
+    """Load the shared library (built by ``paper_2302_01425_amd.build``); raise if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise TopkError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2302_01425_amd.build` "
+            "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, dbl, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_int
+    L.topk_mask_fwd.argtypes = [vp, i64, i64, i64, dbl, dbl, vp, vp]
+    L.topk_mask_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
+    L.topkmag_fwd.argtypes = [vp, i64, i64, i64, dbl, dbl, vp, vp]
+    L.topkmag_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
+    L.topk_argsort_desc.argtypes = [vp, i64, i64, vp, vp]
+    for name in ("topk_mask_fwd", "topk_mask_jvp", "topkmag_fwd", "topkmag_jvp",
+                 "topk_argsort_desc"):
+        getattr(L, name).restype = ci
+    L.topk_workspace_bytes.argtypes = [ci, i64, i64, i64, dbl]
+    L.topk_workspace_bytes.restype = ctypes.c_size_t
+    L.topk_set_workspace.argtypes = [vp, ctypes.c_size_t]
+    L.topk_set_workspace.restype = ci
+    L.topk_strerror.argtypes = [ci]
+    L.topk_strerror.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return load().topk_strerror(int(code)).decode()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise TopkError(f"{what}: {strerror(rc)} (code {rc})")
+
+
+def _dev_f32(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TopkError(f"{name} must be a tensor in GPU memory")
+    if t.dtype != torch.float32 or not t.is_contiguous() or t.dim() != 2:
+        raise TopkError(f"{name} must be a contiguous 2-D float32 tensor [rows, n]")
+    return t
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+_ws_tensor = None
+
+
+def workspace_bytes(op: int, rows: int, n: int, k: int, p: float) -> int:
+    return int(load().topk_workspace_bytes(int(op), int(rows), int(n), int(k), float(p)))
+
+
+def set_workspace(t: torch.Tensor | None) -> None:
+    """Register a caller-owned uint8 GPU tensor as scratch memory (None unregisters)."""
+    global _ws_tensor
+    if t is None:
+        _check(load().topk_set_workspace(None, 0), "topk_set_workspace")
+        _ws_tensor = None
+        return
+    _check(load().topk_set_workspace(ctypes.c_void_p(t.data_ptr()), t.numel() * t.element_size()),
+           "topk_set_workspace")
+    _ws_tensor = t
+
+
+def ensure_workspace(op: int, rows: int, n: int, k: int, p: float, device) -> None:
+    """Allocate (once, growing) and register scratch memory large enough for this call."""
+    need = workspace_bytes(op, rows, n, k, p)
+    if need == 0:
+        return
+    if _ws_tensor is None or _ws_tensor.numel() < need or _ws_tensor.device != torch.device(device):
+        set_workspace(torch.empty(need, dtype=torch.uint8, device=device))
+
+
+def topk_mask_fwd(theta, k, p, lam, out=None, stream=None):
+    theta = _dev_f32(theta, "theta")
+    rows, n = theta.shape
+    out = torch.empty_like(theta) if out is None else _dev_f32(out, "out")
+    ensure_workspace(TOPK_OP_MASK_FWD, rows, n, k, p, theta.device)
+    _check(load().topk_mask_fwd(theta.data_ptr(), rows, n, int(k), float(p), float(lam),
+                                out.data_ptr(), _stream(stream)), "topk_mask_fwd")
+    return out
+
+
+def topk_mask_jvp(theta, tangent, k, p, lam, out=None, jvp_out=None, want_out=True, stream=None):
+    """Returns (out, jvp_out); out is None when want_out is False and no out tensor was given."""
+    theta = _dev_f32(theta, "theta")
+    tangent = _dev_f32(tangent, "tangent")
+    rows, n = theta.shape
+    if out is None and want_out:
+        out = torch.empty_like(theta)
+    jvp_out = torch.empty_like(theta) if jvp_out is None else _dev_f32(jvp_out, "jvp_out")
+    ensure_workspace(TOPK_OP_MASK_JVP, rows, n, k, p, theta.device)
+    _check(load().topk_mask_jvp(theta.data_ptr(), tangent.data_ptr(), rows, n, int(k), float(p),
+                                float(lam), None if out is None else out.data_ptr(),
+                                jvp_out.data_ptr(), _stream(stream)), "topk_mask_jvp")
+    return out, jvp_out
+
+
+def topkmag_fwd(x, k, p, lam, out=None, stream=None):
+    x = _dev_f32(x, "x")
+    rows, n = x.shape
+    out = torch.empty_like(x) if out is None else _dev_f32(out, "out")
+    ensure_workspace(TOPK_OP_MAG_FWD, rows, n, k, p, x.device)
+    _check(load().topkmag_fwd(x.data_ptr(), rows, n, int(k), float(p), float(lam),
+                              out.data_ptr(), _stream(stream)), "topkmag_fwd")
+    return out
+
+
+def topkmag_jvp(x, tangent, k, p, lam, out=None, jvp_out=None, want_out=True, stream=None):
+    x = _dev_f32(x, "x")
+    tangent = _dev_f32(tangent, "tangent")
+    rows, n = x.shape
+    if out is None and want_out:
+        out = torch.empty_like(x)
+    jvp_out = torch.empty_like(x) if jvp_out is None else _dev_f32(jvp_out, "jvp_out")
+    ensure_workspace(TOPK_OP_MAG_JVP, rows, n, k, p, x.device)
+    _check(load().topkmag_jvp(x.data_ptr(), tangent.data_ptr(), rows, n, int(k), float(p),
+                              float(lam), None if out is None else out.data_ptr(),
+                              jvp_out.data_ptr(), _stream(stream)), "topkmag_jvp")
+    return out, jvp_out
+
+
+def topk_argsort_desc(theta, perm_out=None, stream=None):
+    theta = _dev_f32(theta, "theta")
+    rows, n = theta.shape
+    if perm_out is None:
+        perm_out = torch.empty((rows, n), dtype=torch.int32, device=theta.device)
+    ensure_workspace(TOPK_OP_ARGSORT, rows, n, 0, 2.0, theta.device)
+    _check(load().topk_argsort_desc(theta.data_ptr(), rows, n, perm_out.data_ptr(),
+                                    _stream(stream)), "topk_argsort_desc")
+    return perm_out

@@ -1,0 +1,197 @@
+// C ABI of the library: argument validation and dispatch.  See include/sparse_topk.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "../../include/sparse_topk.h"
+#include "launch.hpp"
+
+namespace {
+
+using topk::Reg;
+using topk::RowInfo;
+using topk::SortBuffers;
+
+struct Workspace {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+Workspace g_ws;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// 0: p = 2, 1: p = 4/3, -1: anything else
+int p_code(double p) {
+  if (std::fabs(p - 2.0) < 1e-9) return topk::kP2;
+  if (std::fabs(p - 4.0 / 3.0) < 1e-6) return topk::kP43;
+  return -1;
+}
+
+Reg make_reg(double lambda) {
+  Reg R;
+  R.lambda = lambda;
+  R.inv_lambda = 1.0 / lambda;
+  R.lam3 = lambda * lambda * lambda;
+  R.inv_lam3 = 1.0 / R.lam3;
+  R.one_p_lambda = 1.0 + lambda;
+  R.inv_1pl = 1.0 / (1.0 + lambda);
+  return R;
+}
+
+bool is_long(int64_t n) { return n > TOPK_SHORT_ROW_MAX; }
+
+struct Layout {
+  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, total;
+};
+
+Layout layout_for(int64_t rows, int64_t n) {
+  Layout L;
+  const size_t elems = size_t(rows) * size_t(n);
+  const size_t tiles = size_t(topk::radix_tiles(n));
+  size_t off = 0;
+  L.keys_a = off; off += align_up(elems * 4);
+  L.keys_b = off; off += align_up(elems * 4);
+  L.idx_a = off; off += align_up(elems * 4);
+  L.idx_b = off; off += align_up(elems * 4);
+  L.hist = off; off += align_up(size_t(rows) * 256 * tiles * 4);
+  L.dtot = off; off += align_up(size_t(rows) * 256 * 4);
+  L.info = off; off += align_up(size_t(rows) * sizeof(RowInfo));
+  L.total = off;
+  return L;
+}
+
+int carve(int64_t rows, int64_t n, SortBuffers* B) {
+  const Layout L = layout_for(rows, n);
+  if (g_ws.ptr == nullptr || g_ws.bytes < L.total) return TOPK_ERR_WORKSPACE;
+  char* base = static_cast<char*>(g_ws.ptr);
+  B->keys_a = reinterpret_cast<uint32_t*>(base + L.keys_a);
+  B->keys_b = reinterpret_cast<uint32_t*>(base + L.keys_b);
+  B->idx_a = reinterpret_cast<uint32_t*>(base + L.idx_a);
+  B->idx_b = reinterpret_cast<uint32_t*>(base + L.idx_b);
+  B->hist = reinterpret_cast<uint32_t*>(base + L.hist);
+  B->dtot = reinterpret_cast<uint32_t*>(base + L.dtot);
+  B->info = reinterpret_cast<RowInfo*>(base + L.info);
+  return TOPK_OK;
+}
+
+int check_shape(int64_t rows, int64_t n, int64_t k, double lambda) {
+  if (rows < 0 || n < 1 || n >= (int64_t(1) << 30) || k < 0 || k > n) return TOPK_ERR_INVALID;
+  if (!(lambda > 0.0) || !std::isfinite(lambda)) return TOPK_ERR_INVALID;
+  return TOPK_OK;
+}
+
+int finish() { return hipGetLastError() == hipSuccess ? TOPK_OK : TOPK_ERR_LAUNCH; }
+
+// shared body of the four operator entry points
+int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, int64_t n,
+                 int64_t k, double p, double lambda, float* out, float* jvp, bool need_out,
+                 bool need_jvp, void* stream) {
+  int rc = check_shape(rows, n, k, lambda);
+  if (rc != TOPK_OK) return rc;
+  const int pc = p_code(p);
+  if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
+  if (mag && pc != topk::kP2) return TOPK_ERR_UNSUPPORTED_P;
+  if (rows == 0) return TOPK_OK;          // nothing to do; pointers of empty arrays may be NULL
+  if (x == nullptr) return TOPK_ERR_NULL;
+  if (need_out && out == nullptr) return TOPK_ERR_NULL;
+  if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Reg R = make_reg(lambda);
+  if (!is_long(n)) {
+    if (topk::launch_short_rows(mag, pc, x, need_jvp ? tangent : nullptr, out,
+                                need_jvp ? jvp : nullptr, rows, int(n), int(k), R, st) != 0)
+      return TOPK_ERR_INVALID;
+    return finish();
+  }
+  SortBuffers B;
+  rc = carve(rows, n, &B);
+  if (rc != TOPK_OK) return rc;
+  if (topk::launch_segmented_sort(mag, x, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
+  if (topk::launch_long_tail(mag, pc, B, need_jvp ? tangent : nullptr, out,
+                             need_jvp ? jvp : nullptr, rows, n, k, R, st) != 0)
+    return TOPK_ERR_INVALID;
+  return finish();
+}
+
+}  // namespace
+
+extern "C" {
+
+int topk_mask_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double p, double lambda,
+                  float* out, void* stream) {
+  return run_operator(false, theta, nullptr, rows, n, k, p, lambda, out, nullptr, true, false,
+                      stream);
+}
+
+int topk_mask_jvp(const float* theta, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                  double p, double lambda, float* out, float* jvp_out, void* stream) {
+  return run_operator(false, theta, tangent, rows, n, k, p, lambda, out, jvp_out, false, true,
+                      stream);
+}
+
+int topkmag_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p, double lambda,
+                float* out, void* stream) {
+  return run_operator(true, x, nullptr, rows, n, k, p, lambda, out, nullptr, true, false, stream);
+}
+
+int topkmag_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                double p, double lambda, float* out, float* jvp_out, void* stream) {
+  return run_operator(true, x, tangent, rows, n, k, p, lambda, out, jvp_out, false, true, stream);
+}
+
+int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm_out,
+                      void* stream) {
+  if (rows < 0 || n < 1 || n >= (int64_t(1) << 30)) return TOPK_ERR_INVALID;
+  if (rows == 0) return TOPK_OK;
+  if (theta == nullptr || perm_out == nullptr) return TOPK_ERR_NULL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!is_long(n)) {
+    if (topk::launch_short_argsort(theta, perm_out, rows, int(n), st) != 0) return TOPK_ERR_INVALID;
+    return finish();
+  }
+  SortBuffers B;
+  int rc = carve(rows, n, &B);
+  if (rc != TOPK_OK) return rc;
+  if (topk::launch_segmented_sort(false, theta, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
+  if (hipMemcpyAsync(perm_out, B.idx_a, size_t(rows) * size_t(n) * 4, hipMemcpyDeviceToDevice,
+                     st) != hipSuccess)
+    return TOPK_ERR_LAUNCH;
+  return finish();
+}
+
+size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p) {
+  (void)k;
+  (void)p;
+  if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_ARGSORT) return 0;
+  if (rows <= 0 || n < 1 || n >= (int64_t(1) << 30)) return 0;
+  if (!is_long(n)) return 0;
+  return layout_for(rows, n).total;
+}
+
+int topk_set_workspace(void* dev_ptr, size_t bytes) {
+  if (dev_ptr == nullptr) {
+    if (bytes != 0) return TOPK_ERR_INVALID;
+    g_ws = Workspace{};
+    return TOPK_OK;
+  }
+  if (reinterpret_cast<uintptr_t>(dev_ptr) % kAlign != 0) return TOPK_ERR_INVALID;
+  g_ws.ptr = dev_ptr;
+  g_ws.bytes = bytes;
+  return TOPK_OK;
+}
+
+const char* topk_strerror(int code) {
+  switch (code) {
+    case TOPK_OK: return "ok";
+    case TOPK_ERR_INVALID: return "invalid argument (rows, n, k, lambda or alignment out of range)";
+    case TOPK_ERR_NULL: return "a required pointer is NULL";
+    case TOPK_ERR_UNSUPPORTED_P: return "unsupported p (only 2 and 4/3; magnitude operator only 2)";
+    case TOPK_ERR_WORKSPACE: return "workspace missing or too small (see topk_workspace_bytes)";
+    case TOPK_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

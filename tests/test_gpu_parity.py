@@ -1,0 +1,177 @@
+"""Parity of the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Bars (BASELINE the benchmark spec): the sorting permutation bit-exact; mask and JVP values within 1e-5
+absolute.  float32 cannot represent a value v more finely than 2^-24 |v|, so for outputs of large
+magnitude (the JVP scales like 1/lambda) the bar is 1e-5 + 1.2e-7 |v|, i.e. one float32 ulp.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+P2, P43 = 2.0, 4.0 / 3.0
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2302_01425_amd import binding
+    binding.load()
+    return binding
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def close(got, ref, what):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    tol = 1e-5 + 1.2e-7 * np.abs(ref)
+    err = np.abs(got - ref)
+    bad = err > tol
+    assert not bad.any(), (what, int(bad.sum()), float(err.max()),
+                           np.argwhere(bad)[:5].tolist(), got[bad][:5], ref[bad][:5])
+
+
+def run_case(gpu, oracle, op, x, t, k, p, lam, check_perm=True):
+    print(f"case op={op} shape={x.shape} k={k} p={p:.4f} lam={lam}", flush=True)
+    ofn = oracle.topk_mask if op == "mask" else oracle.topkmag
+    ref = ofn(x, k, p, lam, tangent=t, want_perm=True)
+    xd, td = dev(x), dev(t)
+    fwd = gpu.topk_mask_fwd if op == "mask" else gpu.topkmag_fwd
+    jvpf = gpu.topk_mask_jvp if op == "mask" else gpu.topkmag_jvp
+    out1 = host(fwd(xd, k, p, lam))
+    out2, jv = jvpf(xd, td, k, p, lam)
+    out2, jv = host(out2), host(jv)
+    _, jv_only = jvpf(xd, td, k, p, lam, want_out=False)
+    jv_only = host(jv_only)
+    close(out1, ref["out"], "fwd")
+    assert np.array_equal(out1, out2), "fused forward differs from forward"
+    assert np.array_equal(jv, jv_only), "JVP-only differs from fused JVP"
+    close(jv, ref["jvp"], "jvp")
+    # sparsity: exact zeros where the oracle has exact zeros
+    assert np.all(out1[ref["out"] == 0.0] == 0.0)
+    if check_perm:
+        z = np.abs(x) if op == "mag" else x
+        perm = host(gpu.topk_argsort_desc(dev(z)))
+        assert np.array_equal(perm, ref["perm"]), "sorting permutation differs"
+    return out1, jv
+
+
+# ---- the five workloads at full size ---------------------------------------------------------
+@pytest.mark.parametrize("name", ["tiny", "moe_router", "moe_router_smooth", "expert_choice",
+                                  "magnitude_pruning"])
+def test_workload_parity(gpu, oracle, name):
+    from paper_2302_01425_amd.workloads import WORKLOADS
+    w = WORKLOADS[name]
+    x, t = w.inputs()
+    out, jv = run_case(gpu, oracle, w.op, x, t, w.k, w.p, w.lam)
+    if w.op == "mask":
+        assert np.abs(out.astype(np.float64).sum(axis=1) - w.k).max() < 1e-3 * max(1, w.k / 100)
+
+
+# ---- short rows: every lane-group shape, ragged lengths, ties, both p ----------------------------
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 8, 16, 17, 31, 33, 64, 65, 100, 128, 129, 200, 256, 300,
+                               512, 777, 1024])
+def test_short_rows(gpu, oracle, n):
+    r = np.random.default_rng(1000 + n)
+    for rows in (1, 7, 133):
+        for p in (P2, P43):
+            x = r.normal(size=(rows, n)).astype(np.float32)
+            if n >= 4:
+                x[:, 1] = x[:, 0]                       # ties
+                x[rows // 2, :] = np.round(x[rows // 2, :])   # a row of many ties
+            t = r.normal(size=(rows, n)).astype(np.float32)
+            for k in sorted({0, 1, max(1, n // 10), n // 2, n - 1, n} & set(range(n + 1))):
+                lam = float(r.choice([0.05, 0.5, 2.0]))
+                run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=(k == 1))
+        x = (r.laplace(size=(rows, n)) * 0.1).astype(np.float32)
+        x[0, 0] = 0.0
+        if n >= 3:
+            x[0, 2] = -x[0, 1]
+        t = r.normal(size=(rows, n)).astype(np.float32)
+        for k in sorted({0, 1, n // 3, n} & set(range(n + 1))):
+            run_case(gpu, oracle, "mag", x, t, k, P2, float(r.choice([1e-3, 0.1, 1.0])),
+                     check_perm=(k == 1))
+
+
+# ---- long rows: several tiles, ragged tails, several rows -----------------------------------------
+@pytest.mark.parametrize("rows,n", [(1, 1025), (3, 3000), (2, 4096), (2, 4097), (5, 10000),
+                                    (1, 70001), (130, 2048)])
+def test_long_rows(gpu, oracle, rows, n):
+    r = np.random.default_rng(7 * n + rows)
+    x = r.normal(size=(rows, n)).astype(np.float32)
+    x[:, 5] = x[:, 4]
+    x[-1, :] = np.round(x[-1, :] * 4) / 4                 # heavy ties in the last row
+    t = r.normal(size=(rows, n)).astype(np.float32)
+    for p in (P2, P43):
+        for k in (1, n // 10, n // 2, n - 1):
+            lam = float(r.choice([0.01, 0.1, 1.0]))
+            run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=(k == 1 and p == P2))
+    for k in (0, n // 10, n):
+        run_case(gpu, oracle, "mag", x * np.float32(0.02), t, k, P2, float(r.choice([1e-3, 0.05])),
+                 check_perm=(k == 0))
+    # large lambda: the block spans most of the row (many sweep chunks)
+    run_case(gpu, oracle, "mask", x, t, n // 3, P2, 50.0, check_perm=False)
+    run_case(gpu, oracle, "mask", x, t, n // 3, P43, 50.0, check_perm=False)
+
+
+# ---- paper examples through the GPU path ----------------------------------------------------------
+def test_fig1_points(gpu, oracle):
+    for lam in (0.25, 1.0):
+        for s in (-1.0, 0.0, 1 - lam, 0.9, 1.0, 1.1, 1 + lam, 2.0):
+            th = np.array([[3.0, 1.0, -1.0 + s, s]], dtype=np.float32)
+            t = np.array([[0.5, -1.0, 2.0, 1.0]], dtype=np.float32)
+            for p in (P2, P43):
+                run_case(gpu, oracle, "mask", th, t, 2, p, lam)
+
+
+def test_strict_merge_kinks(gpu, oracle):
+    cases = [([2.0, 2.0, 0.0, -1.0], 2, 0.5), ([3.0, 1.5, 1.0, 0.0], 2, 0.5),
+             ([3.0, 1.0, 0.75, 0.625], 2, 0.5), ([1.0, 1.0, 1.0, 1.0], 2, 1.0),
+             ([0.0, 0.0, 0.0], 1, 0.25),
+             # p = 4/3 tie: eight ones pool at exactly 0 = 2 - lambda, so the 2 stays outside
+             ([2.0] + [1.0] * 8 + [-5.0], 2, 2.0)]
+    for th, k, lam in cases:
+        th = np.array([th], dtype=np.float32)
+        t = np.arange(1, th.shape[1] + 1, dtype=np.float32)[None, :] * np.float32(0.5)
+        for p in (P2, P43):
+            run_case(gpu, oracle, "mask", th, t, k, p, lam)
+        run_case(gpu, oracle, "mag", th, t, k, P2, lam)
+
+
+def test_determinism_and_streams(gpu):
+    import torch
+    from paper_2302_01425_amd.workloads import WORKLOADS
+    w = WORKLOADS["moe_router"]
+    x, t = w.inputs()
+    xd, td = dev(x), dev(t)
+    o1, j1 = gpu.topk_mask_jvp(xd, td, w.k, w.p, w.lam)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        o2, j2 = gpu.topk_mask_jvp(xd, td, w.k, w.p, w.lam, stream=st)
+    st.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(j1, j2)
+
+
+def test_rows_zero_and_errors(gpu):
+    import torch
+    x = torch.zeros((0, 8), device="cuda")
+    assert gpu.topk_mask_fwd(x, 2, P2, 1.0).shape == (0, 8)
+    y = torch.zeros((2, 8), device="cuda")
+    with pytest.raises(gpu.TopkError):
+        gpu.topk_mask_fwd(y, 9, P2, 1.0)
+    with pytest.raises(gpu.TopkError):
+        gpu.topk_mask_fwd(y, 2, 1.7, 1.0)
+    with pytest.raises(gpu.TopkError):
+        gpu.topkmag_fwd(y, 2, P43, 1.0)

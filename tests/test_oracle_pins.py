@@ -415,6 +415,21 @@ def test_strict_merge_convention(oracle):
     assert np.allclose(res["jvp"], [0.0, -1.0, 1.0, 0.0], atol=1e-15)
 
 
+def test_strict_merge_convention_p43(oracle):
+    # p = 4/3, lambda = 2: eight equal values s = 1 carrying one unit of weight pool at
+    # gamma = s - lambda (1/8)^(1/3) = 0 exactly (each gets ((1-0)/2)^3 = 1/8, summing to 1).
+    # The entry 2 above them has singleton minimiser 2 - lambda = 0 == gamma: a tie, not merged,
+    # so it stays at exactly one and its JVP row is zero.
+    th = np.array([2.0] + [1.0] * 8 + [-5.0], dtype=np.float32)
+    t = np.arange(1, 11, dtype=np.float32)
+    res = oracle.topk_mask(th, 2, P43, 2.0, tangent=t, want_block=True)
+    assert res["block"].tolist() == [1, 9]
+    assert np.allclose(res["out"], [1.0] + [0.125] * 8 + [0.0], atol=1e-15)
+    assert res["jvp"][0] == 0.0 and res["jvp"][9] == 0.0
+    # inside the block: dy_i = 3 (s_i - gamma)^2 / lambda^3 (t_i - mean t) = (3/8)(t_i - 5.5)
+    assert np.allclose(res["jvp"][1:9], 0.375 * (t[1:9] - 5.5), atol=1e-13)
+
+
 def test_edge_cases(oracle):
     th = np.array([0.3, -1.0, 2.0], dtype=np.float32)
     t = np.ones(3, np.float32)
