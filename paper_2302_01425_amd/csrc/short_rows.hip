@@ -1,11 +1,20 @@
 // Short rows (n <= 1024): one row per group of GL lanes of a wavefront, E elements per lane,
-// everything after the load kept in registers.
+// 64/GL rows per wavefront; everything between the load and the store stays in registers, plus
+// one small per-wavefront LDS buffer for the un-sort scatter and the tangent gather.
 //
-//   load -> (key, index) bitonic sort -> float64 windowed prefix sums -> block growth
-//        -> pooled value -> y in sorted order -> un-sort scatter (+ JVP of Prop. 7)
+//   load -> pack (key, index) into one float64 -> bitonic network (v_min/v_max_f64 in a lane,
+//   DPP exchanges across lanes) -> float64 windowed prefix sums -> block growth -> pooled value
+//   -> y and dy in sorted order -> scatter through LDS -> coalesced store
 //
-// Layout: lane l of a row group holds the elements l*E .. l*E+E-1 of the row (so a lane's loads
-// are contiguous) and, after the sort, the sorted positions l*E .. l*E+E-1.
+// Layout: lane l of a row group holds elements l*E .. l*E+E-1 of its row (a contiguous,
+// vectorisable load) and, after the sort, the sorted positions l*E .. l*E+E-1.
+//
+// The composite sort key is (descending-order key : 32 bits | index field) stored as the integer
+// part of a float64 in [2^52, 2^53): all such doubles are positive normals whose order is the
+// order of the integers, so v_min_f64 / v_max_f64 are exact compare-exchanges and ties in the
+// value fall back to the index (ascending), which is the tie rule of the library.
+#include <cstdlib>
+
 #include "common.hpp"
 #include "pooling.hpp"
 #include "launch.hpp"
@@ -13,386 +22,596 @@
 namespace topk {
 namespace {
 
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask, int width) {
-  uint32_t lo = uint32_t(v), hi = uint32_t(v >> 32);
-  lo = __shfl_xor(lo, mask, width);
-  hi = __shfl_xor(hi, mask, width);
-  return (uint64_t(hi) << 32) | lo;
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+constexpr int top_bit(int v) { return 1 << ilog2(v); }
+
+// ---- cross-lane exchanges -------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
+  return uint32_t(__builtin_amdgcn_mov_dpp(int(v), CTRL, 0xF, 0xF, true));
 }
 
-// Bitonic sorting network over the GL*E composites of one row, ascending.
-// Strides below E are compare-exchanges between registers of one lane; strides of E and above
-// are exchanges with the lane at distance stride/E.
-template <int GL, int E>
-__device__ __forceinline__ void bitonic_sort(uint64_t (&K)[E], int lr) {
-  constexpr int NP = GL * E;
+// value of lane (l ^ LM).  LM is one of the masks a bitonic network on <= 64 lanes needs:
+// strides 1,2,4,8,16,32 and mirrors 3,7,15,31,63.  Within a row of 16 lanes these are DPP moves.
+template <int LM>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
+  if constexpr (LM == 1) return dpp_mov<0xB1>(v);            // quad_perm [1,0,3,2]
+  else if constexpr (LM == 2) return dpp_mov<0x4E>(v);       // quad_perm [2,3,0,1]
+  else if constexpr (LM == 3) return dpp_mov<0x1B>(v);       // quad_perm [3,2,1,0]
+  else if constexpr (LM == 7) return dpp_mov<0x141>(v);      // row_half_mirror
+  else if constexpr (LM == 15) return dpp_mov<0x140>(v);     // row_mirror
+  else if constexpr (LM == 8) return dpp_mov<0x128>(v);      // row_ror:8
+  else if constexpr (LM == 4) {
+    // banks 0 and 2 (lanes 0-3, 8-11) read lane+4, banks 1 and 3 read lane-4
+    int t = __builtin_amdgcn_update_dpp(int(v), int(v), 0x104, 0xF, 0x5, false);   // row_shl:4
+    t = __builtin_amdgcn_update_dpp(t, int(v), 0x114, 0xF, 0xA, false);            // row_shr:4
+    return uint32_t(t);
+  } else if constexpr (LM == 16) {
+    return uint32_t(__builtin_amdgcn_ds_swizzle(int(v), (16 << 10) | 0x1F));       // swap rows
+  } else if constexpr (LM == 31) {
+    return lane_xor<16>(lane_xor<15>(v));
+  } else if constexpr (LM == 32) {
+    return uint32_t(__shfl_xor(int(v), 32, kWave));
+  } else {
+    static_assert(LM == 63, "unsupported lane mask");
+    return lane_xor<32>(lane_xor<31>(v));
+  }
+}
+
+template <int LM>
+__device__ __forceinline__ double lane_xor_f64(double v) {
+  const uint32_t lo = lane_xor<LM>(uint32_t(__double2loint(v)));
+  const uint32_t hi = lane_xor<LM>(uint32_t(__double2hiint(v)));
+  return __hiloint2double(int(hi), int(lo));
+}
+
+// plain machine min / max: the operands are never NaN, so no canonicalisation is wanted
+__device__ __forceinline__ double min_f64(double a, double b) {
+  double r;
+  asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ double max_f64(double a, double b) {
+  double r;
+  asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+// ---- the sorting network ---------------------------------------------------------------------
+// One stage: every position p is compared with p ^ M; the lower position keeps the minimum.
+// p = lane*E + r, so M splits into a register mask (M mod E) and a lane mask (M / E).
+template <int GL, int E, int M>
+__device__ __forceinline__ void sort_stage(double (&K)[E], int lr) {
+  constexpr int RM = M & (E - 1);
+  constexpr int LM = M / E;
+  if constexpr (LM == 0) {
 #pragma unroll
-  for (int size = 2; size <= NP; size <<= 1) {
-#pragma unroll
-    for (int stride = size >> 1; stride >= 1; stride >>= 1) {
-      if (stride < E) {
-#pragma unroll
-        for (int r = 0; r < E; ++r) {
-          if ((r & stride) == 0) {
-            const bool up = (((lr * E + r) & size) == 0);
-            uint64_t lo = K[r], hi = K[r | stride];
-            const bool sw = (lo > hi) == up;
-            K[r] = sw ? hi : lo;
-            K[r | stride] = sw ? lo : hi;
-          }
-        }
-      } else {
-        const int ls = stride / E;
-        const bool low = (lr & ls) == 0;
-#pragma unroll
-        for (int r = 0; r < E; ++r) {
-          const bool up = (((lr * E + r) & size) == 0);
-          const uint64_t o = shfl_xor_u64(K[r], ls, GL);
-          const bool keep_min = (low == up);
-          const bool o_lt = o < K[r];
-          K[r] = (keep_min == o_lt) ? o : K[r];
-        }
+    for (int r = 0; r < E; ++r) {
+      const int r2 = r ^ RM;
+      if (r < r2) {
+        const double lo = min_f64(K[r], K[r2]);
+        const double hi = max_f64(K[r], K[r2]);
+        K[r] = lo;
+        K[r2] = hi;
       }
+    }
+  } else {
+    const bool low = (lr & top_bit(LM)) == 0;
+    double O[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) O[r] = lane_xor_f64<LM>(K[r ^ RM]);
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const bool o_lt = O[r] < K[r];
+      K[r] = (o_lt == low) ? O[r] : K[r];
     }
   }
 }
 
-// value of per-lane array v[] at sorted position pos0 (0-based) of this lane's row
+template <int GL, int E, int STRIDE>
+struct HalfCleaners {
+  static __device__ __forceinline__ void run(double (&K)[E], int lr) {
+    sort_stage<GL, E, STRIDE>(K, lr);
+    HalfCleaners<GL, E, STRIDE / 2>::run(K, lr);
+  }
+};
+template <int GL, int E>
+struct HalfCleaners<GL, E, 0> {
+  static __device__ __forceinline__ void run(double (&)[E], int) {}
+};
+
+// Bitonic merge sort in its "mirror" form: merging two sorted runs of SIZE/2 starts with the
+// comparison p <-> p ^ (SIZE-1), then half-cleaners of stride SIZE/4 .. 1; every compare-exchange
+// is ascending.
+template <int GL, int E, int SIZE>
+struct SortRuns {
+  static __device__ __forceinline__ void run(double (&K)[E], int lr) {
+    SortRuns<GL, E, SIZE / 2>::run(K, lr);
+    sort_stage<GL, E, SIZE - 1>(K, lr);
+    HalfCleaners<GL, E, SIZE / 4>::run(K, lr);
+  }
+};
+template <int GL, int E>
+struct SortRuns<GL, E, 1> {
+  static __device__ __forceinline__ void run(double (&)[E], int) {}
+};
+
+// ---- row-group collectives --------------------------------------------------------------------
+template <int GL, class T>
+__device__ __forceinline__ T bcast_lane(T v, int src) {
+  if constexpr (GL == 1) return v;
+  else return __shfl(v, src, GL);
+}
+
+// value of the per-lane array v[] at sorted position pos0 (0-based) of this lane's row
 template <int GL, int E, class T>
 __device__ __forceinline__ T at_pos(const T (&v)[E], int pos0) {
   const int r = pos0 & (E - 1);
   T sel = v[0];
 #pragma unroll
   for (int q = 1; q < E; ++q) sel = (r == q) ? v[q] : sel;
-  return group_bcast<GL>(sel, pos0 / E);
+  return bcast_lane<GL>(sel, pos0 / E);
 }
 
-// Load one row into composites.  Index field: original index (mask) or 2*index + signbit (mag).
-template <int GL, int E, bool MAG>
-__device__ __forceinline__ void load_row(const float* __restrict__ x, int64_t base, int n, int lr,
-                                         uint64_t (&K)[E]) {
-#pragma unroll
-  for (int r = 0; r < E; ++r) {
-    const int e = lr * E + r;
-    uint32_t key = kSentinelKey, idx = 0xffffffffu;
-    if (e < n) {
-      float v = x[base + e];
-      if (MAG) {
-        idx = (uint32_t(e) << 1) | (__float_as_uint(v) >> 31);
-        v = fabsf(v);
-      } else {
-        idx = uint32_t(e);
-      }
-      key = desc_key(v);
-    }
-    K[r] = (uint64_t(key) << 32) | idx;
+template <int GL, int LM>
+struct XorSum {
+  static __device__ __forceinline__ double f64(double v) {
+    v = XorSum<GL, LM / 2>::f64(v);
+    return v + lane_xor_f64<LM>(v);
+  }
+  static __device__ __forceinline__ uint32_t u32(uint32_t v) {
+    v = XorSum<GL, LM / 2>::u32(v);
+    return v + lane_xor<LM>(v);
+  }
+};
+template <int GL>
+struct XorSum<GL, 0> {
+  static __device__ __forceinline__ double f64(double v) { return v; }
+  static __device__ __forceinline__ uint32_t u32(uint32_t v) { return v; }
+};
+// sums over the GL lanes of the row group, result in every lane
+template <int GL>
+__device__ __forceinline__ double group_sum_f64(double v) { return XorSum<GL, GL / 2>::f64(v); }
+template <int GL>
+__device__ __forceinline__ uint32_t group_sum_u32(uint32_t v) { return XorSum<GL, GL / 2>::u32(v); }
+
+// value of lane l - OFF of the same DPP row (0 when that lane does not exist)
+template <int OFF>
+__device__ __forceinline__ double row_shr_f64(double v) {
+  const uint32_t lo = dpp_mov<0x110 + OFF>(uint32_t(__double2loint(v)));
+  const uint32_t hi = dpp_mov<0x110 + OFF>(uint32_t(__double2hiint(v)));
+  return __hiloint2double(int(hi), int(lo));
+}
+
+template <int GL, int OFF>
+struct ScanSteps {
+  static __device__ __forceinline__ double run(double inc, int lr) {
+    inc = ScanSteps<GL, OFF / 2>::run(inc, lr);
+    double o;
+    if constexpr (GL <= 16) o = row_shr_f64<OFF>(inc);   // the group lies inside one DPP row
+    else o = __shfl_up(inc, OFF, GL);
+    return (lr >= OFF) ? inc + o : inc;
+  }
+};
+template <int GL>
+struct ScanSteps<GL, 0> {
+  static __device__ __forceinline__ double run(double inc, int) { return inc; }
+};
+// exclusive prefix (over the lanes of the row group) of one value per lane
+template <int GL>
+__device__ __forceinline__ double group_exclusive_scan_f64(double tot, int lr) {
+  if constexpr (GL == 1) return 0.0;
+  else {
+    const double inc = ScanSteps<GL, GL / 2>::run(tot, lr);
+    double prev;
+    if constexpr (GL <= 16) prev = row_shr_f64<1>(inc);
+    else prev = __shfl_up(inc, 1, GL);
+    return lr == 0 ? 0.0 : prev;
   }
 }
 
-template <int GL, int E>
+// ---- packing -----------------------------------------------------------------------------------
+template <int IDXB>
+__device__ __forceinline__ double pack(uint32_t key, uint32_t field) {
+  const uint32_t lo = (key << IDXB) | field;
+  const uint32_t hi = 0x43300000u | (key >> (32 - IDXB));
+  return __hiloint2double(int(hi), int(lo));
+}
+template <int IDXB>
+__device__ __forceinline__ void unpack(double c, uint32_t& key, uint32_t& field) {
+  const uint32_t lo = uint32_t(__double2loint(c)), hi = uint32_t(__double2hiint(c));
+  key = (hi << (32 - IDXB)) | (lo >> IDXB);
+  field = lo & ((1u << IDXB) - 1u);
+}
+
+template <int E, bool MAG, int IDXB>
+__device__ __forceinline__ void make_keys(const float (&v)[E], int e0, int n, double (&K)[E]) {
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int e = e0 + r;
+    uint32_t key = kSentinelKey, field = (1u << IDXB) - 1u;
+    if (e < n) {
+      if (MAG) {
+        field = (uint32_t(e) << 1) | (__float_as_uint(v[r]) >> 31);
+        key = desc_key(fabsf(v[r]));
+      } else {
+        field = uint32_t(e);
+        key = desc_key(v[r]);
+      }
+    }
+    K[r] = pack<IDXB>(key, field);
+  }
+}
+
+// E consecutive floats of a row starting at element e0; VEC: rows are 16-byte aligned and n % 4 == 0
+template <int E, bool VEC>
+__device__ __forceinline__ void load_elems(const float* __restrict__ p, int64_t base, int e0, int n,
+                                           float (&v)[E]) {
+  if constexpr (VEC) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c) {
+      float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (e0 + 4 * c < n) q = *reinterpret_cast<const float4*>(p + base + e0 + 4 * c);
+      v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < E; ++r) v[r] = (e0 + r < n) ? p[base + e0 + r] : 0.0f;
+  }
+}
+
+template <int E, bool VEC>
+__device__ __forceinline__ void store_elems(float* __restrict__ p, int64_t base, int e0, int n,
+                                            const float (&v)[E]) {
+  if constexpr (VEC) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c)
+      if (e0 + 4 * c < n)
+        *reinterpret_cast<float4*>(p + base + e0 + 4 * c) =
+            make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < E; ++r)
+      if (e0 + r < n) p[base + e0 + r] = v[r];
+  }
+}
+
+// E consecutive floats to / from LDS (16-byte aligned when E >= 4)
+template <int E>
+__device__ __forceinline__ void lds_store(float* p, const float (&v)[E]) {
+  if constexpr (E % 4 == 0) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c)
+      *reinterpret_cast<float4*>(p + 4 * c) = make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < E; ++r) p[r] = v[r];
+  }
+}
+template <int E>
+__device__ __forceinline__ void lds_load(const float* p, float (&v)[E]) {
+  if constexpr (E % 4 == 0) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c) {
+      const float4 q = *reinterpret_cast<const float4*>(p + 4 * c);
+      v[4 * c] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < E; ++r) v[r] = p[r];
+  }
+}
+
+// ---- argsort only ------------------------------------------------------------------------------
+template <int GL, int E, bool VEC>
 __global__ __launch_bounds__(256) void short_argsort_kernel(const float* __restrict__ x,
                                                             int32_t* __restrict__ perm,
                                                             int64_t rows, int n) {
-  constexpr int RPW = kWave / GL;
+  constexpr int NP = GL * E, RPW = kWave / GL, IDXB = ilog2(NP) + 1;
   const int lr = lane_in_group<GL>();
   const int64_t wave = int64_t(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
   int64_t row = wave * RPW + ((threadIdx.x & (kWave - 1)) / GL);
   const bool valid = row < rows;
   if (!valid) row = rows - 1;
-  uint64_t K[E];
-  load_row<GL, E, false>(x, row * n, n, lr, K);
-  bitonic_sort<GL, E>(K, lr);
+  float v[E];
+  load_elems<E, VEC>(x, row * n, lr * E, n, v);
+  double K[E];
+  make_keys<E, false, IDXB>(v, lr * E, n, K);
+  SortRuns<GL, E, NP>::run(K, lr);
   if (!valid) return;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const int pos = lr * E + r;
-    if (pos < n) perm[row * n + pos] = int32_t(uint32_t(K[r]));
+    uint32_t key, field;
+    unpack<IDXB>(K[r], key, field);
+    if (pos < n) perm[row * n + pos] = int32_t(field);
   }
 }
 
-template <int GL, int E, bool MAG, int PC>
-__global__ __launch_bounds__(256) void short_rows_kernel(const float* __restrict__ x,
-                                                         const float* __restrict__ tangent,
-                                                         float* __restrict__ out,
-                                                         float* __restrict__ jvp, int64_t rows,
-                                                         int n, int k, Reg R) {
-  using P = Pool<MAG, PC>;
-  constexpr int RPW = kWave / GL;
-  constexpr bool CUBIC = (PC == kP43);
-  const int lr = lane_in_group<GL>();
-  const int64_t wave = int64_t(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
-  int64_t row = wave * RPW + ((threadIdx.x & (kWave - 1)) / GL);
-  const bool valid = row < rows;
-  if (!valid) row = rows - 1;            // keep the lanes alive for the shuffles; no stores
-  const int64_t base = row * n;
+// ---- the fused operator -------------------------------------------------------------------------
+// LDS per wavefront: three arrays of 64/GL rows, each row NP floats plus 4 floats of padding (so
+// that the same position of different rows falls into different banks):
+//   ls : the sorted values (read by the block growth, one broadcast read per row and step)
+//   lt : the tangent in original order (gathered through sigma), later dy in original order
+//   ly : y in original order
+template <int GL, int E>
+struct ShortCfg {
+  static constexpr int NP = GL * E;
+  static constexpr int RPW = kWave / GL;
+  static constexpr int RS = NP + 4;                       // row stride in floats
+  static constexpr int WaveFloats = 3 * RPW * RS;
+  static constexpr int WPB = (WaveFloats * 4 * 4 <= 64 * 1024) ? 4 : 1;   // wavefronts per block
+  static constexpr int IDXB = ilog2(NP) + 1;              // index (+ sign bit for magnitude)
+};
 
-  // ---- load + sort -------------------------------------------------------------------------
-  uint64_t K[E];
-  load_row<GL, E, MAG>(x, base, n, lr, K);
-  bitonic_sort<GL, E>(K, lr);
+template <int GL, int E, bool MAG, int PC, bool VEC>
+__global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_kernel(
+    const float* __restrict__ x, const float* __restrict__ tangent, float* __restrict__ out,
+    float* __restrict__ jvp, int64_t rows, int n, int k, Reg R) {
+  using P = Pool<MAG, PC>;
+  using C = ShortCfg<GL, E>;
+  constexpr int NP = C::NP, RPW = C::RPW, RS = C::RS, IDXB = C::IDXB;
+  constexpr bool CUBIC = (PC == kP43);
+  __shared__ __attribute__((aligned(16))) float lds[C::WPB][3][RPW * RS];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int lr = lane_in_group<GL>();
+  const int wv = threadIdx.x / kWave;
+  const int64_t wave = int64_t(blockIdx.x) * C::WPB + wv;
+  int64_t row = wave * RPW + lane / GL;
+  const bool valid = row < rows;
+  if (!valid) row = rows - 1;            // keep the lanes alive for the exchanges; no stores
+  const int64_t base = row * n;
+  const int e0 = lr * E;
+  float* ls = &lds[wv][0][(lane / GL) * RS];
+  float* lt = &lds[wv][1][(lane / GL) * RS];
+  float* ly = &lds[wv][2][(lane / GL) * RS];
+
+  // ---- load, sort ----------------------------------------------------------------------------
+  float xin[E];
+  load_elems<E, VEC>(x, base, e0, n, xin);
+  if (jvp != nullptr) {
+    float tin[E];
+    load_elems<E, VEC>(tangent, base, e0, n, tin);
+    lds_store<E>(lt + e0, tin);
+  }
+  double K[E];
+  make_keys<E, MAG, IDXB>(xin, e0, n, K);
+  SortRuns<GL, E, NP>::run(K, lr);
 
   float s32[E];
-  uint32_t idx[E];
+  uint32_t field[E];
 #pragma unroll
   for (int r = 0; r < E; ++r) {
-    s32[r] = key_to_float(uint32_t(K[r] >> 32));
-    idx[r] = uint32_t(K[r]);
+    uint32_t key;
+    unpack<IDXB>(K[r], key, field[r]);
+    s32[r] = key_to_float(key);
   }
+  lds_store<E>(ls + e0, s32);
+  __builtin_amdgcn_wave_barrier();
 
-  // ---- window of positions that can pool, centred values ------------------------------------
-  // mask: values relative to s_k (shift invariance); magnitude: the values themselves.
-  double d[E];
-  bool cand[E];
+  // ---- isotonic solve: grow the one pooled block outwards from (k, k+1) ----------------------
+  // All lanes of a row carry the same (a, b, sums).  A step tests the two neighbours of the block
+  // with the strict violation tests of the PAV loop and takes in whichever violates; both may
+  // join in one step (the right one raises the pooled value, the left one lowers it, so each
+  // still violates after the other has joined).  Values are centred on s_k for the mask.
   int a = k + 1, b = k;                  // 1-based inclusive block [a, b]; empty when a > b
-  bool grow = false;
-  double center = 0.0;
-  if (k >= 1 && k < n) {
-    const double sk = double(at_pos<GL, E>(s32, k - 1));
-    const double sk1 = double(at_pos<GL, E>(s32, k));
+  double center = 0.0, gamma = 0.0;
+  if (k >= 1 && k < n) {                 // uniform
+    const double sk = double(ls[k - 1]), sk1 = double(ls[k]);
     if (!MAG) center = sk;
-    const double ck = sk - center, ck1 = sk1 - center;
-    grow = P::seed_violates(ck, ck1, R);
-#pragma unroll
-    for (int r = 0; r < E; ++r) {
-      const int pos1 = lr * E + r + 1;
-      const double v = double(s32[r]) - center;
-      cand[r] = grow && (pos1 <= n) && (pos1 <= k ? P::left_candidate(v, ck1, R)
-                                                    : P::right_candidate(v, ck, R));
-      d[r] = cand[r] ? v : 0.0;
-    }
-    if (grow) { a = k; b = k + 1; }
-  } else {
-#pragma unroll
-    for (int r = 0; r < E; ++r) { d[r] = 0.0; cand[r] = false; }
-  }
-
-  double gamma = 0.0;                    // pooled value (centred for the mask)
-  if (__any(grow)) {
-    // ---- exclusive prefix sums of d, d^2, d^3 over the sorted positions --------------------
-    double X1[E], X2[E], X3[E];
-    {
-      double t1 = 0.0, t2 = 0.0, t3 = 0.0;
-#pragma unroll
-      for (int r = 0; r < E; ++r) {
-        X1[r] = t1; t1 += d[r];
-        if (CUBIC) {
-          X2[r] = t2; t2 += d[r] * d[r];
-          X3[r] = t3; t3 += d[r] * d[r] * d[r];
+    const double dk = sk - center, dk1 = sk1 - center;
+    bool active = P::seed_violates(dk, dk1, R);
+    if (__any(active)) {
+      Sums S{dk + dk1, 0.0, 0.0};
+      if (CUBIC) {
+        S.s2 = dk * dk + dk1 * dk1;
+        S.s3 = dk * dk * dk + dk1 * dk1 * dk1;
+      }
+      if (active) { a = k; b = k + 1; }
+      const bool grew = active;
+      while (__any(active)) {
+        const bool can_r = active && b < n, can_l = active && a > 1;
+        const double dj = double(ls[can_r ? b : 0]) - center;
+        const double di = double(ls[can_l ? a - 2 : 0]) - center;
+        const double cnt = double(b - a + 1), m = double(k - a + 1);
+        const bool add_r = can_r && P::right_violates(dj, cnt, m, S, R);
+        const bool add_l = can_l && P::left_violates(di, cnt, m, S, R);
+        if (add_r) {
+          S.s1 += dj;
+          if (CUBIC) { S.s2 += dj * dj; S.s3 += dj * dj * dj; }
+          b += 1;
         }
+        if (add_l) {
+          S.s1 += di;
+          if (CUBIC) { S.s2 += di * di; S.s3 += di * di * di; }
+          a -= 1;
+        }
+        active = add_r || add_l;
       }
-      const double p1 = group_exclusive_scan<GL>(t1, lr);
-      double p2 = 0.0, p3 = 0.0;
-      if (CUBIC) {
-        p2 = group_exclusive_scan<GL>(t2, lr);
-        p3 = group_exclusive_scan<GL>(t3, lr);
+      if (grew) {
+        const double da = double(ls[a - 1]) - center, db = double(ls[b - 1]) - center;
+        gamma = P::pooled(double(b - a + 1), double(k - a + 1), S, R, da - R.lambda, db);
       }
-#pragma unroll
-      for (int r = 0; r < E; ++r) {
-        X1[r] += p1;
-        if (CUBIC) { X2[r] += p2; X3[r] += p3; }
-      }
-    }
-    double I1[E], I2[E], I3[E];          // inclusive prefixes
-#pragma unroll
-    for (int r = 0; r < E; ++r) {
-      I1[r] = X1[r] + d[r];
-      if (CUBIC) {
-        I2[r] = X2[r] + d[r] * d[r];
-        I3[r] = X3[r] + d[r] * d[r] * d[r];
-      }
-    }
-
-    // ---- grow the block: right run, then left run, until neither moves ---------------------
-    bool active = grow;
-    while (__any(active)) {
-      // right: positions j > k with  s_j > gamma([a, j-1])  form a prefix of the tail
-      Sums A;                             // exclusive prefix at position a
-      A.s1 = at_pos<GL, E>(X1, a - 1);
-      A.s2 = CUBIC ? at_pos<GL, E>(X2, a - 1) : 0.0;
-      A.s3 = CUBIC ? at_pos<GL, E>(X3, a - 1) : 0.0;
-      const double mR = double(k - a + 1);
-      int cntR = 0;
-#pragma unroll
-      for (int r = 0; r < E; ++r) {
-        const int pos1 = lr * E + r + 1;
-        Sums S{X1[r] - A.s1, CUBIC ? X2[r] - A.s2 : 0.0, CUBIC ? X3[r] - A.s3 : 0.0};
-        const bool pr = active && cand[r] && pos1 > k &&
-                        P::right_violates(d[r], double(pos1 - a), mR, S, R);
-        cntR += group_count<GL>(pr);
-      }
-      const int b_new = max(b, k + cntR);
-      // left: positions i <= k with  gamma_i < gamma([i+1, b])  form a suffix of the head
-      Sums B;                             // inclusive prefix at position b_new
-      B.s1 = at_pos<GL, E>(I1, b_new - 1);
-      B.s2 = CUBIC ? at_pos<GL, E>(I2, b_new - 1) : 0.0;
-      B.s3 = CUBIC ? at_pos<GL, E>(I3, b_new - 1) : 0.0;
-      int cntL = 0;
-#pragma unroll
-      for (int r = 0; r < E; ++r) {
-        const int pos1 = lr * E + r + 1;
-        Sums S{B.s1 - I1[r], CUBIC ? B.s2 - I2[r] : 0.0, CUBIC ? B.s3 - I3[r] : 0.0};
-        const bool pl = active && cand[r] && pos1 <= k &&
-                        P::left_violates(d[r], double(b_new - pos1), double(k - pos1), S, R);
-        cntL += group_count<GL>(pl);
-      }
-      const int a_new = min(a, k + 1 - cntL);
-      if (active) {
-        active = (a_new != a) || (b_new != b);
-        a = a_new;
-        b = b_new;
-      }
-    }
-
-    // ---- pooled value of the final block -----------------------------------------------------
-    if (grow) {
-      Sums S;
-      S.s1 = at_pos<GL, E>(I1, b - 1) - at_pos<GL, E>(X1, a - 1);
-      S.s2 = CUBIC ? at_pos<GL, E>(I2, b - 1) - at_pos<GL, E>(X2, a - 1) : 0.0;
-      S.s3 = CUBIC ? at_pos<GL, E>(I3, b - 1) - at_pos<GL, E>(X3, a - 1) : 0.0;
-      const double da = at_pos<GL, E>(d, a - 1), db = at_pos<GL, E>(d, b - 1);
-      gamma = P::pooled(double(b - a + 1), double(k - a + 1), S, R, da - R.lambda, db);
     }
   }
 
-  // ---- y in sorted order, un-sort scatter ------------------------------------------------------
+  // ---- y in sorted order, scattered to the original index (in LDS) ---------------------------
   // Positions before the block keep their singleton solution (mask: exactly 1; magnitude:
   // s/(1+lambda)); positions after it are exactly 0.
-  double ys[E];
-#pragma unroll
-  for (int r = 0; r < E; ++r) {
-    const int pos1 = lr * E + r + 1;
-    const double v = double(s32[r]) - center;
-    double y;
-    if (pos1 < a) y = MAG ? v * R.inv_1pl : 1.0;
-    else if (pos1 <= b) y = P::y_in_block(v, gamma, R);
-    else y = 0.0;
-    ys[r] = y;
-  }
-  if (out != nullptr && valid) {
+  if (out != nullptr) {
 #pragma unroll
     for (int r = 0; r < E; ++r) {
-      const int pos1 = lr * E + r + 1;
-      if (pos1 <= n) {
-        if (MAG) {
-          const uint32_t o = idx[r] >> 1;
-          const float yv = float(ys[r]);
-          out[base + o] = (yv == 0.0f) ? 0.0f : ((idx[r] & 1u) ? -yv : yv);
-        } else {
-          out[base + idx[r]] = float(ys[r]);
-        }
-      }
+      const int pos1 = e0 + r + 1;
+      const double v = double(s32[r]) - center;
+      const double yb = P::y_in_block(v, gamma, R);
+      const double ya = MAG ? v * R.inv_1pl : 1.0;
+      double y = (pos1 < a) ? ya : yb;
+      y = (pos1 > b) ? 0.0 : y;
+      float yf = float(y);
+      if (MAG) yf = (yf == 0.0f) ? 0.0f : ((field[r] & 1u) ? -yf : yf);
+      if (pos1 <= n) ly[MAG ? (field[r] >> 1) : field[r]] = yf;
     }
   }
-  if (jvp == nullptr) return;
 
-  // ---- JVP (Prop. 7): d gamma = weighted block average of the sorted tangent --------------------
-  double tau[E];
-#pragma unroll
-  for (int r = 0; r < E; ++r) {
-    const int pos1 = lr * E + r + 1;
-    double t = 0.0;
-    if (pos1 <= n) {
-      if (MAG) {
-        t = double(tangent[base + (idx[r] >> 1)]);
-        if (idx[r] & 1u) t = -t;
-        if (s32[r] == 0.0f) t = 0.0;         // sign(0) = 0
-      } else {
-        t = double(tangent[base + idx[r]]);
-      }
-    }
-    tau[r] = t;
-  }
-  double dgamma = 0.0;
-  if (__any(a <= b)) {
-    double num = 0.0, wsum = 0.0;
+  // ---- JVP (Prop. 7): d gamma = weighted block average of the sorted tangent ------------------
+  if (jvp != nullptr) {
+    double tau[E];
 #pragma unroll
     for (int r = 0; r < E; ++r) {
-      const int pos1 = lr * E + r + 1;
-      if (pos1 >= a && pos1 <= b) {
-        const double w = P::jac_weight(double(s32[r]) - center, gamma);
-        num += w * tau[r];
-        wsum += w;
+      const int pos1 = e0 + r + 1;
+      float tf = 0.0f;
+      if (pos1 <= n) tf = lt[MAG ? (field[r] >> 1) : field[r]];
+      if (MAG) {
+        if (field[r] & 1u) tf = -tf;
+        if (s32[r] == 0.0f) tf = 0.0f;         // sign(0) = 0
       }
+      tau[r] = double(tf);
     }
-    num = group_sum<GL>(num);
-    wsum = group_sum<GL>(wsum);
-    if (a <= b) dgamma = num / P::jac_denominator(wsum, double(k - a + 1), R);
-  }
-  if (!valid) return;
+    double dgamma = 0.0;
+    if (__any(a <= b)) {
+      double num = 0.0, wsum = 0.0;
 #pragma unroll
-  for (int r = 0; r < E; ++r) {
-    const int pos1 = lr * E + r + 1;
-    if (pos1 > n) continue;
-    double dy;
-    if (pos1 < a) dy = MAG ? tau[r] * R.inv_1pl : 0.0;
-    else if (pos1 <= b) dy = P::hess(double(s32[r]) - center, gamma, R) * (tau[r] - dgamma);
-    else dy = 0.0;
-    if (MAG) {
-      const float v = (s32[r] == 0.0f) ? 0.0f : float(dy);
-      jvp[base + (idx[r] >> 1)] = (v == 0.0f) ? 0.0f : ((idx[r] & 1u) ? -v : v);
-    } else {
-      jvp[base + idx[r]] = float(dy);
+      for (int r = 0; r < E; ++r) {
+        const int pos1 = e0 + r + 1;
+        const bool in = pos1 >= a && pos1 <= b;
+        const double w = in ? P::jac_weight(double(s32[r]) - center, gamma) : 0.0;
+        num += w * tau[r];
+        if (CUBIC) wsum += w;
+      }
+      num = group_sum_f64<GL>(num);
+      if (CUBIC) wsum = group_sum_f64<GL>(wsum);
+      else wsum = double(b - a + 1);
+      if (a <= b) dgamma = num / P::jac_denominator(wsum, double(k - a + 1), R);
     }
+    __builtin_amdgcn_wave_barrier();         // every gather of the tangent is done
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const int pos1 = e0 + r + 1;
+      const double hb = P::hess(double(s32[r]) - center, gamma, R) * (tau[r] - dgamma);
+      const double ha = MAG ? tau[r] * R.inv_1pl : 0.0;
+      double dy = (pos1 < a) ? ha : hb;
+      dy = (pos1 > b) ? 0.0 : dy;
+      float df = float(dy);
+      if (MAG) {
+        if (s32[r] == 0.0f) df = 0.0f;
+        df = (df == 0.0f) ? 0.0f : ((field[r] & 1u) ? -df : df);
+      }
+      if (pos1 <= n) lt[MAG ? (field[r] >> 1) : field[r]] = df;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (!valid) return;
+
+  // ---- coalesced stores of the un-sorted rows ---------------------------------------------------
+  if (out != nullptr) {
+    float yv[E];
+    lds_load<E>(ly + e0, yv);
+    store_elems<E, VEC>(out, base, e0, n, yv);
+  }
+  if (jvp != nullptr) {
+    float jv[E];
+    lds_load<E>(lt + e0, jv);
+    store_elems<E, VEC>(jvp, base, e0, n, jv);
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int GL, int E>
+template <int GL, int E, bool VEC>
 int launch_shape(bool mag, int pc, const float* x, const float* t, float* out, float* jvp,
                  int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
-  constexpr int RPW = kWave / GL;
-  const int64_t waves = (rows + RPW - 1) / RPW;
-  const int64_t blocks = (waves + 3) / 4;
+  using C = ShortCfg<GL, E>;
+  const int64_t waves = (rows + C::RPW - 1) / C::RPW;
+  const int64_t blocks = (waves + C::WPB - 1) / C::WPB;
   if (blocks > 0x7fffffffLL) return -1;
-  dim3 grid((unsigned)blocks), block(256);
+  dim3 grid((unsigned)blocks), block(C::WPB * kWave);
   if (!mag && pc == kP2)
-    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP2>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP2, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
   else if (!mag && pc == kP43)
-    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP43>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP43, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
   else if (mag && pc == kP2)
-    hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP2>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP2, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
   else
     return -1;
   return 0;
 }
 
-template <int GL, int E>
+template <int GL, int E, bool VEC>
 int launch_argsort_shape(const float* x, int32_t* perm, int64_t rows, int n, hipStream_t st) {
   constexpr int RPW = kWave / GL;
   const int64_t waves = (rows + RPW - 1) / RPW;
   const int64_t blocks = (waves + 3) / 4;
   if (blocks > 0x7fffffffLL) return -1;
-  hipLaunchKernelGGL((short_argsort_kernel<GL, E>), dim3((unsigned)blocks), dim3(256), 0, st, x,
-                     perm, rows, n);
+  hipLaunchKernelGGL((short_argsort_kernel<GL, E, VEC>), dim3((unsigned)blocks), dim3(256), 0, st,
+                     x, perm, rows, n);
   return 0;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// log2 of the number of lanes that share a row, for a padded row length np (a power of two).
+// Fewer lanes per row mean fewer cross-lane stages of the network and less replicated work in
+// the solve, but also fewer wavefronts; with few rows the rows are spread over more lanes so
+// that every SIMD of the chip (1024 of them) still gets wavefronts.
+int pick_log_gl(int np, int64_t rows) {
+  static const int forced = [] {
+    const char* e = getenv("TOPK_SHORT_ROW_LANES");      // tuning override: lanes per row
+    return e ? atoi(e) : 0;
+  }();
+  int lo = 0;                                            // smallest allowed log2(GL): E <= 16
+  while ((np >> lo) > 16) ++lo;
+  int hi = 0;                                            // largest allowed: E >= min(4, np)
+  while ((np >> (hi + 1)) >= 4 && hi < 6) ++hi;
+  if (hi < lo) hi = lo;
+  if (forced > 0) {
+    int lg = 0;
+    while ((1 << lg) < forced) ++lg;
+    return lg < lo ? lo : (lg > hi ? hi : lg);
+  }
+  int lg = lo;
+  // want at least ~2048 wavefronts when the batch allows it
+  while (lg < hi && (rows << lg) / kWave < 2048) ++lg;
+  return lg;
 }
 
 }  // namespace
 
-#define TOPK_SHAPE_SWITCH(CALL)                      \
-  if (n <= 2) return CALL(2, 1);                     \
-  if (n <= 4) return CALL(4, 1);                     \
-  if (n <= 8) return CALL(8, 1);                     \
-  if (n <= 16) return CALL(16, 1);                   \
-  if (n <= 32) return CALL(32, 1);                   \
-  if (n <= 64) return CALL(64, 1);                   \
-  if (n <= 128) return CALL(64, 2);                  \
-  if (n <= 256) return CALL(64, 4);                  \
-  if (n <= 512) return CALL(64, 8);                  \
-  if (n <= 1024) return CALL(64, 16);                \
-  return -1;
+// Dispatch over (lanes per row GL, elements per lane E) with GL * E = padded row length.
+#define TOPK_FOR_SHAPE(GL, E)                                                      \
+  if (np == (GL) * (E) && lg == topk::ilog2(GL)) return vec ? CALL(GL, E, true) : CALL(GL, E, false);
+
+#define TOPK_SHAPE_TABLE                                                           \
+  TOPK_FOR_SHAPE(1, 4) TOPK_FOR_SHAPE(1, 8) TOPK_FOR_SHAPE(2, 4) TOPK_FOR_SHAPE(1, 16)      \
+  TOPK_FOR_SHAPE(2, 8) TOPK_FOR_SHAPE(4, 4) TOPK_FOR_SHAPE(2, 16) TOPK_FOR_SHAPE(4, 8)      \
+  TOPK_FOR_SHAPE(8, 4) TOPK_FOR_SHAPE(4, 16) TOPK_FOR_SHAPE(8, 8) TOPK_FOR_SHAPE(16, 4)     \
+  TOPK_FOR_SHAPE(8, 16) TOPK_FOR_SHAPE(16, 8) TOPK_FOR_SHAPE(32, 4) TOPK_FOR_SHAPE(16, 16)  \
+  TOPK_FOR_SHAPE(32, 8) TOPK_FOR_SHAPE(64, 4) TOPK_FOR_SHAPE(32, 16) TOPK_FOR_SHAPE(64, 8)  \
+  TOPK_FOR_SHAPE(64, 16)
 
 int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, float* out,
                       float* jvp, int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
-#define CALL(GL, E) launch_shape<GL, E>(mag, pc, x, tangent, out, jvp, rows, n, k, R, st)
-  TOPK_SHAPE_SWITCH(CALL)
+  const bool vec = (n % 4 == 0) && aligned16(x) && aligned16(tangent) && aligned16(out) &&
+                   aligned16(jvp);
+  int np = 2;
+  while (np < n) np <<= 1;
+#define CALL(GL, E, V) launch_shape<GL, E, V>(mag, pc, x, tangent, out, jvp, rows, n, k, R, st)
+  if (np == 2) return CALL(1, 2, false);
+  const int lg = pick_log_gl(np, rows);
+  TOPK_SHAPE_TABLE
 #undef CALL
+  return -1;
 }
 
 int launch_short_argsort(const float* x, int32_t* perm, int64_t rows, int n, hipStream_t st) {
-#define CALL(GL, E) launch_argsort_shape<GL, E>(x, perm, rows, n, st)
-  TOPK_SHAPE_SWITCH(CALL)
+  const bool vec = (n % 4 == 0) && aligned16(x);
+  int np = 2;
+  while (np < n) np <<= 1;
+#define CALL(GL, E, V) launch_argsort_shape<GL, E, V>(x, perm, rows, n, st)
+  if (np == 2) return CALL(1, 2, false);
+  const int lg = pick_log_gl(np, rows);
+  TOPK_SHAPE_TABLE
 #undef CALL
+  return -1;
 }
 
 }  // namespace topk
