@@ -38,6 +38,11 @@ def parse():
                     help="graph: the K launches are captured once in a HIP graph and replayed; "
                          "stream: K plain launches from Python")
     ap.add_argument("--cold-mib", type=int, default=640, help="footprint of the rotating buffer sets")
+    ap.add_argument("--regime", choices=["both", "cold"], default="both",
+                    help="cold: skip the warm (same-buffer) measurement, e.g. under a profiler")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the operator, time a plain device copy of the same footprint "
+                         "(theta|tangent -> out|jvp); used to scale the rocprofv3 byte counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=4.0)
     return ap.parse_args()
@@ -67,8 +72,22 @@ class Runner:
                       ctypes.c_void_p(c.data_ptr()), ctypes.c_void_p(d.data_ptr()))
                      for (a, b, c, d) in self.bufs]
         self.ctypes = ctypes
+        self.copy_mode = False
+        self.copies = []
+
+    def enable_copy_mode(self):
+        """Plain copies with the operator's footprint: 2 arrays in, 2 arrays out per step."""
+        torch = self.torch
+        self.copy_mode = True
+        for (a, b, c, d) in self.bufs:
+            src = torch.cat([a.reshape(-1), b.reshape(-1)])
+            self.copies.append((src, torch.empty_like(src)))
 
     def launch(self, i, stream_ptr):
+        if self.copy_mode:
+            src, dst = self.copies[i % len(self.copies)]
+            self.torch.mul(src, 1.0, out=dst)   # one plain elementwise kernel: reads src, writes dst
+            return
         rc = self.fn(*self.args[i % len(self.args)], stream_ptr)
         if rc != 0:
             raise RuntimeError(f"library call failed: {rc}")
@@ -153,9 +172,17 @@ def main():
     set_bytes = 4 * 4 * w.rows * w.n
     sets = max(2, -(-a.cold_mib * (1 << 20) // set_bytes))
     r = Runner(w, sets, "cuda:0")
+    if a.copy_calibration:
+        r.enable_copy_mode()
+        ms = r.timed(a.steps, a.warmup, a.mode, rotate=True)
+        print(json.dumps({"calibration": "plain copy", "bytes_read_per_step": algo_bytes // 2,
+                          "bytes_written_per_step": algo_bytes // 2, "steps": a.steps,
+                          "ms_per_step": ms / a.steps,
+                          "gbps": algo_bytes / (ms / a.steps * 1e-3) / 1e9}))
+        return
 
     ms_cold = r.timed(a.steps, a.warmup, a.mode, rotate=True)
-    ms_warm = r.timed(a.steps, a.warmup, a.mode, rotate=False)
+    ms_warm = r.timed(a.steps, a.warmup, a.mode, rotate=False) if a.regime == "both" else ms_cold
 
     per_cold = ms_cold / a.steps
     per_warm = ms_warm / a.steps
@@ -190,8 +217,8 @@ def main():
         "elements_per_s": w.rows * w.n / (per_cold * 1e-3),
         "gbps": gbps_cold,
         "pct_hbm_peak": 100.0 * gbps_cold / HBM_PEAK_GBPS,
-        "warm": {"ms_per_step": per_warm, "rows_per_s": w.rows / (per_warm * 1e-3),
-                 "effective_gbps": gbps_warm},
+        "warm": ({"ms_per_step": per_warm, "rows_per_s": w.rows / (per_warm * 1e-3),
+                  "effective_gbps": gbps_warm} if a.regime == "both" else None),
         "roofline": {
             "bound": "hbm", "achieved": gbps_cold, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": gbps_cold / HBM_PEAK_GBPS, "traffic": traffic,
