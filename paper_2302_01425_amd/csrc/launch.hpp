@@ -32,6 +32,14 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
                       float* jvp, int64_t rows, int n, int k, const Reg& R, hipStream_t st);
 int launch_short_argsort(const float* x, int32_t* perm, int64_t rows, int n, hipStream_t st);
 
+// Fast variants for padded row lengths np <= 128 with 2^lg lanes per row; return -2 when the
+// (np, lg) shape is not instantiated (the caller then uses the general kernels above).
+int launch_short_rows_fast(int np, int lg, bool vec, bool mag, int pc, const float* x,
+                           const float* tangent, float* out, float* jvp, int64_t rows, int n,
+                           int k, const Reg& R, hipStream_t st);
+int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t* perm,
+                              int64_t rows, int n, hipStream_t st);
+
 // Long rows: segmented radix sort (result in B.keys_a / B.idx_a), then solve + scatter.
 int radix_tiles(int64_t n);
 int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, const SortBuffers& B,

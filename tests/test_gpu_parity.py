@@ -149,6 +149,30 @@ def test_strict_merge_kinks(gpu, oracle):
         run_case(gpu, oracle, "mag", th, t, k, P2, lam)
 
 
+def test_values_closer_than_the_truncated_sort_key(gpu, oracle):
+    """Rows whose values differ only in the last few mantissa bits (and mixtures of such clusters
+    with exact ties): the permutation must still be the exact stable argsort."""
+    r = np.random.default_rng(99)
+    for n in (4, 16, 24, 64, 100, 128):
+        rows = 37
+        ulps = r.permutation(n).astype(np.int64)
+        base = np.float32(1.0).view(np.int32)
+        x = np.empty((rows, n), dtype=np.float32)
+        x[0] = (base + ulps).astype(np.int32).view(np.float32)             # one cluster, all distinct
+        x[1] = -x[0]
+        x[2] = (base + (ulps // 3)).astype(np.int32).view(np.float32)      # clusters with exact ties
+        for i in range(3, rows):
+            c = r.normal(size=max(1, n // 8)).astype(np.float32)           # a few cluster centres
+            pick = r.integers(0, c.size, size=n)
+            off = r.integers(-40, 40, size=n)
+            x[i] = (c[pick].view(np.int32) + off).astype(np.int32).view(np.float32)
+        t = r.normal(size=(rows, n)).astype(np.float32)
+        for k in sorted({1, max(1, n // 4), n - 1}):
+            for p in (P2, P43):
+                run_case(gpu, oracle, "mask", x, t, k, p, 0.3)
+            run_case(gpu, oracle, "mag", x, t, k, P2, 0.05)
+
+
 def test_determinism_and_streams(gpu):
     import torch
     from paper_2302_01425_amd.workloads import WORKLOADS
