@@ -109,7 +109,7 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   rc = carve(rows, n, &B);
   if (rc != TOPK_OK) return rc;
   if (topk::launch_segmented_sort(mag, x, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
-  if (topk::launch_long_tail(mag, pc, B, need_jvp ? tangent : nullptr, out,
+  if (topk::launch_long_tail(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
                              need_jvp ? jvp : nullptr, rows, n, k, R, st) != 0)
     return TOPK_ERR_INVALID;
   return finish();

@@ -10,9 +10,14 @@ namespace topk {
 
 // Per-row result of the long-row solve: the pooled block [a, b] (1-based, inclusive; a = k+1,
 // b = k when nothing pools), its pooled value (relative to `center`), and d gamma of the JVP.
+// [wa, wb] is the block widened over values tied with its two end values: every sorted position
+// whose value lies in [lo_incl, hi_incl] is inside it.  Values above hi_incl are before the block,
+// values below lo_incl after it.  When nothing pools, hi_incl < lo_incl and the window is empty.
 struct RowInfo {
   int64_t a, b;
+  int64_t wa, wb;
   double gamma, center, dgamma;
+  float hi_incl, lo_incl;
 };
 
 // Device scratch of the long-row path (all carved out of the caller's workspace).
@@ -44,7 +49,8 @@ int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t*
 int radix_tiles(int64_t n);
 int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, const SortBuffers& B,
                           hipStream_t st);
-int launch_long_tail(bool mag, int pc, const SortBuffers& B, const float* tangent, float* out,
-                     float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R, hipStream_t st);
+int launch_long_tail(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
+                     float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
+                     hipStream_t st);
 
 }  // namespace topk

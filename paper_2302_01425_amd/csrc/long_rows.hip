@@ -132,6 +132,34 @@ __device__ int64_t sweep(const uint32_t* __restrict__ skeys, int64_t n, int64_t 
   return added;
 }
 
+// Length of the run of sorted keys equal to `key` that starts at 1-based position `start` and
+// extends upwards (UP) or downwards, counted by the whole workgroup in chunks.
+template <bool UP>
+__device__ int64_t count_equal_run(const uint32_t* __restrict__ skeys, int64_t n, int64_t start,
+                                   uint32_t key, Acc* sm_acc) {
+  int64_t total = 0;
+  for (;;) {
+    const int64_t from = UP ? start + total : start - total;
+    const int64_t remaining = UP ? (n - from + 1) : from;
+    if (remaining <= 0) break;
+    Acc acc{0.0, 0.0, 0.0, 0};
+    // equal keys are contiguous, so counting matches inside the chunk gives the run length
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int64_t q = int64_t(threadIdx.x) * kPer + i;
+      if (q < remaining) {
+        const int64_t pos1 = UP ? from + q : from - q;
+        acc.c += (skeys[pos1 - 1] == key) ? 1 : 0;
+      }
+    }
+    const Acc got = block_sum_acc(acc, sm_acc);
+    total += got.c;
+    const int64_t visited = remaining < kChunk ? remaining : kChunk;
+    if (got.c < visited) break;
+  }
+  return total;
+}
+
 template <bool MAG, int PC>
 __global__ __launch_bounds__(kThreads) void long_solve_kernel(
     const uint32_t* __restrict__ skeys_all, const uint32_t* __restrict__ sidx_all,
@@ -191,60 +219,109 @@ __global__ __launch_bounds__(kThreads) void long_solve_kernel(
     const Acc got = block_sum_acc(acc, sm_acc);
     dgamma = got.s1 / P::jac_denominator(got.s2, double(k - a + 1), R);
   }
+  // ---- value window of the block, widened over ties at both ends -------------------------------
+  int64_t wa = a, wb = b;
+  float hi_incl, lo_incl;
+  if (grow) {
+    const uint32_t key_a = skeys[a - 1], key_b = skeys[b - 1];
+    hi_incl = key_to_float(key_a);
+    lo_incl = key_to_float(key_b);
+    wa = a - count_equal_run<false>(skeys, n, a - 1, key_a, sm_acc);
+    wb = b + count_equal_run<true>(skeys, n, b + 1, key_b, sm_acc);
+  } else if (k >= 1 && k < n) {
+    // no violation: s_k > s_{k+1} strictly; "above hi" = the top k, "below lo" = the rest
+    hi_incl = key_to_float(skeys[k]);        // s_{k+1}
+    lo_incl = key_to_float(skeys[k - 1]);    // s_k
+    wa = k + 1;
+    wb = k;
+  } else {
+    // k == 0: everything is below; k == n: everything is above
+    hi_incl = (k == 0) ? __uint_as_float(0x7f800000u) : __uint_as_float(0xff800000u);
+    lo_incl = hi_incl;
+    wa = k + 1;
+    wb = k;
+  }
   if (threadIdx.x == 0) {
     RowInfo ri;
     ri.a = a;
     ri.b = b;
+    ri.wa = wa;
+    ri.wb = wb;
     ri.gamma = gamma;
     ri.center = center;
     ri.dgamma = dgamma;
+    ri.hi_incl = hi_incl;
+    ri.lo_incl = lo_incl;
     info[row] = ri;
   }
   (void)CUBIC;
 }
 
-__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* __restrict__ p0,
-                                                             float* __restrict__ p1, int64_t count) {
-  const int64_t stride = int64_t(gridDim.x) * kThreads;
-  for (int64_t i = int64_t(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride) {
-    if (p0) p0[i] = 0.0f;
-    if (p1) p1[i] = 0.0f;
+// Dense pass in original order: everything whose value lies outside the block's value window.
+// mask: 1 above, 0 below; magnitude: x/(1+lambda) above, 0 below; JVP 0 resp. t/(1+lambda).
+// Elements inside the window are left to long_window_kernel.
+template <bool MAG>
+__global__ __launch_bounds__(kThreads) void long_dense_kernel(
+    const float* __restrict__ x_all, const float* __restrict__ tangent_all,
+    const RowInfo* __restrict__ info, float* __restrict__ out_all, float* __restrict__ jvp_all,
+    int64_t n, int chunks, float inv_1pl) {
+  const int64_t row = blockIdx.x / chunks;
+  const int64_t chunk = blockIdx.x % chunks;
+  const RowInfo ri = info[row];
+  const bool empty = ri.wa > ri.wb;
+  const int64_t base = row * n;
+  const int64_t first = chunk * int64_t(kThreads * 8);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
+    if (e >= n) continue;
+    const float xv = x_all[base + e];
+    const float v = MAG ? fabsf(xv) : xv;
+    // empty window: hi_incl = s_{k+1} < lo_incl = s_k, every value is > hi or < lo
+    const bool above = v > ri.hi_incl;
+    const bool below = v < ri.lo_incl;
+    if (!empty && !above && !below) continue;          // inside the window
+    if (out_all != nullptr) out_all[base + e] = above ? (MAG ? xv * inv_1pl : 1.0f) : 0.0f;
+    if (jvp_all != nullptr) {
+      float d = 0.0f;
+      if (MAG && above && xv != 0.0f) d = tangent_all[base + e] * inv_1pl;
+      jvp_all[base + e] = d;
+    }
   }
 }
 
-// Positions 1..b of every row: y and dy in sorted order, scattered to the original index.
+// Sorted positions wa..wb of every row: y and dy from (a, b, gamma), scattered through sigma.
 template <bool MAG, int PC>
-__global__ __launch_bounds__(kThreads) void long_epilogue_kernel(
+__global__ __launch_bounds__(kThreads) void long_window_kernel(
     const uint32_t* __restrict__ skeys_all, const uint32_t* __restrict__ sidx_all,
     const float* __restrict__ tangent_all, const RowInfo* __restrict__ info,
-    float* __restrict__ out_all, float* __restrict__ jvp_all, int64_t n, int tiles, Reg R) {
+    float* __restrict__ out_all, float* __restrict__ jvp_all, int64_t n, int blocks_per_row,
+    Reg R) {
   using P = Pool<MAG, PC>;
-  const int64_t row = blockIdx.x / tiles;
-  const int64_t tile = blockIdx.x % tiles;
+  const int64_t row = blockIdx.x / blocks_per_row;
+  const int64_t part = blockIdx.x % blocks_per_row;
   const RowInfo ri = info[row];
-  const int64_t first = tile * kChunk;           // 0-based position of the tile's first element
-  if (first >= ri.b) return;                     // only positions <= b are non-zero
   const int64_t base = row * n;
-#pragma unroll
-  for (int i = 0; i < kPer; ++i) {
-    const int64_t pos1 = first + i * kThreads + threadIdx.x + 1;
-    if (pos1 > ri.b) continue;
+  for (int64_t pos1 = ri.wa + part * kThreads + threadIdx.x; pos1 <= ri.wb;
+       pos1 += int64_t(blocks_per_row) * kThreads) {
     const uint32_t id = sidx_all[base + pos1 - 1];
     const float sv = key_to_float(skeys_all[base + pos1 - 1]);
     const int64_t o = base + (MAG ? (id >> 1) : id);
     const bool neg = MAG && (id & 1u);
     const double v = double(sv) - ri.center;
-    const bool in_block = pos1 >= ri.a;
+    const bool before = pos1 < ri.a, after = pos1 > ri.b;
     if (out_all != nullptr) {
-      const double y = in_block ? P::y_in_block(v, ri.gamma, R) : (MAG ? v * R.inv_1pl : 1.0);
+      double y = before ? (MAG ? v * R.inv_1pl : 1.0) : P::y_in_block(v, ri.gamma, R);
+      if (after) y = 0.0;
       const float yf = float(y);
       out_all[o] = (MAG && yf == 0.0f) ? 0.0f : (neg ? -yf : yf);
     }
-    if (jvp_all != nullptr && (MAG || in_block)) {
+    if (jvp_all != nullptr) {
       double t = double(tangent_all[o]);
       if (neg) t = -t;
       if (MAG && sv == 0.0f) t = 0.0;
-      const double dy = in_block ? P::hess(v, ri.gamma, R) * (t - ri.dgamma) : t * R.inv_1pl;
+      double dy = before ? (MAG ? t * R.inv_1pl : 0.0) : P::hess(v, ri.gamma, R) * (t - ri.dgamma);
+      if (after) dy = 0.0;
       float df = float(dy);
       if (MAG && sv == 0.0f) df = 0.0f;
       jvp_all[o] = (df == 0.0f) ? 0.0f : (neg ? -df : df);
@@ -253,29 +330,29 @@ __global__ __launch_bounds__(kThreads) void long_epilogue_kernel(
 }
 
 template <bool MAG, int PC>
-void launch_tail(const SortBuffers& B, const float* tangent, float* out, float* jvp, int64_t rows,
-                 int64_t n, int64_t k, const Reg& R, hipStream_t st) {
+void launch_tail(const SortBuffers& B, const float* x, const float* tangent, float* out,
+                 float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R, hipStream_t st) {
   hipLaunchKernelGGL((long_solve_kernel<MAG, PC>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
                      B.keys_a, B.idx_a, jvp ? tangent : nullptr, B.info, n, k, R);
-  const int64_t count = rows * n;
-  const int64_t want = (count + kThreads * 8 - 1) / (kThreads * 8);
-  const unsigned fill_blocks = unsigned(want < 1 ? 1 : (want > 65536 ? 65536 : want));
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(kThreads), 0, st, out, jvp, count);
-  const int tiles = int((n + kChunk - 1) / kChunk);
-  hipLaunchKernelGGL((long_epilogue_kernel<MAG, PC>), dim3(unsigned(rows * tiles)), dim3(kThreads),
-                     0, st, B.keys_a, B.idx_a, tangent, B.info, out, jvp, n, tiles, R);
+  const int chunks = int((n + kThreads * 8 - 1) / (kThreads * 8));
+  hipLaunchKernelGGL((long_dense_kernel<MAG>), dim3(unsigned(rows * chunks)), dim3(kThreads), 0, st,
+                     x, tangent, B.info, out, jvp, n, chunks, float(R.inv_1pl));
+  const int64_t tiles = (n + kChunk - 1) / kChunk;
+  const int bpr = int(tiles < 64 ? tiles : 64);
+  hipLaunchKernelGGL((long_window_kernel<MAG, PC>), dim3(unsigned(rows * bpr)), dim3(kThreads), 0,
+                     st, B.keys_a, B.idx_a, tangent, B.info, out, jvp, n, bpr, R);
 }
 
 }  // namespace
 
-int launch_long_tail(bool mag, int pc, const SortBuffers& B, const float* tangent, float* out,
-                     float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
+int launch_long_tail(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
+                     float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
                      hipStream_t st) {
-  const int64_t tiles = (n + kChunk - 1) / kChunk;
-  if (rows * tiles > 0x7fffffffLL) return -1;
-  if (!mag && pc == kP2) launch_tail<false, kP2>(B, tangent, out, jvp, rows, n, k, R, st);
-  else if (!mag && pc == kP43) launch_tail<false, kP43>(B, tangent, out, jvp, rows, n, k, R, st);
-  else if (mag && pc == kP2) launch_tail<true, kP2>(B, tangent, out, jvp, rows, n, k, R, st);
+  const int64_t chunks = (n + kThreads * 8 - 1) / (kThreads * 8);
+  if (rows * chunks > 0x7fffffffLL) return -1;
+  if (!mag && pc == kP2) launch_tail<false, kP2>(B, x, tangent, out, jvp, rows, n, k, R, st);
+  else if (!mag && pc == kP43) launch_tail<false, kP43>(B, x, tangent, out, jvp, rows, n, k, R, st);
+  else if (mag && pc == kP2) launch_tail<true, kP2>(B, x, tangent, out, jvp, rows, n, k, R, st);
   else return -1;
   return 0;
 }

@@ -89,8 +89,16 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const float* __res
     if (valid) key = FIRST ? first_key<MAG>(x[row_base + e]) : keys[row_base + e];
     const uint32_t d = (key >> shift) & (kRadix - 1);
     const unsigned long long vm = __ballot(valid);
-    const unsigned long long peers = match_digit(d, vm);
-    if (valid && (peers & lanemask_lt()) == 0) cnt[w][d] += __popcll(peers);   // leader of its digit
+    if (vm == 0) continue;
+    // The digit of the first valid lane is counted once for all lanes that share it (this keeps
+    // skewed digits, e.g. the exponent byte, from serialising); the other lanes add 1 each to
+    // this wavefront's private counters.
+    const int first = __ffsll((long long)vm) - 1;
+    const uint32_t d0 = uint32_t(__builtin_amdgcn_readlane(int(d), first));
+    const bool same = valid && d == d0;
+    const unsigned long long m0 = __ballot(same);
+    if (lane == first) cnt[w][d0] += __popcll(m0);
+    if (valid && !same) atomicAdd(&cnt[w][d], 1u);
   }
   __syncthreads();
   const int d = threadIdx.x;

@@ -422,7 +422,10 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
 #define CALL(GL, E, V) launch_shape<GL, E, V>(mag, pc, x, tangent, out, jvp, rows, n, k, R, st)
   if (np == 2) return CALL(1, 2, false);
   const int lg = pick_log_gl(np, rows);
-  if (np <= 128 && fast_enabled()) {
+  // The fast kernels grow the pooled block one neighbour per step, which suits the small blocks
+  // of p = 2 routers; p = 4/3 pools more positions and its step is dearer, so it stays on the
+  // kernels below, which test every position of the row at once from prefix sums.
+  if (np <= 128 && pc == kP2 && fast_enabled()) {
     const int rc = launch_short_rows_fast(np, lg, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
     if (rc != -2) return rc;
   }
