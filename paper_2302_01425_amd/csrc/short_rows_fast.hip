@@ -226,7 +226,9 @@ __device__ __forceinline__ double recip(double c) {
 
 // VEC: rows are 16-byte aligned and n % 4 == 0 (float4 loads and stores).
 // FULL: additionally n == NP, so there is no padding and no bounds test anywhere.
-template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL>
+// MODE: 0 forward only, 1 JVP only, 2 forward + JVP (compile-time, so no output is tested for at
+// run time).
+template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE>
 __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast_kernel(
     const float* __restrict__ x, const float* __restrict__ tangent, float* __restrict__ out,
     float* __restrict__ jvp, int64_t rows, int n, int k, Reg R, float inv_lambda32,
@@ -253,7 +255,7 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   float* ly = &lds[wv][3][roff];         // y, original order, zero-filled
   float* ld = &lds[wv][4][roff];         // dy, original order, zero-filled
   const int nn = FULL ? NP : n;
-  const bool want_out = out != nullptr, want_jvp = jvp != nullptr;
+  constexpr bool want_out = (MODE != 1), want_jvp = (MODE != 0);
 
   // ---- load, stage, sort ---------------------------------------------------------------------
   TOPK_MARK(0);
@@ -500,24 +502,37 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   TOPK_MARK(5);
 }
 
-template <int GL, int E, bool VEC, bool FULL>
-int launch_fast_shape2(bool mag, int pc, const float* x, const float* t, float* out, float* jvp,
-                       int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
+template <int GL, int E, bool MAG, bool VEC, bool FULL, int MODE>
+int launch_fast_mode(const float* x, const float* t, float* out, float* jvp, int64_t rows, int n,
+                     int k, const Reg& R, hipStream_t st) {
   using C = FastCfg<GL, E>;
   const int64_t waves = (rows + C::RPW - 1) / C::RPW;
   const int64_t blocks = (waves + C::WPB - 1) / C::WPB;
   if (blocks > 0x7fffffffLL) return -1;
   dim3 grid((unsigned)blocks), block(C::WPB * kWave);
   const float il = float(R.inv_lambda), i1 = float(R.inv_1pl);
-  if (!mag && pc == kP2)
-    hipLaunchKernelGGL((short_rows_fast_kernel<GL, E, false, kP2, VEC, FULL>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R, il, i1);
-  else if (!mag && pc == kP43)
-    hipLaunchKernelGGL((short_rows_fast_kernel<GL, E, false, kP43, VEC, FULL>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R, il, i1);
-  else if (mag && pc == kP2)
-    hipLaunchKernelGGL((short_rows_fast_kernel<GL, E, true, kP2, VEC, FULL>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R, il, i1);
-  else
-    return -1;
+  hipLaunchKernelGGL((short_rows_fast_kernel<GL, E, MAG, kP2, VEC, FULL, MODE>), grid, block, 0, st,
+                     x, t, out, jvp, rows, n, k, R, il, i1);
   return 0;
+}
+
+// only p = 2 is instantiated (p = 4/3 rows use the prefix-sum kernels of short_rows.hip)
+template <int GL, int E, bool VEC, bool FULL>
+int launch_fast_shape2(bool mag, int pc, const float* x, const float* t, float* out, float* jvp,
+                       int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
+  if (pc != kP2) return -2;
+  const int mode = (jvp == nullptr) ? 0 : (out == nullptr ? 1 : 2);
+#define TOPK_MODE_CALL(MAGV, M) \
+  return launch_fast_mode<GL, E, MAGV, VEC, FULL, M>(x, t, out, jvp, rows, n, k, R, st)
+  if (!mag) {
+    if (mode == 0) TOPK_MODE_CALL(false, 0);
+    if (mode == 1) TOPK_MODE_CALL(false, 1);
+    TOPK_MODE_CALL(false, 2);
+  }
+  if (mode == 0) TOPK_MODE_CALL(true, 0);
+  if (mode == 1) TOPK_MODE_CALL(true, 1);
+  TOPK_MODE_CALL(true, 2);
+#undef TOPK_MODE_CALL
 }
 
 template <int GL, int E, bool VEC>
