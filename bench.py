@@ -192,7 +192,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(a.workload)
+            entry = json.load(f).get(a.workload)
+            traffic = entry["total_bytes"] if entry else None    # HBM bytes per launch (rocprofv3)
 
     line = {
         "metric": METRIC if a.workload == "moe_router" else f"rows/s for {w.op} fwd+JVP, {a.workload}",
