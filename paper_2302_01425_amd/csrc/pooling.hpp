@@ -42,6 +42,14 @@ struct Reg {           // regulariser constants, computed once on the host in fl
   double inv_1pl;      // 1 / (1 + lambda)
 };
 
+// reciprocal of a positive float64 to full precision: hardware estimate + two Newton steps
+__device__ __forceinline__ double recip(double c) {
+  double r = __builtin_amdgcn_rcp(c);
+  r = fma(fma(-c, r, 1.0), r, r);
+  r = fma(fma(-c, r, 1.0), r, r);
+  return r;
+}
+
 template <bool MAG, int PC>
 struct Pool {
   static constexpr bool kCubic = (PC == kP43);
@@ -91,18 +99,22 @@ struct Pool {
                                                   const Reg& R, double lo, double hi) {
     if (MAG) return S.s1 / (cnt + R.lambda * m);
     if (!kCubic) return (S.s1 - R.lambda * m) / cnt;
+    // Safeguarded Newton.  Inside the block all |s_i| <= ~lambda (centred values), so lambda is
+    // the scale of gamma; steps below 1e-13 lambda are rounding noise of the expanded cubic
+    // (the outputs need gamma to ~1e-7 lambda only).
     double a = lo, b = hi;
     double x = 0.5 * (a + b);
-    for (int it = 0; it < 100; ++it) {
-      double F = cubic(x, cnt, m, S, R);
+    const double tol = 1e-13 * R.lambda;
+    for (int it = 0; it < 64; ++it) {
+      const double F = cubic(x, cnt, m, S, R);
       if (F == 0.0) break;
       if (F > 0.0) b = x; else a = x;
-      double D = (3.0 * cnt * x - 6.0 * S.s1) * x + 3.0 * S.s2;
-      double xn = (D > 0.0) ? x - F / D : 0.5 * (a + b);
-      if (!(xn > a && xn < b)) xn = 0.5 * (a + b);
-      double step = fabs(xn - x);
+      const double D = (3.0 * cnt * x - 6.0 * S.s1) * x + 3.0 * S.s2;
+      double xn = x - F * recip(D);
+      if (!(xn > a && xn < b)) xn = 0.5 * (a + b);   // also catches D <= 0 (inf / nan)
+      const double step = fabs(xn - x);
       x = xn;
-      if (step <= 2.3e-16 * fmax(fabs(x), R.lambda) || !(b > a)) break;
+      if (step <= tol) break;
     }
     return x;
   }

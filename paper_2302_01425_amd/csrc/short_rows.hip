@@ -374,8 +374,11 @@ int pick_log_gl(int np, int64_t rows) {
     const char* e = getenv("TOPK_SHORT_ROW_LANES");      // tuning override: lanes per row
     return e ? atoi(e) : 0;
   }();
-  int lo = 0;                                            // smallest allowed log2(GL): E <= 16
-  while ((np >> lo) > 16) ++lo;
+  // smallest allowed log2(GL): at most 8 elements per lane up to 128 padded elements (measured:
+  // 16 per lane lose to 8 on both router workloads), at most 16 beyond
+  const int emax = np <= 128 ? 8 : 16;
+  int lo = 0;
+  while ((np >> lo) > emax) ++lo;
   int hi = 0;                                            // largest allowed: E >= min(4, np)
   while ((np >> (hi + 1)) >= 4 && hi < 6) ++hi;
   if (hi < lo) hi = lo;
@@ -422,10 +425,7 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
 #define CALL(GL, E, V) launch_shape<GL, E, V>(mag, pc, x, tangent, out, jvp, rows, n, k, R, st)
   if (np == 2) return CALL(1, 2, false);
   const int lg = pick_log_gl(np, rows);
-  // The fast kernels grow the pooled block one neighbour per step, which suits the small blocks
-  // of p = 2 routers; p = 4/3 pools more positions and its step is dearer, so it stays on the
-  // kernels below, which test every position of the row at once from prefix sums.
-  if (np <= 128 && pc == kP2 && fast_enabled()) {
+  if (np <= 128 && fast_enabled()) {
     const int rc = launch_short_rows_fast(np, lg, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
     if (rc != -2) return rc;
   }

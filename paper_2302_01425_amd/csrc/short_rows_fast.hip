@@ -216,12 +216,13 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void fast_argsort_ke
 }
 
 // ---- the fused operator -------------------------------------------------------------------------
-// reciprocal of a positive float64 to full precision: hardware estimate + two Newton steps
-__device__ __forceinline__ double recip(double c) {
-  double r = __builtin_amdgcn_rcp(c);
-  r = fma(fma(-c, r, 1.0), r, r);
-  r = fma(fma(-c, r, 1.0), r, r);
-  return r;
+// inclusive prefix sum over groups of H consecutive lanes (H <= 8, inside one DPP row); t = lane
+// index inside the group
+template <int H>
+__device__ __forceinline__ void half_scan(double& v, int t) {
+  if constexpr (H >= 2) { const double o = row_shr_f64<1>(v); v = (t >= 1) ? v + o : v; }
+  if constexpr (H >= 4) { const double o = row_shr_f64<2>(v); v = (t >= 2) ? v + o : v; }
+  if constexpr (H >= 8) { const double o = row_shr_f64<4>(v); v = (t >= 4) ? v + o : v; }
 }
 
 // VEC: rows are 16-byte aligned and n % 4 == 0 (float4 loads and stores).
@@ -238,6 +239,7 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   constexpr int NP = C::NP, RS = C::RS;
   constexpr uint32_t IM = C::IM;
   constexpr bool CUBIC = (PC == kP43);
+  constexpr bool CHUNKED = GL >= 4;      // rows with at least 4 lanes also grow the block in chunks
   __shared__ __attribute__((aligned(16))) float lds[C::WPB][C::Arrays][C::RPW * RS];
 
   const int lane = threadIdx.x & (kWave - 1);
@@ -327,14 +329,16 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
       }
       a = grew ? k : a;
       b = grew ? k + 1 : b;
-      double da = dk, db = dk1;          // values at the two ends of the block
       cnt = 2.0;
       m = 1.0;
-      for (;;) {
+      // (1) a few single-neighbour steps: the usual p = 2 block has 2-5 positions
+      constexpr int kSingleSteps = CUBIC ? 0 : 3;
+      bool pending = true;               // some row of the wavefront may still grow
+      for (int step = 0; step < kSingleSteps || !CHUNKED; ++step) {
         const double dj = double(nr) - center, di = double(nl) - center;
         const bool add_r = grew & (b < nn) & P::right_violates(dj, cnt, m, S, R);
         const bool add_l = grew & (a > 1) & P::left_violates(di, cnt, m, S, R);
-        if (!__any(add_r | add_l)) break;
+        if (!__any(add_r | add_l)) { pending = false; break; }
         b += add_r ? 1 : 0;
         a -= add_l ? 1 : 0;
         nr = ls[b < nn ? b : nn - 1];
@@ -344,12 +348,52 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
         if (CUBIC) {
           S.s2 += ar * ar + al * al;
           S.s3 += ar * ar * ar + al * al * al;
-          db = add_r ? dj : db;
-          da = add_l ? di : da;
         }
         cnt = double(b - a + 1);
         m = double(k - a + 1);
       }
+      // (2) larger blocks: every step tests GL/2 positions on each side at once.  The lower half
+      // of the row's lanes takes the positions b+1, b+2, .. and the upper half a-1, a-2, ..; an
+      // exclusive scan of the power sums inside each half gives every lane the block it would
+      // join (all candidates before it included), and the violation tests hold on a prefix of
+      // each half, whose length is read off a ballot.
+      if constexpr (CHUNKED) {
+        constexpr int H = GL / 2;
+        const int t = lr & (H - 1);
+        const bool left = lr >= H;
+        while (pending) {
+          const int q = left ? a - 2 - t : b + t;            // 0-based sorted position
+          const bool ok = grew & (left ? q >= 0 : q < nn);
+          const float v = ls[ok ? q : 0];
+          const double d = ok ? double(v) - center : 0.0;
+          Sums own{d, CUBIC ? d * d : 0.0, CUBIC ? d * d * d : 0.0};
+          Sums pre = own;                                    // inclusive scan over the half
+          half_scan<H>(pre.s1, t);
+          if (CUBIC) { half_scan<H>(pre.s2, t); half_scan<H>(pre.s3, t); }
+          Sums blk{S.s1 + (pre.s1 - own.s1), S.s2 + (pre.s2 - own.s2), S.s3 + (pre.s3 - own.s3)};
+          const double cnt_t = cnt + double(t), m_t = m + (left ? double(t) : 0.0);
+          const bool viol = left ? P::left_violates(d, cnt_t, m_t, blk, R)
+                                 : P::right_violates(d, cnt_t, m_t, blk, R);
+          const unsigned long long bal = __ballot(ok & viol);
+          const uint32_t rowbits = uint32_t(bal >> (lane & ~(GL - 1))) & ((1u << GL) - 1u);
+          // number of leading candidates that join, per side (the tests are monotone)
+          const int n_r = __builtin_ctz(~(rowbits & ((1u << H) - 1u)) | (1u << H));
+          const int n_l = __builtin_ctz(~(rowbits >> H) | (1u << H));
+          if (!__any((n_r | n_l) != 0)) break;
+          const bool take = t < (left ? n_l : n_r);
+          Sums add{take ? own.s1 : 0.0, take ? own.s2 : 0.0, take ? own.s3 : 0.0};
+          S.s1 += group_sum_f64<GL>(add.s1);
+          if (CUBIC) {
+            S.s2 += group_sum_f64<GL>(add.s2);
+            S.s3 += group_sum_f64<GL>(add.s3);
+          }
+          b += n_r;
+          a -= n_l;
+          cnt = double(b - a + 1);
+          m = double(k - a + 1);
+        }
+      }
+      const double da = double(ls[a - 1]) - center, db = double(ls[b - 1]) - center;
       if (MAG) gamma = S.s1 * recip(cnt + R.lambda * m);
       else if (!CUBIC) gamma = (S.s1 - R.lambda * m) * recip(cnt);
       else gamma = P::pooled(cnt, m, S, R, da - R.lambda, db);
@@ -502,7 +546,7 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   TOPK_MARK(5);
 }
 
-template <int GL, int E, bool MAG, bool VEC, bool FULL, int MODE>
+template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE>
 int launch_fast_mode(const float* x, const float* t, float* out, float* jvp, int64_t rows, int n,
                      int k, const Reg& R, hipStream_t st) {
   using C = FastCfg<GL, E>;
@@ -511,28 +555,35 @@ int launch_fast_mode(const float* x, const float* t, float* out, float* jvp, int
   if (blocks > 0x7fffffffLL) return -1;
   dim3 grid((unsigned)blocks), block(C::WPB * kWave);
   const float il = float(R.inv_lambda), i1 = float(R.inv_1pl);
-  hipLaunchKernelGGL((short_rows_fast_kernel<GL, E, MAG, kP2, VEC, FULL, MODE>), grid, block, 0, st,
+  hipLaunchKernelGGL((short_rows_fast_kernel<GL, E, MAG, PC, VEC, FULL, MODE>), grid, block, 0, st,
                      x, t, out, jvp, rows, n, k, R, il, i1);
   return 0;
 }
 
-// only p = 2 is instantiated (p = 4/3 rows use the prefix-sum kernels of short_rows.hip)
+// mask: p = 2 and p = 4/3; magnitude: p = 2
 template <int GL, int E, bool VEC, bool FULL>
 int launch_fast_shape2(bool mag, int pc, const float* x, const float* t, float* out, float* jvp,
                        int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
-  if (pc != kP2) return -2;
   const int mode = (jvp == nullptr) ? 0 : (out == nullptr ? 1 : 2);
-#define TOPK_MODE_CALL(MAGV, M) \
-  return launch_fast_mode<GL, E, MAGV, VEC, FULL, M>(x, t, out, jvp, rows, n, k, R, st)
-  if (!mag) {
-    if (mode == 0) TOPK_MODE_CALL(false, 0);
-    if (mode == 1) TOPK_MODE_CALL(false, 1);
-    TOPK_MODE_CALL(false, 2);
+#define TOPK_MODE_CALL(MAGV, PCV, M) \
+  return launch_fast_mode<GL, E, MAGV, PCV, VEC, FULL, M>(x, t, out, jvp, rows, n, k, R, st)
+  if (!mag && pc == kP2) {
+    if (mode == 0) TOPK_MODE_CALL(false, kP2, 0);
+    if (mode == 1) TOPK_MODE_CALL(false, kP2, 1);
+    TOPK_MODE_CALL(false, kP2, 2);
   }
-  if (mode == 0) TOPK_MODE_CALL(true, 0);
-  if (mode == 1) TOPK_MODE_CALL(true, 1);
-  TOPK_MODE_CALL(true, 2);
+  if (!mag && pc == kP43) {
+    if (mode == 0) TOPK_MODE_CALL(false, kP43, 0);
+    if (mode == 1) TOPK_MODE_CALL(false, kP43, 1);
+    TOPK_MODE_CALL(false, kP43, 2);
+  }
+  if (mag && pc == kP2) {
+    if (mode == 0) TOPK_MODE_CALL(true, kP2, 0);
+    if (mode == 1) TOPK_MODE_CALL(true, kP2, 1);
+    TOPK_MODE_CALL(true, kP2, 2);
+  }
 #undef TOPK_MODE_CALL
+  return -2;
 }
 
 template <int GL, int E, bool VEC>
@@ -557,14 +608,13 @@ int launch_fast_argsort_shape(const float* x, int32_t* perm, int64_t rows, int n
 }  // namespace
 
 // Shapes of the fast kernels: rows of 4..128 padded elements, at most 16 lanes per row (one DPP
-// row), 4..16 elements per lane.  Returns -2 when (np, lg) is not one of them.
+// row), 4 or 8 elements per lane.  Returns -2 when (np, lg) is not one of them.
 #define TOPK_FAST_SHAPE(GL, E) \
   if (np == (GL) * (E) && lg == ilog2(GL)) return vec ? CALL(GL, E, true) : CALL(GL, E, false);
 #define TOPK_FAST_TABLE                                                                      \
-  TOPK_FAST_SHAPE(1, 4) TOPK_FAST_SHAPE(1, 8) TOPK_FAST_SHAPE(2, 4) TOPK_FAST_SHAPE(1, 16)   \
-  TOPK_FAST_SHAPE(2, 8) TOPK_FAST_SHAPE(4, 4) TOPK_FAST_SHAPE(2, 16) TOPK_FAST_SHAPE(4, 8)   \
-  TOPK_FAST_SHAPE(8, 4) TOPK_FAST_SHAPE(4, 16) TOPK_FAST_SHAPE(8, 8) TOPK_FAST_SHAPE(16, 4)  \
-  TOPK_FAST_SHAPE(8, 16) TOPK_FAST_SHAPE(16, 8)
+  TOPK_FAST_SHAPE(1, 4) TOPK_FAST_SHAPE(1, 8) TOPK_FAST_SHAPE(2, 4) TOPK_FAST_SHAPE(2, 8)    \
+  TOPK_FAST_SHAPE(4, 4) TOPK_FAST_SHAPE(4, 8) TOPK_FAST_SHAPE(8, 4) TOPK_FAST_SHAPE(8, 8)    \
+  TOPK_FAST_SHAPE(16, 4) TOPK_FAST_SHAPE(16, 8)
 
 int launch_short_rows_fast(int np, int lg, bool vec, bool mag, int pc, const float* x,
                            const float* tangent, float* out, float* jvp, int64_t rows, int n,
