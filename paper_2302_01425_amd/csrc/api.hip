@@ -3,6 +3,8 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
+#include <cstring>
 
 #include "../../include/sparse_topk.h"
 #include "launch.hpp"
@@ -11,6 +13,7 @@ namespace {
 
 using topk::Reg;
 using topk::RowInfo;
+using topk::RowSel;
 using topk::SortBuffers;
 
 struct Workspace {
@@ -42,8 +45,20 @@ Reg make_reg(double lambda) {
 
 bool is_long(int64_t n) { return n > TOPK_SHORT_ROW_MAX; }
 
+// How rows above TOPK_SHORT_ROW_MAX are handled.  Default: one fused launch up to
+// topk::kMediumRowMax elements, candidate selection + sort of the candidates above.
+// TOPK_LONG_ROWS=select uses the multi-launch selection path for every such row, =sort sorts
+// the rows completely (same results; for tests and comparisons).
+enum LongMode { kAuto, kSelect, kFullSort };
+LongMode long_mode() {
+  const char* e = std::getenv("TOPK_LONG_ROWS");
+  if (e != nullptr && std::strcmp(e, "sort") == 0) return kFullSort;
+  if (e != nullptr && std::strcmp(e, "select") == 0) return kSelect;
+  return kAuto;
+}
+
 struct Layout {
-  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, total;
+  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, bins, tcnt, tabove, sel, total;
 };
 
 Layout layout_for(int64_t rows, int64_t n) {
@@ -58,6 +73,10 @@ Layout layout_for(int64_t rows, int64_t n) {
   L.hist = off; off += align_up(size_t(rows) * 256 * tiles * 4);
   L.dtot = off; off += align_up(size_t(rows) * 256 * 4);
   L.info = off; off += align_up(size_t(rows) * sizeof(RowInfo));
+  L.bins = off; off += align_up(size_t(rows) * topk::kSelBins * 4);
+  L.tcnt = off; off += align_up(size_t(rows) * tiles * 4);
+  L.tabove = off; off += align_up(size_t(rows) * tiles * 4);
+  L.sel = off; off += align_up(size_t(rows) * sizeof(RowSel));
   L.total = off;
   return L;
 }
@@ -73,6 +92,10 @@ int carve(int64_t rows, int64_t n, SortBuffers* B) {
   B->hist = reinterpret_cast<uint32_t*>(base + L.hist);
   B->dtot = reinterpret_cast<uint32_t*>(base + L.dtot);
   B->info = reinterpret_cast<RowInfo*>(base + L.info);
+  B->bins = reinterpret_cast<uint32_t*>(base + L.bins);
+  B->tcnt = reinterpret_cast<uint32_t*>(base + L.tcnt);
+  B->tabove = reinterpret_cast<uint32_t*>(base + L.tabove);
+  B->sel = reinterpret_cast<RowSel*>(base + L.sel);
   return TOPK_OK;
 }
 
@@ -108,8 +131,22 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   SortBuffers B;
   rc = carve(rows, n, &B);
   if (rc != TOPK_OK) return rc;
-  if (topk::launch_segmented_sort(mag, x, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
-  if (topk::launch_long_tail(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
+  const LongMode mode = long_mode();
+  if (mode == kAuto && n <= topk::kMediumRowMax) {
+    if (topk::launch_medium_rows(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
+                                 need_jvp ? jvp : nullptr, rows, n, k, R, st) != 0)
+      return TOPK_ERR_INVALID;
+    return finish();
+  }
+  // k = 0 and k = n pool nothing and read no sorted value: no sort at all
+  const bool trivial = (k == 0 || k == n);
+  const bool selected = !trivial && mode != kFullSort;
+  if (selected) {
+    if (topk::launch_candidate_sort(mag, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
+  } else if (!trivial) {
+    if (topk::launch_segmented_sort(mag, x, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
+  }
+  if (topk::launch_long_tail(mag, pc, selected, B, x, need_jvp ? tangent : nullptr, out,
                              need_jvp ? jvp : nullptr, rows, n, k, R, st) != 0)
     return TOPK_ERR_INVALID;
   return finish();

@@ -20,6 +20,21 @@ struct RowInfo {
   float hi_incl, lo_incl;
 };
 
+// Per-row result of the candidate selection of the long-row path.  Only the elements whose
+// descending-order key lies in [klo, khi] (a value window around s_k and s_{k+1} that contains
+// every position able to pool) are sorted: cn of them, and `above` elements of the row have a
+// smaller key (a larger value), so sorted position q (1-based) of the candidate list is sorted
+// position above + q of the row.
+struct RowSel {
+  uint32_t klo, khi;
+  uint32_t cn;
+  uint32_t pad;
+  int64_t above;
+};
+
+constexpr int kSelBits = 12;              // leading key bits of the selection histogram
+constexpr int kSelBins = 1 << kSelBits;
+
 // Device scratch of the long-row path (all carved out of the caller's workspace).
 struct SortBuffers {
   uint32_t* keys_a;   // [rows*n] sorted keys end here
@@ -29,6 +44,10 @@ struct SortBuffers {
   uint32_t* hist;     // [rows][256][tiles]
   uint32_t* dtot;     // [rows][256]
   RowInfo* info;      // [rows]
+  uint32_t* bins;     // [rows][kSelBins] histogram of the leading key bits
+  uint32_t* tcnt;     // [rows][tiles] candidates per tile
+  uint32_t* tabove;   // [rows][tiles] elements above the candidate window per tile
+  RowSel* sel;        // [rows]
 };
 
 // Rows of up to 1024 elements, one row per (part of a) wavefront.  tangent/jvp may be null
@@ -49,8 +68,25 @@ int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t*
 int radix_tiles(int64_t n);
 int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, const SortBuffers& B,
                           hipStream_t st);
-int launch_long_tail(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
-                     float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
-                     hipStream_t st);
+// selected: the sorted arrays hold the candidate lists of launch_candidate_sort (B.sel says how
+// many and where they sit in the row); otherwise the fully sorted rows.
+int launch_long_tail(bool mag, int pc, bool selected, const SortBuffers& B, const float* x,
+                     const float* tangent, float* out, float* jvp, int64_t rows, int64_t n,
+                     int64_t k, const Reg& R, hipStream_t st);
+
+// Rows of up to kMediumRowMax elements: the whole operator in one launch, one workgroup per row
+// (selection of the candidates, their sort, the solve and the outputs); scratch in B.keys_* and
+// B.idx_* (row stride n).  Any 0 <= k <= n.
+constexpr int64_t kMediumRowMax = 131072;
+int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
+                       float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
+                       hipStream_t st);
+
+// Long rows without a full sort (0 < k < n): histogram of the leading key bits -> key window
+// around positions k, k+1 that holds every element able to pool -> ordered compaction of those
+// candidates -> segmented radix sort of the candidates only.  Result as for
+// launch_segmented_sort, restricted to the candidates (see RowSel).
+int launch_candidate_sort(bool mag, const float* x, int64_t rows, int64_t n, int64_t k,
+                          const Reg& R, const SortBuffers& B, hipStream_t st);
 
 }  // namespace topk

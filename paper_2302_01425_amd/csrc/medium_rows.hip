@@ -1,0 +1,373 @@
+// Medium rows (1024 < n <= 131072): the whole operator for one row in ONE workgroup of 1024
+// threads, one launch.
+//
+//   1. histogram of the leading key bits of the row (LDS, four lane-rotated copies per bin so
+//      that skewed exponents do not serialise the atomics)
+//   2. the bins of sorted positions k and k+1 give the key window that holds every element able
+//      to pool (radix.hpp: key_window)
+//   3. ordered compaction of those candidates (key, index payload) into the row's scratch
+//   4. stable LSD radix sort of the candidates on (key - klo), 8 bits per pass, only as many
+//      passes as the window has significant bits; the candidates come in index order, so equal
+//      values keep ascending index
+//   5. isotonic solve on the sorted candidates (long_solve.hpp)
+//   6. dense pass over the row for everything outside the block's value window, and the window's
+//      positions through sigma
+//
+// Steps 3..5 go through global scratch that only this workgroup touches (L2-resident at these
+// sizes); the row itself is read three times, the second and third time from L2.
+#include <hip/hip_runtime.h>
+
+#ifdef TOPK_PHASE_TRACE
+// Development aid (not compiled into the library): wall-clock stamps of the steps of a workgroup.
+__device__ unsigned long long g_med_trace[256][16];
+#define TOPK_MED_MARK(i)                                                               \
+  do {                                                                                 \
+    if (blockIdx.x < 256 && threadIdx.x == 0) g_med_trace[blockIdx.x][i] = wall_clock64(); \
+  } while (0)
+#define TOPK_SOLVE_MARK(i) TOPK_MED_MARK(i)
+extern "C" int topk_debug_read_med_trace(unsigned long long* host_out) {
+  return int(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_med_trace), sizeof(g_med_trace)));
+}
+#else
+#define TOPK_MED_MARK(i) do { } while (0)
+#endif
+
+#include "common.hpp"
+#include "launch.hpp"
+#include "long_solve.hpp"
+#include "pooling.hpp"
+#include "radix.hpp"
+
+namespace topk {
+namespace {
+
+constexpr int kMT = 1024;                  // threads
+constexpr int kMW = kMT / kWave;           // wavefronts
+constexpr int kMItems = 8;                 // elements per thread and tile of a sorting pass
+constexpr int kCItems = 16;                // elements per thread and tile of the compaction
+constexpr int kCTile = kMT * kCItems;
+constexpr int kLdsCap = 2048;              // candidate lists up to this length are sorted in LDS
+constexpr int kCopies = 4;
+constexpr int kSelShift = 32 - kSelBits;
+
+struct MedShared {
+  union {
+    uint32_t hist[kSelBins * kCopies];     // steps 1-2
+    struct {
+      uint32_t cnt[kMW][kRadix];           // per-wave digit counts, then per-wave offsets
+      uint32_t base[kRadix];               // running start of every digit in the output
+      uint32_t gofs[kRadix];               // start of the current tile's items of every digit
+      uint32_t lk[2][kLdsCap];             // short candidate lists: keys, ping-pong
+      uint32_t li[2][kLdsCap];             //                        index payloads
+    } sort;                                // steps 3-6
+  } u;
+  SolveShared<kMT> solve;
+  uint32_t wave_a[kMW], wave_b[kMW];
+  uint32_t found[2];
+};
+
+// exclusive scan of one value per thread over the workgroup; *total gets the sum
+__device__ __forceinline__ uint32_t med_exclusive_scan(uint32_t v, uint32_t* wave_tot,
+                                                       uint32_t* total) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  uint32_t inc = v;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t o = __shfl_up(inc, off, kWave);
+    if (lane >= off) inc += o;
+  }
+  __syncthreads();
+  if (lane == kWave - 1) wave_tot[w] = inc;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int q = 0; q < kMW; ++q) {
+    const uint32_t t = wave_tot[q];
+    if (q < w) before += t;
+    all += t;
+  }
+  if (total) *total = all;
+  return before + inc - v;
+}
+
+// One LSD pass over the cn candidates: (kin, iin) -> (kout, iout), stable, by the 8-bit digit of
+// (key - klo) at `shift`.  Tiles of ni*1024 elements; wave w owns elements w*ni*64 .. of a tile.
+__device__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t* kout,
+                              uint32_t* iout, uint32_t cn, uint32_t klo, int shift, int ni,
+                              MedShared& sm) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const uint32_t tile_elems = uint32_t(ni) * kMT;
+  const uint32_t wave_elems = uint32_t(ni) * kWave;
+  // several tiles: digit totals of the whole list first -> start of every digit (a single tile
+  // gets them from its own ranking below)
+  const bool single = cn <= tile_elems;
+  if (!single) {
+    for (int i = threadIdx.x; i < kMW * kRadix; i += kMT) (&sm.u.sort.cnt[0][0])[i] = 0;
+    __syncthreads();
+    for (uint32_t tile_first = 0; tile_first < cn; tile_first += tile_elems) {
+#pragma unroll
+      for (int i = 0; i < kMItems; ++i) {
+        if (i < ni) {
+          const uint32_t e = tile_first + w * wave_elems + i * kWave + lane;
+          const bool valid = e < cn;
+          const uint32_t key = valid ? kin[e] : 0u;
+          count_digit(sm.u.sort.cnt[w], ((key - klo) >> shift) & (kRadix - 1), valid, lane);
+        }
+      }
+    }
+    __syncthreads();
+    uint32_t tot = 0;
+    if (threadIdx.x < kRadix) {
+#pragma unroll
+      for (int q = 0; q < kMW; ++q) tot += sm.u.sort.cnt[q][threadIdx.x];
+    }
+    const uint32_t ex = med_exclusive_scan(tot, sm.wave_a, nullptr);
+    if (threadIdx.x < kRadix) sm.u.sort.base[threadIdx.x] = ex;
+  }
+  // tile by tile: rank inside the wavefront, offsets of the wavefronts, scatter
+  for (uint32_t tile_first = 0; tile_first < cn; tile_first += tile_elems) {
+    __syncthreads();                       // previous users of cnt / gofs are done
+    for (int i = threadIdx.x; i < kMW * kRadix; i += kMT) (&sm.u.sort.cnt[0][0])[i] = 0;
+    __syncthreads();
+    uint32_t key[kMItems], idx[kMItems], rank[kMItems];
+#pragma unroll
+    for (int i = 0; i < kMItems; ++i) {
+      if (i < ni) {
+        const uint32_t e = tile_first + w * wave_elems + i * kWave + lane;
+        const bool valid = e < cn;
+        key[i] = valid ? kin[e] : 0u;
+        idx[i] = valid ? iin[e] : 0u;
+        const uint32_t d = ((key[i] - klo) >> shift) & (kRadix - 1);
+        const unsigned long long peers = match_digit(d, __ballot(valid));
+        const unsigned long long lower = peers & lanemask_lt();
+        uint32_t pre = 0;
+        if (valid) {
+          pre = sm.u.sort.cnt[w][d];
+          if (lower == 0) sm.u.sort.cnt[w][d] = pre + __popcll(peers);
+        }
+        rank[i] = pre + __popcll(lower);
+      }
+    }
+    __syncthreads();
+    uint32_t run = 0;
+    if (threadIdx.x < kRadix) {
+#pragma unroll
+      for (int q = 0; q < kMW; ++q) {
+        const uint32_t c = sm.u.sort.cnt[q][threadIdx.x];
+        sm.u.sort.cnt[q][threadIdx.x] = run;
+        run += c;
+      }
+    }
+    if (single) {
+      const uint32_t ex = med_exclusive_scan(run, sm.wave_a, nullptr);
+      if (threadIdx.x < kRadix) sm.u.sort.gofs[threadIdx.x] = ex;
+    } else if (threadIdx.x < kRadix) {
+      const uint32_t b = sm.u.sort.base[threadIdx.x];
+      sm.u.sort.gofs[threadIdx.x] = b;
+      sm.u.sort.base[threadIdx.x] = b + run;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kMItems; ++i) {
+      if (i < ni) {
+        const uint32_t e = tile_first + w * wave_elems + i * kWave + lane;
+        if (e < cn) {
+          const uint32_t d = ((key[i] - klo) >> shift) & (kRadix - 1);
+          const uint32_t dst = sm.u.sort.gofs[d] + sm.u.sort.cnt[w][d] + rank[i];
+          kout[dst] = key[i];
+          iout[dst] = idx[i];
+        }
+      }
+    }
+  }
+  __syncthreads();          // workgroup-scope release/acquire: the next pass reads what this one wrote
+}
+
+template <bool MAG, int PC>
+__global__ __launch_bounds__(kMT) void medium_rows_kernel(
+    const float* __restrict__ x_all, const float* __restrict__ tangent_all,
+    float* __restrict__ out_all, float* __restrict__ jvp_all, uint32_t* keys_a, uint32_t* idx_a,
+    uint32_t* keys_b, uint32_t* idx_b, int n, int k_row, Reg R) {
+  __shared__ MedShared sm;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t base = int64_t(blockIdx.x) * n;
+  const float* x = x_all + base;
+  const float* tangent = tangent_all != nullptr ? tangent_all + base : nullptr;
+  float* out = out_all != nullptr ? out_all + base : nullptr;
+  float* jvp = jvp_all != nullptr ? jvp_all + base : nullptr;
+  uint32_t* ka = keys_a + base;
+  uint32_t* ia = idx_a + base;
+  uint32_t* kb = keys_b + base;
+  uint32_t* ib = idx_b + base;
+
+  TOPK_MED_MARK(0);
+  uint32_t cn = 0;
+  int k = k_row;
+  const uint32_t* skeys = ka;
+  const uint32_t* sidx = ia;
+  if (k_row >= 1 && k_row < n) {
+    // ---- 1. histogram of the leading key bits ---------------------------------------------------
+    for (int i = threadIdx.x; i < kSelBins * kCopies; i += kMT) sm.u.hist[i] = 0;
+    __syncthreads();
+    for (int e0 = threadIdx.x; e0 < n; e0 += 16 * kMT) {
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = (e0 + i * kMT < n) ? x[e0 + i * kMT] : 0.0f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint32_t bin = first_key<MAG>(v[i]) >> kSelShift;
+        if (e0 + i * kMT < n) atomicAdd(&sm.u.hist[bin * kCopies + (lane & (kCopies - 1))], 1u);
+      }
+    }
+    __syncthreads();
+    TOPK_MED_MARK(1);
+    // ---- 2. bins of positions k and k+1, key window ---------------------------------------------
+    constexpr int kPerThread = kSelBins / kMT;
+    uint32_t c[kPerThread], mine = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const uint32_t* h = &sm.u.hist[(threadIdx.x * kPerThread + i) * kCopies];
+      c[i] = h[0] + h[1] + h[2] + h[3];
+      mine += c[i];
+    }
+    uint32_t run = med_exclusive_scan(mine, sm.wave_a, nullptr);
+    const uint32_t q0 = uint32_t(k_row), q1 = uint32_t(k_row) + 1u;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const uint32_t next = run + c[i];
+      if (run < q0 && q0 <= next) sm.found[0] = threadIdx.x * kPerThread + i;
+      if (run < q1 && q1 <= next) sm.found[1] = threadIdx.x * kPerThread + i;
+      run = next;
+    }
+    __syncthreads();
+    uint32_t klo, khi;
+    key_window<MAG>(sm.found[0], sm.found[1], R, &klo, &khi);
+    __syncthreads();                       // the histogram's memory is reused below
+
+    TOPK_MED_MARK(2);
+    // ---- 3. ordered compaction of the candidates into (ka, ia) ----------------------------------
+    uint32_t above = 0;                    // per wavefront, summed at the end
+    for (int tile_first = 0; tile_first < n; tile_first += kCTile) {
+      uint32_t key[kCItems], idx[kCItems], pos[kCItems];
+      float xv[kCItems];
+      uint32_t ncand = 0;
+#pragma unroll
+      for (int i = 0; i < kCItems; ++i) {
+        const int e = tile_first + w * (kCItems * kWave) + i * kWave + lane;
+        xv[i] = e < n ? x[e] : 0.0f;
+      }
+#pragma unroll
+      for (int i = 0; i < kCItems; ++i) {
+        const int e = tile_first + w * (kCItems * kWave) + i * kWave + lane;
+        const bool valid = e < n;
+        key[i] = 0xffffffffu;
+        idx[i] = 0;
+        if (valid) {
+          const float v = xv[i];
+          key[i] = first_key<MAG>(v);
+          idx[i] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(v) >> 31)) : uint32_t(e);
+        }
+        const bool cand = valid && key[i] >= klo && key[i] <= khi;
+        const unsigned long long cm = __ballot(cand);
+        above += __popcll(__ballot(valid && key[i] < klo));
+        pos[i] = cand ? ncand + __popcll(cm & lanemask_lt()) : 0xffffffffu;
+        ncand += __popcll(cm);
+      }
+      __syncthreads();                     // wave_a of the previous tile has been read
+      if (lane == 0) sm.wave_a[w] = ncand;
+      __syncthreads();
+      uint32_t before = 0, total = 0;
+#pragma unroll
+      for (int q = 0; q < kMW; ++q) {
+        const uint32_t t = sm.wave_a[q];
+        if (q < w) before += t;
+        total += t;
+      }
+#pragma unroll
+      for (int i = 0; i < kCItems; ++i) {
+        if (pos[i] != 0xffffffffu) {
+          ka[cn + before + pos[i]] = key[i];
+          ia[cn + before + pos[i]] = idx[i];
+        }
+      }
+      cn += total;
+    }
+    if (lane == 0) sm.wave_b[w] = above;
+    __syncthreads();
+    uint32_t above_all = 0;
+#pragma unroll
+    for (int q = 0; q < kMW; ++q) above_all += sm.wave_b[q];
+    k = k_row - int(above_all);
+
+    TOPK_MED_MARK(3);
+    // ---- 4. sort the candidates -------------------------------------------------------------------
+    const uint32_t span = khi - klo;
+    const int nbits = span == 0 ? 0 : 32 - __clz(int(span));
+    int ni = int((cn + kMT - 1) / kMT);
+    ni = ni > kMItems ? kMItems : ni;
+    // passes alternate between two buffers: in LDS for short lists, else the row's scratch
+    const bool in_lds = cn <= uint32_t(kLdsCap);
+    uint32_t* k0 = in_lds ? sm.u.sort.lk[0] : kb;
+    uint32_t* i0 = in_lds ? sm.u.sort.li[0] : ib;
+    uint32_t* k1 = in_lds ? sm.u.sort.lk[1] : ka;
+    uint32_t* i1 = in_lds ? sm.u.sort.li[1] : ia;
+    const uint32_t* kin = ka;
+    const uint32_t* iin = ia;
+    bool even = true;
+    for (int shift = 0; shift < nbits; shift += 8) {
+      uint32_t* kout = even ? k0 : k1;
+      uint32_t* iout = even ? i0 : i1;
+      med_sort_pass(kin, iin, kout, iout, cn, klo, shift, ni, sm);
+      kin = kout;
+      iin = iout;
+      even = !even;
+    }
+    skeys = kin;
+    sidx = iin;
+  }
+
+  TOPK_MED_MARK(4);
+  // ---- 5. solve ---------------------------------------------------------------------------------------
+  const int64_t n_sorted = (k_row >= 1 && k_row < n) ? int64_t(cn) : int64_t(n);
+  const RowInfo ri = RowSolver<kMT>::solve<MAG, PC>(skeys, sidx, tangent, n_sorted, int64_t(k), R,
+                                                    sm.solve);
+
+  TOPK_MED_MARK(5);
+  // ---- 6. outputs ----------------------------------------------------------------------------------
+  const float inv_1pl = float(R.inv_1pl);
+  for (int e0 = threadIdx.x; e0 < n; e0 += 8 * kMT) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (e0 + i * kMT < n) ? x[e0 + i * kMT] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (e0 + i * kMT < n)
+        emit_dense_element<MAG>(ri, v[i], int64_t(e0 + i * kMT), tangent, out, jvp, inv_1pl);
+  }
+  for (int64_t pos1 = ri.wa + threadIdx.x; pos1 <= ri.wb; pos1 += kMT)
+    emit_window_position<MAG, PC>(ri, pos1, key_to_float(skeys[pos1 - 1]), sidx[pos1 - 1], tangent,
+                                  out, jvp, R);
+  TOPK_MED_MARK(6);
+}
+
+template <bool MAG, int PC>
+void launch(const SortBuffers& B, const float* x, const float* tangent, float* out, float* jvp,
+            int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
+  hipLaunchKernelGGL((medium_rows_kernel<MAG, PC>), dim3(unsigned(rows)), dim3(kMT), 0, st, x,
+                     tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R);
+}
+
+}  // namespace
+
+int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
+                       float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
+                       hipStream_t st) {
+  if (n > kMediumRowMax || rows > 0x7fffffffLL) return -1;
+  if (!mag && pc == kP2) launch<false, kP2>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
+  else if (!mag && pc == kP43) launch<false, kP43>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
+  else if (mag && pc == kP2) launch<true, kP2>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
+  else return -1;
+  return 0;
+}
+
+}  // namespace topk

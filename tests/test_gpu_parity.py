@@ -125,6 +125,66 @@ def test_long_rows(gpu, oracle, rows, n):
     run_case(gpu, oracle, "mask", x, t, n // 3, P43, 50.0, check_perm=False)
 
 
+def test_long_rows_kinks_ties_and_full_sort_agreement(gpu, oracle, monkeypatch):
+    """Long rows whose block boundary falls inside runs of equal values (the position of each tied
+    index decides its JVP), and agreement of the candidate-selection path with the full sort."""
+    r = np.random.default_rng(5)
+    n = 9000
+    heads = [([2.0, 2.0, 0.0, -1.0], 2, 0.5), ([3.0, 1.5, 1.0, 0.0], 2, 0.5),
+             ([1.0, 1.0, 1.0, 1.0], 2, 1.0), ([2.0] + [1.0] * 8 + [-5.0], 2, 2.0)]
+    for head, k, lam in heads:
+        x = (-50.0 - r.random(size=(2, n))).astype(np.float32)
+        pos = r.permutation(n)[: len(head)]
+        x[0, np.sort(pos)] = head                       # in order
+        x[1, pos] = head                                # scattered: ties meet in another index order
+        t = r.normal(size=(2, n)).astype(np.float32)
+        for p in (P2, P43):
+            run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
+        run_case(gpu, oracle, "mag", x + np.float32(50.0), t, k, P2, lam, check_perm=False)
+    # quantised values: every boundary is a tie; both paths must give identical bits
+    x = (np.round(r.normal(size=(3, 20000)) * 8) / 8).astype(np.float32)
+    t = r.normal(size=x.shape).astype(np.float32)
+    xd, td = dev(x), dev(t)
+    for op, p, k, lam in [("mask", P2, 500, 0.3), ("mask", P43, 3000, 1.0), ("mag", P2, 7000, 0.2),
+                          ("mask", P2, 19999, 100.0), ("mask", P2, 1, 1e-3)]:
+        run_case(gpu, oracle, op, x, t, k, p, lam, check_perm=False)
+        jvpf = gpu.topk_mask_jvp if op == "mask" else gpu.topkmag_jvp
+        o_def, j_def = (host(a) for a in jvpf(xd, td, k, p, lam))
+        for mode in ("select", "sort"):
+            monkeypatch.setenv("TOPK_LONG_ROWS", mode)
+            o_alt, j_alt = (host(a) for a in jvpf(xd, td, k, p, lam))
+            monkeypatch.delenv("TOPK_LONG_ROWS")
+            assert np.array_equal(o_def, o_alt) and np.array_equal(j_def, j_alt), (mode, op, p, k, lam)
+
+
+@pytest.mark.parametrize("mode", ["select", "sort"])
+def test_long_rows_multi_launch_paths(gpu, oracle, monkeypatch, mode):
+    """The multi-launch paths (candidate selection + sort of the candidates; full sort), which by
+    default only rows above 131072 elements take, on sizes the oracle finishes quickly."""
+    monkeypatch.setenv("TOPK_LONG_ROWS", mode)
+    r = np.random.default_rng(11)
+    for rows, n in [(3, 3000), (2, 4097), (1, 70001)]:
+        x = r.normal(size=(rows, n)).astype(np.float32)
+        x[-1, :] = np.round(x[-1, :] * 4) / 4
+        t = r.normal(size=(rows, n)).astype(np.float32)
+        for p, k, lam in [(P2, 1, 0.1), (P2, n // 10, 0.01), (P43, n // 2, 1.0), (P2, n - 1, 0.1),
+                          (P43, n // 3, 50.0)]:
+            run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
+        for k in (0, n // 10, n):
+            run_case(gpu, oracle, "mag", x * np.float32(0.02), t, k, P2, 0.05, check_perm=False)
+
+
+def test_rows_above_the_fused_kernel_limit(gpu, oracle):
+    r = np.random.default_rng(12)
+    n = 200000
+    x = r.normal(size=(2, n)).astype(np.float32)
+    x[1] = np.round(x[1] * 16) / 16
+    t = r.normal(size=(2, n)).astype(np.float32)
+    run_case(gpu, oracle, "mask", x, t, n // 20, P2, 0.05, check_perm=False)
+    run_case(gpu, oracle, "mask", x, t, n // 3, P43, 2.0, check_perm=False)
+    run_case(gpu, oracle, "mag", x, t, n // 10, P2, 0.01, check_perm=False)
+
+
 # ---- paper examples through the GPU path ----------------------------------------------------------
 def test_fig1_points(gpu, oracle):
     for lam in (0.25, 1.0):
