@@ -58,7 +58,7 @@ LongMode long_mode() {
 }
 
 struct Layout {
-  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, bins, tcnt, tabove, sel, total;
+  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, bins, bins2, tcnt, tabove, toff, sel, total;
 };
 
 Layout layout_for(int64_t rows, int64_t n) {
@@ -73,9 +73,11 @@ Layout layout_for(int64_t rows, int64_t n) {
   L.hist = off; off += align_up(size_t(rows) * 256 * tiles * 4);
   L.dtot = off; off += align_up(size_t(rows) * 256 * 4);
   L.info = off; off += align_up(size_t(rows) * sizeof(RowInfo));
-  L.bins = off; off += align_up(size_t(rows) * topk::kSelBins * 4);
+  L.bins = off; off += size_t(rows) * topk::sel_global_copies(rows) * topk::kSelBins * 4;
+  L.bins2 = off; off += align_up(size_t(rows) * 2 * topk::kSelBins * 4);
   L.tcnt = off; off += align_up(size_t(rows) * tiles * 4);
   L.tabove = off; off += align_up(size_t(rows) * tiles * 4);
+  L.toff = off; off += align_up(size_t(rows) * tiles * 4);
   L.sel = off; off += align_up(size_t(rows) * sizeof(RowSel));
   L.total = off;
   return L;
@@ -93,8 +95,10 @@ int carve(int64_t rows, int64_t n, SortBuffers* B) {
   B->dtot = reinterpret_cast<uint32_t*>(base + L.dtot);
   B->info = reinterpret_cast<RowInfo*>(base + L.info);
   B->bins = reinterpret_cast<uint32_t*>(base + L.bins);
+  B->bins2 = reinterpret_cast<uint32_t*>(base + L.bins2);
   B->tcnt = reinterpret_cast<uint32_t*>(base + L.tcnt);
   B->tabove = reinterpret_cast<uint32_t*>(base + L.tabove);
+  B->toff = reinterpret_cast<uint32_t*>(base + L.toff);
   B->sel = reinterpret_cast<RowSel*>(base + L.sel);
   return TOPK_OK;
 }
@@ -142,7 +146,10 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   const bool trivial = (k == 0 || k == n);
   const bool selected = !trivial && mode != kFullSort;
   if (selected) {
-    if (topk::launch_candidate_sort(mag, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
+    if (topk::launch_candidate_lists(mag, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
+    if (topk::launch_finish(mag, pc, B, need_jvp ? tangent : nullptr, rows, n, k, R, st) != 0)
+      return TOPK_ERR_INVALID;
+    if (topk::launch_long_list_sort(mag, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
   } else if (!trivial) {
     if (topk::launch_segmented_sort(mag, x, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
   }

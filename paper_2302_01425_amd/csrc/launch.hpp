@@ -18,6 +18,8 @@ struct RowInfo {
   int64_t wa, wb;
   double gamma, center, dgamma;
   float hi_incl, lo_incl;
+  int32_t src;      // which pair of scratch arrays holds the sorted list: 0 = "a", 1 = "b"
+  int32_t pad;
 };
 
 // Per-row result of the candidate selection of the long-row path.  Only the elements whose
@@ -30,6 +32,10 @@ struct RowSel {
   uint32_t cn;
   uint32_t pad;
   int64_t above;
+  // first selection level: histogram bins of sorted positions k and k+1, and the 1-based ranks
+  // of those positions inside their bins
+  uint32_t bin_k, bin_k1;
+  uint32_t rank_k, rank_k1;
 };
 
 constexpr int kSelBits = 12;              // leading key bits of the selection histogram
@@ -44,9 +50,12 @@ struct SortBuffers {
   uint32_t* hist;     // [rows][256][tiles]
   uint32_t* dtot;     // [rows][256]
   RowInfo* info;      // [rows]
-  uint32_t* bins;     // [rows][kSelBins] histogram of the leading key bits
+  uint32_t* bins;     // [rows][copies][kSelBins] histogram of the leading key bits
+  uint32_t* bins2;    // [rows][2][kSelBins] the next kSelBits key bits inside the bins of k and k+1
+                      // (directly behind `bins`: one fill zeroes both)
   uint32_t* tcnt;     // [rows][tiles] candidates per tile
   uint32_t* tabove;   // [rows][tiles] elements above the candidate window per tile
+  uint32_t* toff;     // [rows][tiles] start of the tile's candidates in the row's dense list
   RowSel* sel;        // [rows]
 };
 
@@ -66,10 +75,17 @@ int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t*
 
 // Long rows: segmented radix sort (result in B.keys_a / B.idx_a), then solve + scatter.
 int radix_tiles(int64_t n);
+// copies of a row's selection histogram in B.bins: [rows][copies][kSelBins]
+int sel_global_copies(int64_t rows);
 int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, const SortBuffers& B,
                           hipStream_t st);
-// selected: the sorted arrays hold the candidate lists of launch_candidate_sort (B.sel says how
-// many and where they sit in the row); otherwise the fully sorted rows.
+// Candidate lists of up to kFinishMax elements are sorted and solved by one workgroup
+// (launch_finish); longer ones by the passes of launch_long_list_sort and the solve of
+// launch_long_tail.  Every kernel of either route skips the rows of the other.
+constexpr int64_t kFinishMax = 131072;
+
+// selected: B.sel describes candidate lists (see RowSel), and rows whose list is at most
+// kFinishMax long already have their RowInfo; otherwise the "a" arrays hold fully sorted rows.
 int launch_long_tail(bool mag, int pc, bool selected, const SortBuffers& B, const float* x,
                      const float* tangent, float* out, float* jvp, int64_t rows, int64_t n,
                      int64_t k, const Reg& R, hipStream_t st);
@@ -82,11 +98,15 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
                        float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
                        hipStream_t st);
 
-// Long rows without a full sort (0 < k < n): histogram of the leading key bits -> key window
-// around positions k, k+1 that holds every element able to pool -> ordered compaction of those
-// candidates -> segmented radix sort of the candidates only.  Result as for
-// launch_segmented_sort, restricted to the candidates (see RowSel).
-int launch_candidate_sort(bool mag, const float* x, int64_t rows, int64_t n, int64_t k,
-                          const Reg& R, const SortBuffers& B, hipStream_t st);
+// Long rows without a full sort (0 < k < n): two histogram levels of the leading key bits -> key
+// window around positions k, k+1 that holds every element able to pool -> those candidates, in
+// index order, as a dense list per row in the "a" arrays; B.sel[row] = {window, length, above}.
+int launch_candidate_lists(bool mag, const float* x, int64_t rows, int64_t n, int64_t k,
+                           const Reg& R, const SortBuffers& B, hipStream_t st);
+// Lists of up to kFinishMax candidates: sort + solve by one workgroup per row -> B.info[row].
+int launch_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, int64_t rows,
+                  int64_t n, int64_t k, const Reg& R, hipStream_t st);
+// Longer lists: four radix passes, sorted lists end in the "a" arrays.
+int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& B, hipStream_t st);
 
 }  // namespace topk

@@ -6,6 +6,20 @@
 //              (centred on s_k for the mask); writes (a, b, gamma, d gamma) per row.
 //   fill     : dense zero fill of the outputs (everything below the block is exactly 0).
 //   epilogue : positions 1..b only: y (and dy) from (a, b, gamma), scattered through sigma.
+#include <hip/hip_runtime.h>
+
+#ifdef TOPK_PHASE_TRACE
+// Development aid (not compiled into the library): wall-clock stamps of the steps of the solve.
+__device__ unsigned long long g_long_trace[64][16];
+#define TOPK_SOLVE_MARK(i)                                                              \
+  do {                                                                                  \
+    if (blockIdx.x < 64 && threadIdx.x == 0) g_long_trace[blockIdx.x][i] = wall_clock64(); \
+  } while (0)
+extern "C" int topk_debug_read_long_trace(unsigned long long* host_out) {
+  return int(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_long_trace), sizeof(g_long_trace)));
+}
+#endif
+
 #include "common.hpp"
 #include "pooling.hpp"
 #include "launch.hpp"
@@ -15,14 +29,15 @@ namespace topk {
 namespace {
 
 constexpr int kThreads = 256;
-using Solver = RowSolver<kThreads>;
+constexpr int kSolveThreads = 1024;
+using Solver = RowSolver<kSolveThreads>;
 
 template <bool MAG, int PC>
-__global__ __launch_bounds__(kThreads) void long_solve_kernel(
+__global__ __launch_bounds__(kSolveThreads) void long_solve_kernel(
     const uint32_t* __restrict__ skeys_all, const uint32_t* __restrict__ sidx_all,
     const float* __restrict__ tangent_all, RowInfo* __restrict__ info,
     const RowSel* __restrict__ sel, int64_t row_len, int64_t k_row, Reg R) {
-  __shared__ SolveShared<kThreads> sm;
+  __shared__ SolveShared<kSolveThreads> sm;
   const int64_t row = blockIdx.x;
   // With a candidate list the sorted arrays hold sorted positions above+1 .. above+cn of the
   // row; all positions below are relative to that list (it contains positions k and k+1 and
@@ -31,11 +46,14 @@ __global__ __launch_bounds__(kThreads) void long_solve_kernel(
   if (sel != nullptr) {
     n = int64_t(sel[row].cn);
     k = k_row - sel[row].above;
+    if (n <= kFinishMax) return;          // solved together with the sort of its short list
   }
+  TOPK_SOLVE_MARK(0);
   const RowInfo ri = Solver::solve<MAG, PC>(
       skeys_all + row * row_len, sidx_all + row * row_len,
       tangent_all != nullptr ? tangent_all + row * row_len : nullptr, n, k, R, sm);
   if (threadIdx.x == 0) info[row] = ri;
+  TOPK_SOLVE_MARK(6);
 }
 
 // Dense pass in original order: everything whose value lies outside the block's value window.
@@ -64,7 +82,8 @@ __global__ __launch_bounds__(kThreads) void long_dense_kernel(
 // Sorted positions wa..wb of every row: y and dy from (a, b, gamma), scattered through sigma.
 template <bool MAG, int PC>
 __global__ __launch_bounds__(kThreads) void long_window_kernel(
-    const uint32_t* __restrict__ skeys_all, const uint32_t* __restrict__ sidx_all,
+    const uint32_t* __restrict__ keys_a, const uint32_t* __restrict__ idx_a,
+    const uint32_t* __restrict__ keys_b, const uint32_t* __restrict__ idx_b,
     const float* __restrict__ tangent_all, const RowInfo* __restrict__ info,
     float* __restrict__ out_all, float* __restrict__ jvp_all, int64_t n, int blocks_per_row,
     Reg R) {
@@ -72,6 +91,8 @@ __global__ __launch_bounds__(kThreads) void long_window_kernel(
   const int64_t part = blockIdx.x % blocks_per_row;
   const RowInfo ri = info[row];
   const int64_t base = row * n;
+  const uint32_t* skeys_all = ri.src == 0 ? keys_a : keys_b;
+  const uint32_t* sidx_all = ri.src == 0 ? idx_a : idx_b;
   const float* tangent = tangent_all != nullptr ? tangent_all + base : nullptr;
   float* out = out_all != nullptr ? out_all + base : nullptr;
   float* jvp = jvp_all != nullptr ? jvp_all + base : nullptr;
@@ -86,16 +107,16 @@ template <bool MAG, int PC>
 void launch_tail(bool selected, const SortBuffers& B, const float* x, const float* tangent,
                  float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
                  hipStream_t st) {
-  hipLaunchKernelGGL((long_solve_kernel<MAG, PC>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
+  hipLaunchKernelGGL((long_solve_kernel<MAG, PC>), dim3(unsigned(rows)), dim3(kSolveThreads), 0, st,
                      B.keys_a, B.idx_a, jvp ? tangent : nullptr, B.info,
                      selected ? B.sel : nullptr, n, k, R);
   const int chunks = int((n + kThreads * 8 - 1) / (kThreads * 8));
   hipLaunchKernelGGL((long_dense_kernel<MAG>), dim3(unsigned(rows * chunks)), dim3(kThreads), 0, st,
                      x, tangent, B.info, out, jvp, n, chunks, float(R.inv_1pl));
-  const int64_t tiles = (n + Solver::kChunk - 1) / Solver::kChunk;
+  const int64_t tiles = (n + 1023) / 1024;
   const int bpr = int(tiles < 64 ? tiles : 64);
   hipLaunchKernelGGL((long_window_kernel<MAG, PC>), dim3(unsigned(rows * bpr)), dim3(kThreads), 0,
-                     st, B.keys_a, B.idx_a, tangent, B.info, out, jvp, n, bpr, R);
+                     st, B.keys_a, B.idx_a, B.keys_b, B.idx_b, tangent, B.info, out, jvp, n, bpr, R);
 }
 
 }  // namespace

@@ -26,6 +26,13 @@ struct Acc {
 };
 
 template <int NT>
+struct GrowShared {
+  Sums wave_r[NT / kWave], wave_l[NT / kWave];   // wavefront totals of the scans
+  int first_r[NT / kWave], first_l[NT / kWave];  // leading accepted run inside each wavefront
+  Sums take_r, take_l;                           // sums of the accepted runs
+};
+
+template <int NT>
 struct SolveShared {
   Sums sums[NT / kWave];
   Acc acc[NT / kWave];
@@ -34,6 +41,8 @@ struct SolveShared {
     Sums S;
     int done;
   } hand;                 // state of the block after the single-wavefront phase
+  GrowShared<NT> grow;
+  GrowShared<kWave> grow1;
 };
 
 __device__ __forceinline__ double readlane_f64(double v, int src_lane) {
@@ -58,31 +67,46 @@ __device__ __forceinline__ double wave_inclusive_scan_f64(double v) {
   return v + before;
 }
 
-// Block growth by ONE wavefront, both sides per step, 128 sorted positions per side and step
-// (lane l looks at positions 2l and 2l+1 of each side's traversal).  Tests as in the sweeps
-// below; accepting both sides' prefixes in the same step is valid because additions on one side
-// only make the other side's tests more true.  Returns true when neither side can grow any
-// further, false when `max_steps` steps were not enough (the caller continues with block-wide
-// sweeps from the state left in a, b, S).  Called by all 64 lanes of one wavefront; no barriers.
-template <bool MAG, int PC>
-__device__ bool wave_grow(const uint32_t* __restrict__ skeys, int64_t n, int64_t k, double center,
-                          const Reg& R, int64_t& a, int64_t& b, Sums& S, int max_steps) {
+// Block growth by W = 1 wavefront or by the whole workgroup of NT threads (W = NT / 64), both
+// sides per step, 2 sorted positions per thread, side and step (thread t looks at positions 2t
+// and 2t+1 of each side's traversal, counted from the block outwards).
+//
+// Per step: inclusive scans of the float64 power sums over the traversal give every position the
+// sums of its side's positions before it; the strict-violation tests of pooling.hpp are evaluated
+// for all positions at once; each side takes its leading run of accepted positions (the tests are
+// monotone along the traversal), and the sums of that run are read off the scan.  Accepting both
+// sides' runs in the same step is valid because additions on one side only make the other
+// side's tests more true.
+//
+// Returns true when neither side can grow any further.  With `max_steps` > 0 it gives up (false)
+// after that many steps, or after three steps that took a whole chunk on one side: the block is
+// large, and the caller continues with the whole workgroup from the state left in a, b, S.
+// W = 1: called by the 64 lanes of one wavefront, no barriers; else by all NT threads.
+template <int NT, bool MAG, int PC>
+__device__ __forceinline__ bool grow_block(const uint32_t* __restrict__ skeys, int64_t n, int64_t k, double center,
+                           const Reg& R, int64_t& a, int64_t& b, Sums& S, int max_steps,
+                           GrowShared<NT>& gs) {
   using P = Pool<MAG, PC>;
   constexpr bool CUBIC = (PC == kP43);
+  constexpr int W = NT / kWave;
+  constexpr int kSide = 2 * NT;                  // positions per side and step
   const int lane = threadIdx.x & (kWave - 1);
-  for (int step = 0; step < max_steps; ++step) {
+  const int w = (W == 1) ? 0 : int(threadIdx.x) / kWave;
+  const int t = (W == 1) ? lane : int(threadIdx.x);
+  int full_steps = 0;
+  for (int step = 0; max_steps <= 0 || (step < max_steps && full_steps < 3); ++step) {
     const int64_t rem_r = n - b, rem_l = a - 1;
     double dr[2], dl[2];
     bool vr[2], vl[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int64_t q = 2 * lane + i;
+      const int64_t q = 2 * t + i;
       vr[i] = q < rem_r;
       vl[i] = q < rem_l;
       dr[i] = vr[i] ? double(key_to_float(skeys[b + q])) - center : 0.0;          // position b+1+q
       dl[i] = vl[i] ? double(key_to_float(skeys[a - 2 - q])) - center : 0.0;      // position a-1-q
     }
-    // inclusive scans of the lane totals; exclusive prefix of a position = inclusive - what follows
+    // inclusive scans of the thread totals
     Sums ir, il;
     ir.s1 = wave_inclusive_scan_f64(dr[0] + dr[1]);
     il.s1 = wave_inclusive_scan_f64(dl[0] + dl[1]);
@@ -93,54 +117,104 @@ __device__ bool wave_grow(const uint32_t* __restrict__ skeys, int64_t n, int64_t
       il.s2 = wave_inclusive_scan_f64(dl[0] * dl[0] + dl[1] * dl[1]);
       il.s3 = wave_inclusive_scan_f64(dl[0] * dl[0] * dl[0] + dl[1] * dl[1] * dl[1]);
     }
-    // prefix[j] = sums of this side's positions before position 2*lane + j, j = 0, 1, 2
-    Sums pr[3], pl[3];
-    pr[2] = ir;
-    pr[1] = Sums{ir.s1 - dr[1], ir.s2 - dr[1] * dr[1], ir.s3 - dr[1] * dr[1] * dr[1]};
-    pr[0] = Sums{pr[1].s1 - dr[0], pr[1].s2 - dr[0] * dr[0], pr[1].s3 - dr[0] * dr[0] * dr[0]};
-    pl[2] = il;
-    pl[1] = Sums{il.s1 - dl[1], il.s2 - dl[1] * dl[1], il.s3 - dl[1] * dl[1] * dl[1]};
-    pl[0] = Sums{pl[1].s1 - dl[0], pl[1].s2 - dl[0] * dl[0], pl[1].s3 - dl[0] * dl[0] * dl[0]};
+    if constexpr (W > 1) {
+      __syncthreads();                           // the previous step's readers are done
+      if (lane == kWave - 1) {
+        gs.wave_r[w] = ir;
+        gs.wave_l[w] = il;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < W; ++q) {
+        if (q < w) {
+          const Sums tr = gs.wave_r[q], tl = gs.wave_l[q];
+          ir.s1 += tr.s1; il.s1 += tl.s1;
+          if (CUBIC) { ir.s2 += tr.s2; ir.s3 += tr.s3; il.s2 += tl.s2; il.s3 += tl.s3; }
+        }
+      }
+    }
+    // sums of this side's positions before position 2t + j  =  inclusive scan - tail[j], where
+    // tail[0] = both positions of this thread, tail[1] = the second one, tail[2] = nothing
+    // (plain variables and selects: indexable arrays would end up in scratch memory)
+    const Sums tr0{dr[0] + dr[1], dr[0] * dr[0] + dr[1] * dr[1],
+                   dr[0] * dr[0] * dr[0] + dr[1] * dr[1] * dr[1]};
+    const Sums tr1{dr[1], dr[1] * dr[1], dr[1] * dr[1] * dr[1]};
+    const Sums tl0{dl[0] + dl[1], dl[0] * dl[0] + dl[1] * dl[1],
+                   dl[0] * dl[0] * dl[0] + dl[1] * dl[1] * dl[1]};
+    const Sums tl1{dl[1], dl[1] * dl[1], dl[1] * dl[1] * dl[1]};
     const double cnt0 = double(b - a + 1), m0 = double(k - a + 1);
     unsigned long long okr[2], okl[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const double q = double(2 * lane + i);
-      const Sums run_r{S.s1 + pr[i].s1, S.s2 + pr[i].s2, S.s3 + pr[i].s3};
-      const Sums run_l{S.s1 + pl[i].s1, S.s2 + pl[i].s2, S.s3 + pl[i].s3};
-      const bool tr = vr[i] & P::right_violates(dr[i], cnt0 + q, m0, run_r, R);
-      const bool tl = vl[i] & P::left_violates(dl[i], cnt0 + q, m0 + q, run_l, R);
-      okr[i] = __ballot(tr);
-      okl[i] = __ballot(tl);
+    {
+      const double q = double(2 * t);
+      const Sums run_r{S.s1 + (ir.s1 - tr0.s1), S.s2 + (ir.s2 - tr0.s2), S.s3 + (ir.s3 - tr0.s3)};
+      const Sums run_l{S.s1 + (il.s1 - tl0.s1), S.s2 + (il.s2 - tl0.s2), S.s3 + (il.s3 - tl0.s3)};
+      okr[0] = __ballot(vr[0] & P::right_violates(dr[0], cnt0 + q, m0, run_r, R));
+      okl[0] = __ballot(vl[0] & P::left_violates(dl[0], cnt0 + q, m0 + q, run_l, R));
     }
-    // length of the leading run of accepted positions in traversal order 0, 1, 2, ...
+    {
+      const double q = double(2 * t + 1);
+      const Sums run_r{S.s1 + (ir.s1 - tr1.s1), S.s2 + (ir.s2 - tr1.s2), S.s3 + (ir.s3 - tr1.s3)};
+      const Sums run_l{S.s1 + (il.s1 - tl1.s1), S.s2 + (il.s2 - tl1.s2), S.s3 + (il.s3 - tl1.s3)};
+      okr[1] = __ballot(vr[1] & P::right_violates(dr[1], cnt0 + q, m0, run_r, R));
+      okl[1] = __ballot(vl[1] & P::left_violates(dl[1], cnt0 + q, m0 + q, run_l, R));
+    }
+    // length of the leading run of accepted positions of this wavefront's 128 positions
     auto leading = [](unsigned long long ok0, unsigned long long ok1) -> int {
       const int f0 = (~ok0 == 0ull) ? 128 : 2 * (__ffsll((long long)~ok0) - 1);
       const int f1 = (~ok1 == 0ull) ? 128 : 2 * (__ffsll((long long)~ok1) - 1) + 1;
       return f0 < f1 ? f0 : f1;
     };
-    const int nr = leading(okr[0], okr[1]);
-    const int nl = leading(okl[0], okl[1]);
+    int nr = leading(okr[0], okr[1]);
+    int nl = leading(okl[0], okl[1]);
+    if constexpr (W > 1) {
+      if (lane == 0) {
+        gs.first_r[w] = nr;
+        gs.first_l[w] = nl;
+      }
+      __syncthreads();
+      // the run of the workgroup ends in the first wavefront whose own run is not complete
+      int tot_r = kSide, tot_l = kSide;
+#pragma unroll
+      for (int q = W - 1; q >= 0; --q) {
+        if (gs.first_r[q] < 128) tot_r = q * 128 + gs.first_r[q];
+        if (gs.first_l[q] < 128) tot_l = q * 128 + gs.first_l[q];
+      }
+      nr = tot_r;
+      nl = tot_l;
+    }
     if (nr == 0 && nl == 0) return true;
-    // sums of the first nr (nl) positions: prefix[j] of lane nr/2 with j = nr%2 (128: lane 63, j = 2)
-    auto take = [&](const Sums (&pre)[3], int cnt) -> Sums {
-      const int src = cnt >= 128 ? 63 : (cnt >> 1);
-      const int j = cnt >= 128 ? 2 : (cnt & 1);
-      Sums pick = pre[0];
-      if (j == 1) pick = pre[1];
-      if (j == 2) pick = pre[2];
-      Sums out;
-      out.s1 = readlane_f64(pick.s1, src);
-      out.s2 = CUBIC ? readlane_f64(pick.s2, src) : 0.0;
-      out.s3 = CUBIC ? readlane_f64(pick.s3, src) : 0.0;
-      return out;
+    // sums of the first nr (nl) positions: those before position nr, held by thread nr/2 with
+    // j = nr%2 (a whole chunk: the last thread's inclusive value)
+    const int src_r = nr >= kSide ? NT - 1 : (nr >> 1), jr = nr >= kSide ? 2 : (nr & 1);
+    const int src_l = nl >= kSide ? NT - 1 : (nl >> 1), jl = nl >= kSide ? 2 : (nl & 1);
+    auto before = [](const Sums& inc, const Sums& t0, const Sums& t1, int j) -> Sums {
+      const double c1 = j == 0 ? t0.s1 : (j == 1 ? t1.s1 : 0.0);
+      const double c2 = j == 0 ? t0.s2 : (j == 1 ? t1.s2 : 0.0);
+      const double c3 = j == 0 ? t0.s3 : (j == 1 ? t1.s3 : 0.0);
+      return Sums{inc.s1 - c1, inc.s2 - c2, inc.s3 - c3};
     };
-    const Sums ar = take(pr, nr), al = take(pl, nl);
+    const Sums mine_r = before(ir, tr0, tr1, jr), mine_l = before(il, tl0, tl1, jl);
+    Sums ar, al;
+    if constexpr (W == 1) {
+      ar.s1 = readlane_f64(mine_r.s1, src_r);
+      al.s1 = readlane_f64(mine_l.s1, src_l);
+      ar.s2 = CUBIC ? readlane_f64(mine_r.s2, src_r) : 0.0;
+      ar.s3 = CUBIC ? readlane_f64(mine_r.s3, src_r) : 0.0;
+      al.s2 = CUBIC ? readlane_f64(mine_l.s2, src_l) : 0.0;
+      al.s3 = CUBIC ? readlane_f64(mine_l.s3, src_l) : 0.0;
+    } else {
+      if (t == src_r) gs.take_r = mine_r;
+      if (t == src_l) gs.take_l = mine_l;
+      __syncthreads();
+      ar = gs.take_r;
+      al = gs.take_l;
+    }
     S.s1 += ar.s1 + al.s1;
     S.s2 += ar.s2 + al.s2;
     S.s3 += ar.s3 + al.s3;
     b += nr;
     a -= nl;
+    if (nr == kSide || nl == kSide) ++full_steps;
   }
   return false;
 }
@@ -150,34 +224,6 @@ struct RowSolver {
   static constexpr int kWaves = NT / kWave;
   static constexpr int kPer = 4;
   static constexpr int kChunk = NT * kPer;
-
-  // Block-wide exclusive scan (in thread order) of the power sums.
-  template <bool CUBIC>
-  __device__ static __forceinline__ Sums exclusive_scan_sums(const Sums& v, Sums* wave_tot) {
-    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-    Sums inc = v;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const double o1 = __shfl_up(inc.s1, off, kWave);
-      const double o2 = CUBIC ? __shfl_up(inc.s2, off, kWave) : 0.0;
-      const double o3 = CUBIC ? __shfl_up(inc.s3, off, kWave) : 0.0;
-      if (lane >= off) { inc.s1 += o1; inc.s2 += o2; inc.s3 += o3; }
-    }
-    __syncthreads();
-    if (lane == kWave - 1) wave_tot[w] = inc;
-    __syncthreads();
-    Sums before{0.0, 0.0, 0.0};
-    for (int q = 0; q < w; ++q) {
-      const Sums t = wave_tot[q];
-      before.s1 += t.s1; before.s2 += t.s2; before.s3 += t.s3;
-    }
-    // exclusive value inside the wave: the inclusive value of the lane before
-    double e1 = __shfl_up(inc.s1, 1, kWave);
-    double e2 = CUBIC ? __shfl_up(inc.s2, 1, kWave) : 0.0;
-    double e3 = CUBIC ? __shfl_up(inc.s3, 1, kWave) : 0.0;
-    if (lane == 0) { e1 = 0.0; e2 = 0.0; e3 = 0.0; }
-    return Sums{before.s1 + e1, before.s2 + e2, before.s3 + e3};
-  }
 
   // Block-wide sum of (s1, s2, s3, c).
   __device__ static __forceinline__ Acc sum_acc(Acc v, Acc* wave_tot) {
@@ -196,62 +242,6 @@ struct RowSolver {
       r.s1 += wave_tot[q].s1; r.s2 += wave_tot[q].s2; r.s3 += wave_tot[q].s3; r.c += wave_tot[q].c;
     }
     return r;
-  }
-
-  // One sweep in one direction.  Traversal step q visits sorted position (1-based)
-  // start + dir*q.  The predicate holds on a prefix of the traversal; the sweep stops at its end.
-  // RIGHT: positions > k joining [a, pos-1]; LEFT: positions <= k joining [pos+1, b].
-  template <bool MAG, int PC, bool RIGHT>
-  __device__ static int64_t sweep(const uint32_t* __restrict__ skeys, int64_t n, int64_t k,
-                                  double center, const Reg& R, int64_t& a, int64_t& b, Sums& S,
-                                  SolveShared<NT>& sm) {
-    using P = Pool<MAG, PC>;
-    constexpr bool CUBIC = (PC == kP43);
-    int64_t added = 0;
-    for (;;) {
-      const int64_t start = RIGHT ? b + 1 : a - 1;
-      const int64_t remaining = RIGHT ? (n - b) : (a - 1);
-      if (remaining <= 0) break;
-      double d[kPer];
-      bool valid[kPer];
-      Sums mine{0.0, 0.0, 0.0};
-#pragma unroll
-      for (int i = 0; i < kPer; ++i) {
-        const int64_t q = int64_t(threadIdx.x) * kPer + i;
-        valid[i] = q < remaining;
-        const int64_t pos1 = RIGHT ? start + q : start - q;
-        d[i] = valid[i] ? double(key_to_float(skeys[pos1 - 1])) - center : 0.0;
-        mine.s1 += d[i];
-        if (CUBIC) { mine.s2 += d[i] * d[i]; mine.s3 += d[i] * d[i] * d[i]; }
-      }
-      const Sums ex = exclusive_scan_sums<CUBIC>(mine, sm.sums);
-      Acc acc{0.0, 0.0, 0.0, 0};
-      Sums run{S.s1 + ex.s1, S.s2 + ex.s2, S.s3 + ex.s3};
-#pragma unroll
-      for (int i = 0; i < kPer; ++i) {
-        const int64_t q = int64_t(threadIdx.x) * kPer + i;
-        const int64_t pos1 = RIGHT ? start + q : start - q;
-        bool pred = false;
-        if (valid[i]) {
-          if (RIGHT) pred = P::right_violates(d[i], double(pos1 - a), double(k - a + 1), run, R);
-          else pred = P::left_violates(d[i], double(b - pos1), double(k - pos1), run, R);
-        }
-        if (pred) {
-          acc.s1 += d[i];
-          if (CUBIC) { acc.s2 += d[i] * d[i]; acc.s3 += d[i] * d[i] * d[i]; }
-          acc.c += 1;
-        }
-        run.s1 += d[i];
-        if (CUBIC) { run.s2 += d[i] * d[i]; run.s3 += d[i] * d[i] * d[i]; }
-      }
-      const Acc got = sum_acc(acc, sm.acc);
-      S.s1 += got.s1; S.s2 += got.s2; S.s3 += got.s3;
-      if (RIGHT) b += got.c; else a -= got.c;
-      added += got.c;
-      const int64_t visited = remaining < kChunk ? remaining : kChunk;
-      if (got.c < visited) break;
-    }
-    return added;
   }
 
   // Length of the run of sorted keys equal to `key` that starts at 1-based position `start` and
@@ -310,7 +300,7 @@ struct RowSolver {
         // steps without barriers; blocks that are still growing after that continue with
         // sweeps of the whole workgroup
         if (threadIdx.x < kWave) {
-          const bool done = wave_grow<MAG, PC>(skeys, n, k, center, R, a, b, S, 12);
+          const bool done = grow_block<kWave, MAG, PC>(skeys, n, k, center, R, a, b, S, 12, sm.grow1);
           if (threadIdx.x == 0) {
             sm.hand.a = a;
             sm.hand.b = b;
@@ -319,20 +309,11 @@ struct RowSolver {
           }
         }
         __syncthreads();
+        TOPK_SOLVE_MARK(11);
         a = sm.hand.a;
         b = sm.hand.b;
         S = sm.hand.S;
-        const bool done = sm.hand.done != 0;
-        if (!done) {
-          bool first = true;
-          for (;;) {
-            const int64_t r = sweep<MAG, PC, true>(skeys, n, k, center, R, a, b, S, sm);
-            if (r == 0 && !first) break;
-            const int64_t l = sweep<MAG, PC, false>(skeys, n, k, center, R, a, b, S, sm);
-            if (l == 0) break;
-            first = false;
-          }
-        }
+        if (sm.hand.done == 0) grow_block<NT, MAG, PC>(skeys, n, k, center, R, a, b, S, 0, sm.grow);
         TOPK_SOLVE_MARK(8);
         const double da = double(key_to_float(skeys[a - 1])) - center;
         const double db = double(key_to_float(skeys[b - 1])) - center;
@@ -343,18 +324,30 @@ struct RowSolver {
     if (grow && tangent != nullptr) {
       // Prop. 7: d gamma = sum_B c_j tau_j / (sum_B c_j [+ lambda m]),  c_j = |gamma - s_j|^(q-2)
       Acc acc{0.0, 0.0, 0.0, 0};
-      for (int64_t pos1 = a + threadIdx.x; pos1 <= b; pos1 += NT) {
-        const uint32_t key = skeys[pos1 - 1];
-        const uint32_t id = sidx[pos1 - 1];
-        const float sv = key_to_float(key);
-        double t = double(tangent[MAG ? (id >> 1) : id]);
-        if (MAG) {
-          if (id & 1u) t = -t;
-          if (sv == 0.0f) t = 0.0;
+      for (int64_t p0 = a + threadIdx.x; p0 <= b; p0 += 4 * NT) {
+        uint32_t id[4];
+        float sv[4], tv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int64_t pos1 = p0 + int64_t(i) * NT;
+          id[i] = pos1 <= b ? sidx[pos1 - 1] : 0u;
+          sv[i] = pos1 <= b ? key_to_float(skeys[pos1 - 1]) : 0.0f;
         }
-        const double w = P::jac_weight(double(sv) - center, gamma);
-        acc.s1 += w * t;
-        acc.s2 += w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          tv[i] = (p0 + int64_t(i) * NT <= b) ? tangent[MAG ? (id[i] >> 1) : id[i]] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (p0 + int64_t(i) * NT > b) continue;
+          double t = double(tv[i]);
+          if (MAG) {
+            if (id[i] & 1u) t = -t;
+            if (sv[i] == 0.0f) t = 0.0;
+          }
+          const double w = P::jac_weight(double(sv[i]) - center, gamma);
+          acc.s1 += w * t;
+          acc.s2 += w;
+        }
       }
       const Acc got = sum_acc(acc, sm.acc);
       dgamma = got.s1 / P::jac_denominator(got.s2, double(k - a + 1), R);
@@ -362,6 +355,8 @@ struct RowSolver {
     TOPK_SOLVE_MARK(10);
     // ---- value window of the block, widened over ties at both ends -----------------------------
     RowInfo ri;
+    ri.src = 0;
+    ri.pad = 0;
     ri.a = a;
     ri.b = b;
     ri.gamma = gamma;

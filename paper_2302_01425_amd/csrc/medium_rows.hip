@@ -48,6 +48,7 @@ constexpr int kCItems = 16;                // elements per thread and tile of th
 constexpr int kCTile = kMT * kCItems;
 constexpr int kLdsCap = 2048;              // candidate lists up to this length are sorted in LDS
 constexpr int kCopies = 4;
+constexpr int kLdsKeys = kSelBins * kCopies;   // sorted keys of a list this long fit the LDS for the solve
 constexpr int kSelShift = 32 - kSelBits;
 
 struct MedShared {
@@ -92,7 +93,8 @@ __device__ __forceinline__ uint32_t med_exclusive_scan(uint32_t v, uint32_t* wav
 
 // One LSD pass over the cn candidates: (kin, iin) -> (kout, iout), stable, by the 8-bit digit of
 // (key - klo) at `shift`.  Tiles of ni*1024 elements; wave w owns elements w*ni*64 .. of a tile.
-__device__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t* kout,
+template <int ITEMS>
+__device__ __forceinline__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t* kout,
                               uint32_t* iout, uint32_t cn, uint32_t klo, int shift, int ni,
                               MedShared& sm) {
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
@@ -106,7 +108,7 @@ __device__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t
     __syncthreads();
     for (uint32_t tile_first = 0; tile_first < cn; tile_first += tile_elems) {
 #pragma unroll
-      for (int i = 0; i < kMItems; ++i) {
+      for (int i = 0; i < ITEMS; ++i) {
         if (i < ni) {
           const uint32_t e = tile_first + w * wave_elems + i * kWave + lane;
           const bool valid = e < cn;
@@ -129,9 +131,9 @@ __device__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t
     __syncthreads();                       // previous users of cnt / gofs are done
     for (int i = threadIdx.x; i < kMW * kRadix; i += kMT) (&sm.u.sort.cnt[0][0])[i] = 0;
     __syncthreads();
-    uint32_t key[kMItems], idx[kMItems], rank[kMItems];
+    uint32_t key[ITEMS], idx[ITEMS], rank[ITEMS];
 #pragma unroll
-    for (int i = 0; i < kMItems; ++i) {
+    for (int i = 0; i < ITEMS; ++i) {
       if (i < ni) {
         const uint32_t e = tile_first + w * wave_elems + i * kWave + lane;
         const bool valid = e < cn;
@@ -168,7 +170,7 @@ __device__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < kMItems; ++i) {
+    for (int i = 0; i < ITEMS; ++i) {
       if (i < ni) {
         const uint32_t e = tile_first + w * wave_elems + i * kWave + lane;
         if (e < cn) {
@@ -181,6 +183,45 @@ __device__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t
     }
   }
   __syncthreads();          // workgroup-scope release/acquire: the next pass reads what this one wrote
+}
+
+// Where sort_candidates left the sorted list.
+struct SortedList {
+  const uint32_t* keys;   // LDS or global
+  const uint32_t* idx;    // LDS or global
+  int global_src;         // global copy of (keys, idx): 0 = (ka, ia), 1 = (kb, ib), -1 = none yet
+  bool keys_in_lds;
+};
+
+// Stable LSD sort of the cn candidates in (ka, ia) on key - klo, one pass per 8 significant bits
+// of khi - klo.  The passes alternate between two buffers: in LDS for short lists, else (kb, ib)
+// and (ka, ia).
+template <int ITEMS>
+__device__ __forceinline__ SortedList sort_candidates(uint32_t* ka, uint32_t* ia, uint32_t* kb, uint32_t* ib,
+                                      uint32_t cn, uint32_t klo, uint32_t khi, MedShared& sm) {
+  const uint32_t span = khi - klo;
+  const int nbits = span == 0 ? 0 : 32 - __clz(int(span));
+  int ni = int((cn + kMT - 1) / kMT);
+  ni = ni > ITEMS ? ITEMS : ni;
+  if (nbits == 0) return SortedList{ka, ia, 0, false};
+  const bool in_lds = cn <= uint32_t(kLdsCap);
+  uint32_t* k0 = in_lds ? sm.u.sort.lk[0] : kb;
+  uint32_t* i0 = in_lds ? sm.u.sort.li[0] : ib;
+  uint32_t* k1 = in_lds ? sm.u.sort.lk[1] : ka;
+  uint32_t* i1 = in_lds ? sm.u.sort.li[1] : ia;
+  const uint32_t* kin = ka;
+  const uint32_t* iin = ia;
+  bool even = true;
+  for (int shift = 0; shift < nbits; shift += 8) {
+    uint32_t* kout = even ? k0 : k1;
+    uint32_t* iout = even ? i0 : i1;
+    med_sort_pass<ITEMS>(kin, iin, kout, iout, cn, klo, shift, ni, sm);
+    kin = kout;
+    iin = iout;
+    even = !even;
+  }
+  if (in_lds) return SortedList{kin, iin, -1, true};
+  return SortedList{kin, iin, even ? 0 : 1, false};    // even: an even number of passes was made
 }
 
 template <bool MAG, int PC>
@@ -301,29 +342,9 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 
     TOPK_MED_MARK(3);
     // ---- 4. sort the candidates -------------------------------------------------------------------
-    const uint32_t span = khi - klo;
-    const int nbits = span == 0 ? 0 : 32 - __clz(int(span));
-    int ni = int((cn + kMT - 1) / kMT);
-    ni = ni > kMItems ? kMItems : ni;
-    // passes alternate between two buffers: in LDS for short lists, else the row's scratch
-    const bool in_lds = cn <= uint32_t(kLdsCap);
-    uint32_t* k0 = in_lds ? sm.u.sort.lk[0] : kb;
-    uint32_t* i0 = in_lds ? sm.u.sort.li[0] : ib;
-    uint32_t* k1 = in_lds ? sm.u.sort.lk[1] : ka;
-    uint32_t* i1 = in_lds ? sm.u.sort.li[1] : ia;
-    const uint32_t* kin = ka;
-    const uint32_t* iin = ia;
-    bool even = true;
-    for (int shift = 0; shift < nbits; shift += 8) {
-      uint32_t* kout = even ? k0 : k1;
-      uint32_t* iout = even ? i0 : i1;
-      med_sort_pass(kin, iin, kout, iout, cn, klo, shift, ni, sm);
-      kin = kout;
-      iin = iout;
-      even = !even;
-    }
-    skeys = kin;
-    sidx = iin;
+    const SortedList sorted = sort_candidates<kMItems>(ka, ia, kb, ib, cn, klo, khi, sm);
+    skeys = sorted.keys;
+    sidx = sorted.idx;
   }
 
   TOPK_MED_MARK(4);
@@ -350,6 +371,55 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
   TOPK_MED_MARK(6);
 }
 
+// Long rows: sort and solve of a candidate list of up to kFinishMax elements (the dense list in
+// the "a" arrays, described by sel[row]) by one workgroup; writes the row's RowInfo.  Longer
+// lists are left to the multi-workgroup passes.
+template <bool MAG, int PC>
+__global__ __launch_bounds__(kMT) void finish_kernel(uint32_t* keys_a, uint32_t* idx_a,
+                                                     uint32_t* keys_b, uint32_t* idx_b,
+                                                     const float* __restrict__ tangent_all,
+                                                     const RowSel* __restrict__ sel,
+                                                     RowInfo* __restrict__ info, int64_t n,
+                                                     int64_t k_row, Reg R) {
+  __shared__ MedShared sm;
+  const int64_t row = blockIdx.x;
+  const RowSel rs = sel[row];
+  if (int64_t(rs.cn) > kFinishMax) return;
+  const int64_t base = row * n;
+  uint32_t* ka = keys_a + base;
+  uint32_t* ia = idx_a + base;
+  TOPK_MED_MARK(0);
+  uint32_t* kb = keys_b + base;
+  uint32_t* ib = idx_b + base;
+  const SortedList sorted = sort_candidates<16>(ka, ia, kb, ib, rs.cn, rs.klo, rs.khi, sm);
+  const uint32_t* skeys = sorted.keys;
+  const uint32_t* sidx = sorted.idx;
+  int src = sorted.global_src;
+  TOPK_MED_MARK(3);
+  if (src < 0) {
+    // sorted in LDS only; the window pass reads the list from global memory
+    for (uint32_t j = threadIdx.x; j < rs.cn; j += kMT) {
+      ka[j] = skeys[j];
+      ia[j] = sidx[j];
+    }
+    src = 0;
+  } else if (rs.cn <= uint32_t(kLdsKeys)) {
+    // the solve reads the sorted keys many times: from LDS when they fit (the sort is over and
+    // its LDS is free)
+    uint32_t* lds_keys = sm.u.hist;
+    for (uint32_t j = threadIdx.x; j < rs.cn; j += kMT) lds_keys[j] = skeys[j];
+    skeys = lds_keys;
+    __syncthreads();
+  }
+  TOPK_MED_MARK(4);
+  RowInfo ri = RowSolver<kMT>::solve<MAG, PC>(
+      skeys, sidx, tangent_all != nullptr ? tangent_all + base : nullptr, int64_t(rs.cn),
+      k_row - rs.above, R, sm.solve);
+  ri.src = src;
+  if (threadIdx.x == 0) info[row] = ri;
+  TOPK_MED_MARK(5);
+}
+
 template <bool MAG, int PC>
 void launch(const SortBuffers& B, const float* x, const float* tangent, float* out, float* jvp,
             int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
@@ -366,6 +436,23 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
   if (!mag && pc == kP2) launch<false, kP2>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
   else if (!mag && pc == kP43) launch<false, kP43>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
   else if (mag && pc == kP2) launch<true, kP2>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
+  else return -1;
+  return 0;
+}
+
+int launch_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, int64_t rows,
+                  int64_t n, int64_t k, const Reg& R, hipStream_t st) {
+  if (rows > 0x7fffffffLL) return -1;
+  const dim3 grid{unsigned(rows)}, block{kMT};
+  if (!mag && pc == kP2)
+    hipLaunchKernelGGL((finish_kernel<false, kP2>), grid, block, 0, st, B.keys_a, B.idx_a, B.keys_b,
+                       B.idx_b, tangent, B.sel, B.info, n, k, R);
+  else if (!mag && pc == kP43)
+    hipLaunchKernelGGL((finish_kernel<false, kP43>), grid, block, 0, st, B.keys_a, B.idx_a,
+                       B.keys_b, B.idx_b, tangent, B.sel, B.info, n, k, R);
+  else if (mag && pc == kP2)
+    hipLaunchKernelGGL((finish_kernel<true, kP2>), grid, block, 0, st, B.keys_a, B.idx_a, B.keys_b,
+                       B.idx_b, tangent, B.sel, B.info, n, k, R);
   else return -1;
   return 0;
 }

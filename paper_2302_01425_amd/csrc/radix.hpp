@@ -55,15 +55,15 @@ __device__ __forceinline__ double bound_value(uint32_t key) {
 }
 
 
-// Key window [klo, khi] of the candidates of one row, from the histogram bins (leading kSelBits
+// Key window [klo, khi] of the candidates of one row, from the histogram bins (leading BITS
 // key bits) that hold sorted positions k and k+1.  s_k is at least the smallest value of its bin
 // and s_{k+1} at most the largest value of its bin; the window holds both bins and every element
 // that passes the necessary conditions for joining the block (pooling.hpp: left_candidate,
 // right_candidate) for ANY s_k, s_{k+1} inside those bins.
-template <bool MAG>
+template <bool MAG, int BITS = kSelBits>
 __device__ __forceinline__ void key_window(uint32_t bin_k, uint32_t bin_k1, const Reg& R,
                                            uint32_t* klo_out, uint32_t* khi_out) {
-  constexpr int kShift = 32 - kSelBits;
+  constexpr int kShift = 32 - BITS;
   const uint32_t low_bits = (1u << kShift) - 1u;
   const uint32_t first_k = bin_k << kShift;                       // largest value of s_k's bin
   const uint32_t last_k1 = (bin_k1 << kShift) | low_bits;         // smallest value of s_{k+1}'s bin

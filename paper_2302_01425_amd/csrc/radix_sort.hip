@@ -10,8 +10,10 @@
 //
 // The operators do not need the whole permutation: only elements in a value window around
 // s_k and s_{k+1} can pool (pooling.hpp).  The second half of this file selects those candidates
-// (histogram of the leading key bits, key window, ordered compaction per tile) and sorts only
-// them with the same passes; topk_argsort_desc and rows with k = 0 or k = n use the full sort.
+// in two histogram levels (12 + 12 leading key bits) and gathers them, in index order, into a
+// dense list per row.  Short lists are then sorted and solved by one workgroup
+// (medium_rows.hip); only rows whose list is longer go through the passes of this file.
+// topk_argsort_desc sorts whole rows with them.
 #include "common.hpp"
 #include "launch.hpp"
 #include "radix.hpp"
@@ -48,91 +50,68 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
   return before + inc - v;
 }
 
-// Number of valid elements at the start of tile `tile` of row `row` (the rest of the tile is
-// padding).  Three layouts of the arrays a pass reads, all with row stride n:
-//   dense, n per row            (tcnt == nullptr, sel == nullptr)
-//   per-tile slots              (tcnt != nullptr): tile t holds tcnt[row][t] elements at its start
-//   dense, sel[row].cn per row  (sel != nullptr)
-__device__ __forceinline__ int tile_valid_count(int64_t row, int tile, int64_t n, int tiles,
-                                                const uint32_t* __restrict__ tcnt,
-                                                const RowSel* __restrict__ sel) {
-  if (tcnt != nullptr) return int(tcnt[row * tiles + tile]);
-  const int64_t len = (sel != nullptr) ? int64_t(sel[row].cn) : n;
-  const int64_t left = len - int64_t(tile) * kTile;
-  return int(left < 0 ? 0 : (left > kTile ? kTile : left));
+// Length of the list a pass sorts in row `row`: the whole row, or (sel != nullptr) the row's
+// candidate list -- and then only if it is too long for the single-workgroup finish, which has
+// dealt with the shorter ones.
+__device__ __forceinline__ int64_t pass_length(int64_t row, int64_t n, const RowSel* __restrict__ sel) {
+  if (sel == nullptr) return n;
+  const int64_t cn = int64_t(sel[row].cn);
+  return cn > kFinishMax ? cn : 0;
 }
 
 // ---- 1. per-tile digit histogram ------------------------------------------------------------
-// hist layout: [row][digit][tile]
+// hist layout: [row][digit][tile] with `tiles` tiles per row; a workgroup handles tiles
+// (its index in the row) + j * grid_tiles.
 template <bool FIRST, bool MAG>
 __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const float* __restrict__ x,
                                                               const uint32_t* __restrict__ keys,
                                                               uint32_t* __restrict__ hist,
                                                               const RowSel* __restrict__ sel,
-                                                              int64_t n, int tiles, int shift) {
+                                                              int64_t n, int tiles, int grid_tiles,
+                                                              int shift) {
   __shared__ uint32_t cnt[kWaves][kRadix];
-  const int64_t row = blockIdx.x / tiles;
-  const int tile = blockIdx.x % tiles;
-  const int nvalid = tile_valid_count(row, tile, n, tiles, nullptr, sel);
-  if (nvalid == 0) return;                 // tiles past the end of a candidate list are not scanned
+  const int64_t row = blockIdx.x / grid_tiles;
+  const int64_t len = pass_length(row, n, sel);
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-  for (int i = threadIdx.x; i < kWaves * kRadix; i += kThreads) (&cnt[0][0])[i] = 0;
-  __syncthreads();
-  const int64_t tile_base = row * n + int64_t(tile) * kTile;
-  const int chunk = w * (kTile / kWaves);
+  for (int tile = blockIdx.x % grid_tiles; int64_t(tile) * kTile < len; tile += grid_tiles) {
+    const int64_t left = len - int64_t(tile) * kTile;
+    const int nvalid = int(left > kTile ? kTile : left);
+    for (int i = threadIdx.x; i < kWaves * kRadix; i += kThreads) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    const int64_t tile_base = row * n + int64_t(tile) * kTile;
+    const int chunk = w * (kTile / kWaves);
 #pragma unroll 4
-  for (int i = 0; i < kItems; ++i) {
-    const int e = chunk + i * kWave + lane;
-    const bool valid = e < nvalid;
-    uint32_t key = 0;
-    if (valid) key = FIRST ? first_key<MAG>(x[tile_base + e]) : keys[tile_base + e];
-    count_digit(cnt[w], (key >> shift) & (kRadix - 1), valid, lane);
-  }
-  __syncthreads();
-  const int d = threadIdx.x;
-  uint32_t tot = 0;
+    for (int i = 0; i < kItems; ++i) {
+      const int e = chunk + i * kWave + lane;
+      const bool valid = e < nvalid;
+      uint32_t key = 0;
+      if (valid) key = FIRST ? first_key<MAG>(x[tile_base + e]) : keys[tile_base + e];
+      count_digit(cnt[w], (key >> shift) & (kRadix - 1), valid, lane);
+    }
+    __syncthreads();
+    const int d = threadIdx.x;
+    uint32_t tot = 0;
 #pragma unroll
-  for (int q = 0; q < kWaves; ++q) tot += cnt[q][d];
-  hist[(row * kRadix + d) * tiles + tile] = tot;
+    for (int q = 0; q < kWaves; ++q) tot += cnt[q][d];
+    hist[(row * kRadix + d) * tiles + tile] = tot;
+    __syncthreads();
+  }
 }
 
 // ---- 2. exclusive scan over tiles, per (row, digit) -------------------------------------------
 // wide: one workgroup per (row, digit); narrow: one workgroup per row, thread = digit.
-// `tiles` is the stride of the histogram; with `sel` only the tiles of the row's candidate list
-// are scanned.
-__device__ __forceinline__ int used_tiles(int64_t row, int tiles, const RowSel* __restrict__ sel) {
-  if (sel == nullptr) return tiles;
-  return int((int64_t(sel[row].cn) + kTile - 1) / kTile);
+// `tiles` is the stride of the histogram; only the tiles of the list are scanned.
+__device__ __forceinline__ int used_tiles(int64_t row, int64_t n, const RowSel* __restrict__ sel) {
+  return int((pass_length(row, n, sel) + kTile - 1) / kTile);
 }
 
-// Totals of the per-tile candidate counts of one row (first pass of a candidate sort).
-__device__ __forceinline__ void total_candidates(int64_t row, int tiles,
-                                                 const uint32_t* __restrict__ tcnt,
-                                                 const uint32_t* __restrict__ tabove,
-                                                 RowSel* __restrict__ sel_out, uint32_t* wave_tot) {
-  uint32_t c = 0, a = 0;
-  for (int t = threadIdx.x; t < tiles; t += kThreads) {
-    c += tcnt[row * tiles + t];
-    a += tabove[row * tiles + t];
-  }
-  uint32_t cn, above;
-  block_exclusive_scan(c, wave_tot, &cn);
-  block_exclusive_scan(a, wave_tot, &above);
-  if (threadIdx.x == 0) {
-    sel_out[row].cn = cn;
-    sel_out[row].above = int64_t(above);
-  }
-}
-
-__global__ __launch_bounds__(kThreads) void radix_scan_wide_kernel(
-    uint32_t* __restrict__ hist, uint32_t* __restrict__ dtot, const RowSel* __restrict__ sel,
-    const uint32_t* __restrict__ tcnt, const uint32_t* __restrict__ tabove,
-    RowSel* __restrict__ sel_out, int tiles) {
+__global__ __launch_bounds__(kThreads) void radix_scan_wide_kernel(uint32_t* __restrict__ hist,
+                                                                   uint32_t* __restrict__ dtot,
+                                                                   const RowSel* __restrict__ sel,
+                                                                   int64_t n, int tiles) {
   __shared__ uint32_t wave_tot[kWaves];
   uint32_t* h = hist + int64_t(blockIdx.x) * tiles;
-  if (sel_out != nullptr && blockIdx.x % kRadix == 0)
-    total_candidates(blockIdx.x / kRadix, tiles, tcnt, tabove, sel_out, wave_tot);
-  const int used = used_tiles(blockIdx.x / kRadix, tiles, sel);
+  const int used = used_tiles(blockIdx.x / kRadix, n, sel);
   uint32_t carry = 0;
   for (int c = 0; c < used; c += kThreads) {
     const int t = c + threadIdx.x;
@@ -145,15 +124,13 @@ __global__ __launch_bounds__(kThreads) void radix_scan_wide_kernel(
   if (threadIdx.x == 0) dtot[blockIdx.x] = carry;
 }
 
-__global__ __launch_bounds__(kThreads) void radix_scan_narrow_kernel(
-    uint32_t* __restrict__ hist, uint32_t* __restrict__ dtot, const RowSel* __restrict__ sel,
-    const uint32_t* __restrict__ tcnt, const uint32_t* __restrict__ tabove,
-    RowSel* __restrict__ sel_out, int tiles) {
-  __shared__ uint32_t wave_tot[kWaves];
-  if (sel_out != nullptr) total_candidates(blockIdx.x, tiles, tcnt, tabove, sel_out, wave_tot);
+__global__ __launch_bounds__(kThreads) void radix_scan_narrow_kernel(uint32_t* __restrict__ hist,
+                                                                     uint32_t* __restrict__ dtot,
+                                                                     const RowSel* __restrict__ sel,
+                                                                     int64_t n, int tiles) {
   const int64_t rd = int64_t(blockIdx.x) * kRadix + threadIdx.x;
   uint32_t* h = hist + rd * tiles;
-  const int used = used_tiles(blockIdx.x, tiles, sel);
+  const int used = used_tiles(blockIdx.x, n, sel);
   uint32_t carry = 0;
   for (int t = 0; t < used; ++t) {
     const uint32_t v = h[t];
@@ -170,98 +147,99 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     const float* __restrict__ x, const uint32_t* __restrict__ keys_in,
     const uint32_t* __restrict__ idx_in, uint32_t* __restrict__ keys_out,
     uint32_t* __restrict__ idx_out, const uint32_t* __restrict__ hist,
-    const uint32_t* __restrict__ dtot, const uint32_t* __restrict__ tcnt,
-    const RowSel* __restrict__ sel, int64_t n, int tiles, int shift) {
+    const uint32_t* __restrict__ dtot, const RowSel* __restrict__ sel, int64_t n, int tiles,
+    int grid_tiles, int shift) {
   __shared__ uint32_t cnt[kWaves][kRadix];       // per-wave digit counts, then per-wave offsets
   __shared__ uint32_t gdelta[kRadix];            // global destination minus position in the tile
   __shared__ uint32_t wave_tot[kWaves];
   __shared__ uint32_t kbuf[kTile];
   __shared__ uint32_t ibuf[kTile];
 
-  const int64_t row = blockIdx.x / tiles;
-  const int tile = blockIdx.x % tiles;
-  const int nvalid = tile_valid_count(row, tile, n, tiles, tcnt, sel);
-  if (nvalid == 0) return;
+  const int64_t row = blockIdx.x / grid_tiles;
+  const int64_t len = pass_length(row, n, sel);
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-  for (int i = threadIdx.x; i < kWaves * kRadix; i += kThreads) (&cnt[0][0])[i] = 0;
-  __syncthreads();
-
   const int64_t row_base = row * n;
-  const int64_t tile_first = int64_t(tile) * kTile;
-  const int chunk = w * (kTile / kWaves);
-  uint32_t key[kItems], idx[kItems], rank[kItems];
+  for (int tile = blockIdx.x % grid_tiles; int64_t(tile) * kTile < len; tile += grid_tiles) {
+    const int64_t tile_first = int64_t(tile) * kTile;
+    const int64_t left = len - tile_first;
+    const int nvalid = int(left > kTile ? kTile : left);
+    for (int i = threadIdx.x; i < kWaves * kRadix; i += kThreads) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+
+    const int chunk = w * (kTile / kWaves);
+    uint32_t key[kItems], idx[kItems], rank[kItems];
 #pragma unroll
-  for (int i = 0; i < kItems; ++i) {
-    const int el = chunk + i * kWave + lane;              // element of the tile
-    const int64_t e = tile_first + el;                    // element of the row
-    const bool valid = el < nvalid;
-    key[i] = 0xffffffffu;
-    idx[i] = 0;
-    if (valid) {
-      if (FIRST) {
-        const float v = x[row_base + e];
-        key[i] = first_key<MAG>(v);
-        idx[i] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(v) >> 31)) : uint32_t(e);
-      } else {
-        key[i] = keys_in[row_base + e];
-        idx[i] = idx_in[row_base + e];
+    for (int i = 0; i < kItems; ++i) {
+      const int el = chunk + i * kWave + lane;              // element of the tile
+      const int64_t e = tile_first + el;                    // element of the row
+      const bool valid = el < nvalid;
+      key[i] = 0xffffffffu;
+      idx[i] = 0;
+      if (valid) {
+        if (FIRST) {
+          const float v = x[row_base + e];
+          key[i] = first_key<MAG>(v);
+          idx[i] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(v) >> 31)) : uint32_t(e);
+        } else {
+          key[i] = keys_in[row_base + e];
+          idx[i] = idx_in[row_base + e];
+        }
+      }
+      const uint32_t d = (key[i] >> shift) & (kRadix - 1);
+      const unsigned long long vm = __ballot(valid);
+      const unsigned long long peers = match_digit(d, vm);
+      const unsigned long long lower = peers & lanemask_lt();
+      uint32_t pre = 0;
+      if (valid) {
+        pre = cnt[w][d];
+        if (lower == 0) cnt[w][d] = pre + __popcll(peers);
+      }
+      rank[i] = pre + __popcll(lower);
+    }
+    __syncthreads();
+
+    // digit d (= this thread): counts per wave -> offsets inside the tile, and the global base
+    {
+      const int d = threadIdx.x;
+      uint32_t c[kWaves], tot = 0;
+#pragma unroll
+      for (int q = 0; q < kWaves; ++q) { c[q] = cnt[q][d]; tot += c[q]; }
+      const uint32_t tile_ex = block_exclusive_scan(tot, wave_tot, nullptr);
+      const uint32_t dt = dtot[row * kRadix + d];
+      const uint32_t digit_base = block_exclusive_scan(dt, wave_tot, nullptr);
+      uint32_t run = tile_ex;
+#pragma unroll
+      for (int q = 0; q < kWaves; ++q) { cnt[q][d] = run; run += c[q]; }
+      gdelta[d] = digit_base + hist[(row * kRadix + d) * tiles + tile] - tile_ex;
+    }
+    __syncthreads();
+
+    // place the pairs at their position in the sorted tile
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+      const int el = chunk + i * kWave + lane;
+      if (el < nvalid) {
+        const uint32_t d = (key[i] >> shift) & (kRadix - 1);
+        const uint32_t lp = cnt[w][d] + rank[i];
+        kbuf[lp] = key[i];
+        ibuf[lp] = idx[i];
       }
     }
-    const uint32_t d = (key[i] >> shift) & (kRadix - 1);
-    const unsigned long long vm = __ballot(valid);
-    const unsigned long long peers = match_digit(d, vm);
-    const unsigned long long lower = peers & lanemask_lt();
-    uint32_t pre = 0;
-    if (valid) {
-      pre = cnt[w][d];
-      if (lower == 0) cnt[w][d] = pre + __popcll(peers);
+    __syncthreads();
+
+    for (int j = threadIdx.x; j < nvalid; j += kThreads) {
+      const uint32_t kk = kbuf[j];
+      const uint32_t d = (kk >> shift) & (kRadix - 1);
+      const int64_t dst = row_base + int64_t(gdelta[d] + uint32_t(j));
+      keys_out[dst] = kk;
+      idx_out[dst] = ibuf[j];
     }
-    rank[i] = pre + __popcll(lower);
-  }
-  __syncthreads();
-
-  // digit d (= this thread): counts per wave -> offsets inside the tile, and the global base
-  {
-    const int d = threadIdx.x;
-    uint32_t c[kWaves], tot = 0;
-#pragma unroll
-    for (int q = 0; q < kWaves; ++q) { c[q] = cnt[q][d]; tot += c[q]; }
-    const uint32_t tile_ex = block_exclusive_scan(tot, wave_tot, nullptr);
-    const uint32_t dt = dtot[row * kRadix + d];
-    const uint32_t digit_base = block_exclusive_scan(dt, wave_tot, nullptr);
-    uint32_t run = tile_ex;
-#pragma unroll
-    for (int q = 0; q < kWaves; ++q) { cnt[q][d] = run; run += c[q]; }
-    gdelta[d] = digit_base + hist[(row * kRadix + d) * tiles + tile] - tile_ex;
-  }
-  __syncthreads();
-
-  // place the pairs at their position in the sorted tile
-#pragma unroll
-  for (int i = 0; i < kItems; ++i) {
-    const int el = chunk + i * kWave + lane;
-    if (el < nvalid) {
-      const uint32_t d = (key[i] >> shift) & (kRadix - 1);
-      const uint32_t lp = cnt[w][d] + rank[i];
-      kbuf[lp] = key[i];
-      ibuf[lp] = idx[i];
-    }
-  }
-  __syncthreads();
-
-  for (int j = threadIdx.x; j < nvalid; j += kThreads) {
-    const uint32_t kk = kbuf[j];
-    const uint32_t d = (kk >> shift) & (kRadix - 1);
-    const int64_t dst = row_base + int64_t(gdelta[d] + uint32_t(j));
-    keys_out[dst] = kk;
-    idx_out[dst] = ibuf[j];
+    __syncthreads();
   }
 }
 
 // ---- candidate selection ---------------------------------------------------------------------
 // Histogram of the leading kSelBits key bits of every row (global counters, zeroed before).
-constexpr int kSelItems = 32;
-constexpr int kSelTile = kThreads * kSelItems;
 constexpr int kSelShift = 32 - kSelBits;
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* __restrict__ p, int64_t count) {
@@ -269,25 +247,43 @@ __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* __restric
   if (i < count) p[i] = 0u;
 }
 
+// Every workgroup histograms a contiguous span of its row (a multiple of kSelChunk elements) in
+// LDS (bin = LDS word: neighbouring bins, the ones a wavefront hits together, lie in different
+// banks) and adds its non-empty bins once, at the end, to one of `gcopies` global copies of the
+// row's counters, so that the chains of same-address global atomics stay short.
+constexpr int kSelChunk = kThreads * 16;
+
 template <bool MAG>
 __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float* __restrict__ x,
                                                                uint32_t* __restrict__ bins,
-                                                               int64_t n, int sel_tiles) {
+                                                               int64_t n, int64_t span, int parts,
+                                                               int gcopies) {
   __shared__ uint32_t h[kSelBins];
-  const int64_t row = blockIdx.x / sel_tiles;
-  const int64_t first = int64_t(blockIdx.x % sel_tiles) * kSelTile;
+  const int64_t row = blockIdx.x / parts;
+  const int part = blockIdx.x % parts;
+  const int64_t first = int64_t(part) * span;
+  const int64_t last = (first + span < n) ? first + span : n;
+  uint32_t* gb = bins + (row * gcopies + part % gcopies) * kSelBins;
   for (int i = threadIdx.x; i < kSelBins; i += kThreads) h[i] = 0;
   __syncthreads();
   const float* xr = x + row * n;
-#pragma unroll 8
-  for (int i = 0; i < kSelItems; ++i) {
-    const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
-    if (e < n) atomicAdd(&h[first_key<MAG>(xr[e]) >> kSelShift], 1u);
+  for (int64_t c0 = first; c0 < last; c0 += kSelChunk) {
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int64_t e = c0 + int64_t(i) * kThreads + threadIdx.x;
+      v[i] = e < last ? xr[e] : 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int64_t e = c0 + int64_t(i) * kThreads + threadIdx.x;
+      if (e < last) atomicAdd(&h[first_key<MAG>(v[i]) >> kSelShift], 1u);
+    }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < kSelBins; i += kThreads) {
     const uint32_t c = h[i];
-    if (c != 0) atomicAdd(&bins[row * kSelBins + i], c);
+    if (c != 0) atomicAdd(&gb[i], c);
   }
 }
 
@@ -298,26 +294,42 @@ __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float* __re
 template <bool MAG>
 __global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t* __restrict__ bins,
                                                                  RowSel* __restrict__ sel,
-                                                                 int64_t k, Reg R) {
+                                                                 int64_t k, int gcopies, Reg R) {
   constexpr int kPerThread = kSelBins / kThreads;
   __shared__ uint32_t wave_tot[kWaves];
   __shared__ uint32_t found[2];
   const int64_t row = blockIdx.x;
-  const uint32_t* b = bins + row * kSelBins;
+  const uint32_t* b = bins + row * gcopies * kSelBins;
   uint32_t c[kPerThread], mine = 0;
+  static_assert(kPerThread % 4 == 0, "bins are read as uint4");
 #pragma unroll
-  for (int i = 0; i < kPerThread; ++i) {
-    c[i] = b[threadIdx.x * kPerThread + i];
-    mine += c[i];
+  for (int i = 0; i < kPerThread; ++i) c[i] = 0;
+  for (int g = 0; g < gcopies; ++g) {
+    const uint4* src = reinterpret_cast<const uint4*>(b + g * kSelBins + threadIdx.x * kPerThread);
+#pragma unroll
+    for (int i = 0; i < kPerThread / 4; ++i) {
+      const uint4 v = src[i];
+      c[4 * i] += v.x; c[4 * i + 1] += v.y; c[4 * i + 2] += v.z; c[4 * i + 3] += v.w;
+    }
   }
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) mine += c[i];
   uint32_t run = block_exclusive_scan(mine, wave_tot, nullptr);
   // position q (1-based) lies in the first bin whose inclusive count reaches q
   const uint32_t q0 = uint32_t(k), q1 = uint32_t(k + 1);
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
     const uint32_t next = run + c[i];
-    if (run < q0 && q0 <= next) found[0] = threadIdx.x * kPerThread + i;
-    if (run < q1 && q1 <= next) found[1] = threadIdx.x * kPerThread + i;
+    if (run < q0 && q0 <= next) {
+      found[0] = threadIdx.x * kPerThread + i;
+      sel[row].bin_k = threadIdx.x * kPerThread + i;
+      sel[row].rank_k = q0 - run;
+    }
+    if (run < q1 && q1 <= next) {
+      found[1] = threadIdx.x * kPerThread + i;
+      sel[row].bin_k1 = threadIdx.x * kPerThread + i;
+      sel[row].rank_k1 = q1 - run;
+    }
     run = next;
   }
   __syncthreads();
@@ -329,44 +341,91 @@ __global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t*
   }
 }
 
+// Second level: the next kSelBits key bits of the elements inside the bins of positions k and
+// k+1 (counted by the compaction pass) narrow s_k and s_{k+1} down to 2*kSelBits leading bits;
+// the window is recomputed from those.
+template <bool MAG>
+__global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t* __restrict__ bins2,
+                                                                 RowSel* __restrict__ sel, Reg R) {
+  constexpr int kPerThread = kSelBins / kThreads;
+  __shared__ uint32_t wave_tot[kWaves];
+  __shared__ uint32_t found[2];
+  const int64_t row = blockIdx.x;
+  if (threadIdx.x < 2) found[threadIdx.x] = 0;       // (stays 0 only for rows with NaNs)
+  const uint32_t rank[2] = {sel[row].rank_k, sel[row].rank_k1};
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint4* src =
+        reinterpret_cast<const uint4*>(bins2 + (row * 2 + h) * kSelBins + threadIdx.x * kPerThread);
+    uint32_t c[kPerThread], mine = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread / 4; ++i) {
+      const uint4 v = src[i];
+      c[4 * i] = v.x; c[4 * i + 1] = v.y; c[4 * i + 2] = v.z; c[4 * i + 3] = v.w;
+    }
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) mine += c[i];
+    uint32_t run = block_exclusive_scan(mine, wave_tot, nullptr);
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const uint32_t next = run + c[i];
+      if (run < rank[h] && rank[h] <= next) found[h] = threadIdx.x * kPerThread + i;
+      run = next;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    static_assert(2 * kSelBits <= 32, "two levels of kSelBits bits");
+    uint32_t klo, khi;
+    key_window<MAG, 2 * kSelBits>((sel[row].bin_k << kSelBits) | found[0],
+                                  (sel[row].bin_k1 << kSelBits) | found[1], R, &klo, &khi);
+    sel[row].klo = klo;
+    sel[row].khi = khi;
+  }
+}
+
 // Ordered compaction of the candidates of every tile to the start of the tile's own slot of the
-// output arrays (row stride n, tile stride kTile), with their count, the number of elements of
-// the tile above the window, and the digit histogram of the first sorting pass.
+// output arrays (row stride n, tile stride kTile), with their count and the number of elements of
+// the tile above the window.  The candidates are staged in LDS in order, so that the slot is
+// written with full wavefronts; candidates inside the histogram bins of positions k and k+1 are
+// also counted by their next kSelBits key bits (second selection level).
 template <bool MAG>
 __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     const float* __restrict__ x, const RowSel* __restrict__ sel, uint32_t* __restrict__ keys_out,
     uint32_t* __restrict__ idx_out, uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove,
-    uint32_t* __restrict__ hist, int64_t n, int tiles) {
-  __shared__ uint32_t cnt[kWaves][kRadix];
+    uint32_t* __restrict__ bins2, int64_t n, int tiles) {
   __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
+  __shared__ uint32_t kbuf[kTile];
+  __shared__ uint32_t ibuf[kTile];
   const int64_t row = blockIdx.x / tiles;
   const int tile = blockIdx.x % tiles;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-  for (int i = threadIdx.x; i < kWaves * kRadix; i += kThreads) (&cnt[0][0])[i] = 0;
-  __syncthreads();
-  const uint32_t klo = sel[row].klo, khi = sel[row].khi;
+  // the window in value space: key order is reversed value order, and -0 == +0 either way
+  // (bound_value clamps the keys beyond the infinities, which would decode to NaN)
+  const float v_top = float(bound_value(sel[row].klo)), v_bot = float(bound_value(sel[row].khi));
+  const uint32_t bin_k = sel[row].bin_k, bin_k1 = sel[row].bin_k1;
+  uint32_t* b2 = bins2 + row * 2 * kSelBins;
   const int64_t row_base = row * n;
   const int64_t tile_first = int64_t(tile) * kTile;
   const int chunk = w * (kTile / kWaves);
-  uint32_t key[kItems], idx[kItems], pos[kItems];
+  float val[kItems];
+  uint32_t pos[kItems];
   uint32_t ncand = 0, nabove = 0;                    // wavefront totals (uniform)
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
     const int64_t e = tile_first + chunk + i * kWave + lane;
+    val[i] = e < n ? x[row_base + e] : 0.0f;
+  }
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    const int64_t e = tile_first + chunk + i * kWave + lane;
     const bool valid = e < n;
-    key[i] = 0xffffffffu;
-    idx[i] = 0;
-    if (valid) {
-      const float v = x[row_base + e];
-      key[i] = first_key<MAG>(v);
-      idx[i] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(v) >> 31)) : uint32_t(e);
-    }
-    const bool cand = valid && key[i] >= klo && key[i] <= khi;
+    const float v = MAG ? fabsf(val[i]) : val[i];
+    const bool cand = valid && v <= v_top && v >= v_bot;
     const unsigned long long cm = __ballot(cand);
-    nabove += __popcll(__ballot(valid && key[i] < klo));
+    nabove += __popcll(__ballot(valid && v > v_top));
     pos[i] = cand ? ncand + __popcll(cm & lanemask_lt()) : 0xffffffffu;
     ncand += __popcll(cm);
-    count_digit(cnt[w], key[i] & (kRadix - 1), cand, lane);
   }
   if (lane == 0) {
     wave_cand[w] = ncand;
@@ -383,124 +442,239 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
     if (pos[i] != 0xffffffffu) {
-      const int64_t dst = row_base + tile_first + before + pos[i];
-      keys_out[dst] = key[i];
-      idx_out[dst] = idx[i];
+      const int64_t e = tile_first + chunk + i * kWave + lane;
+      kbuf[before + pos[i]] = first_key<MAG>(val[i]);
+      ibuf[before + pos[i]] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(val[i]) >> 31)) : uint32_t(e);
     }
+  }
+  __syncthreads();
+  for (uint32_t j = threadIdx.x; j < total; j += kThreads) {
+    const uint32_t key = kbuf[j];
+    keys_out[row_base + tile_first + j] = key;
+    idx_out[row_base + tile_first + j] = ibuf[j];
+    const uint32_t top = key >> kSelShift;
+    const uint32_t sub = (key >> (32 - 2 * kSelBits)) & (kSelBins - 1);
+    if (top == bin_k) atomicAdd(&b2[sub], 1u);
+    if (top == bin_k1) atomicAdd(&b2[kSelBins + sub], 1u);
   }
   if (threadIdx.x == 0) {
     tcnt[row * tiles + tile] = total;
     tabove[row * tiles + tile] = above;
   }
-  const int d = threadIdx.x;
-  uint32_t tot = 0;
+}
+
+// Second compaction, in place, of every tile's slot to the refined window; adds the elements
+// that fall above it to the tile's count of elements above.
+__global__ __launch_bounds__(kThreads) void select_recompact_kernel(
+    const RowSel* __restrict__ sel, uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
+    uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove, int64_t n, int tiles) {
+  __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
+  const int64_t row = blockIdx.x / tiles;
+  const int tile = blockIdx.x % tiles;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int nvalid = int(tcnt[row * tiles + tile]);
+  if (nvalid == 0) return;
+  const uint32_t klo = sel[row].klo, khi = sel[row].khi;
+  const int64_t slot = row * n + int64_t(tile) * kTile;
+  const int chunk = w * (kTile / kWaves);
+  uint32_t key[kItems], id[kItems], pos[kItems];
+  uint32_t ncand = 0, nabove = 0;
 #pragma unroll
-  for (int q = 0; q < kWaves; ++q) tot += cnt[q][d];
-  hist[(row * kRadix + d) * tiles + tile] = tot;
+  for (int i = 0; i < kItems; ++i) {
+    const int el = chunk + i * kWave + lane;
+    const bool valid = el < nvalid;
+    key[i] = valid ? keys[slot + el] : 0u;
+    id[i] = valid ? idx[slot + el] : 0u;
+    const bool cand = valid && key[i] >= klo && key[i] <= khi;
+    const unsigned long long cm = __ballot(cand);
+    nabove += __popcll(__ballot(valid && key[i] < klo));
+    pos[i] = cand ? ncand + __popcll(cm & lanemask_lt()) : 0xffffffffu;
+    ncand += __popcll(cm);
+  }
+  if (lane == 0) {
+    wave_cand[w] = ncand;
+    wave_above[w] = nabove;
+  }
+  __syncthreads();                         // every element of the slot is in registers by now
+  uint32_t before = 0, total = 0, above = 0;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) {
+    if (q < w) before += wave_cand[q];
+    total += wave_cand[q];
+    above += wave_above[q];
+  }
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    if (pos[i] != 0xffffffffu) {
+      keys[slot + before + pos[i]] = key[i];
+      idx[slot + before + pos[i]] = id[i];
+    }
+  }
+  if (threadIdx.x == 0) {
+    tcnt[row * tiles + tile] = total;
+    tabove[row * tiles + tile] += above;
+  }
+}
+
+// One workgroup per row: exclusive prefix of the tiles' candidate counts (where each tile's
+// candidates go in the row's dense list), the length of the list and the number of elements
+// above the window.
+__global__ __launch_bounds__(kThreads) void select_offsets_kernel(const uint32_t* __restrict__ tcnt,
+                                                                  const uint32_t* __restrict__ tabove,
+                                                                  uint32_t* __restrict__ toff,
+                                                                  RowSel* __restrict__ sel,
+                                                                  int tiles) {
+  __shared__ uint32_t wave_tot[kWaves];
+  const int64_t row = blockIdx.x;
+  uint32_t carry = 0, above = 0;
+  for (int c = 0; c < tiles; c += kThreads) {
+    const int t = c + threadIdx.x;
+    const uint32_t v = (t < tiles) ? tcnt[row * tiles + t] : 0u;
+    above += (t < tiles) ? tabove[row * tiles + t] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan(v, wave_tot, &total);
+    if (t < tiles) toff[row * tiles + t] = carry + ex;
+    carry += total;
+  }
+  uint32_t above_all;
+  block_exclusive_scan(above, wave_tot, &above_all);
+  if (threadIdx.x == 0) {
+    sel[row].cn = carry;
+    sel[row].above = int64_t(above_all);
+  }
+}
+
+// Every tile's slot (in the "b" arrays) to its place in the row's dense list (in the "a" arrays).
+__global__ __launch_bounds__(kThreads) void select_gather_kernel(
+    const uint32_t* __restrict__ tcnt, const uint32_t* __restrict__ toff,
+    const uint32_t* __restrict__ slot_keys, const uint32_t* __restrict__ slot_idx,
+    uint32_t* __restrict__ keys_a, uint32_t* __restrict__ idx_a, int64_t n, int tiles) {
+  const int64_t row = blockIdx.x / tiles;
+  const int tile = blockIdx.x % tiles;
+  const uint32_t count = tcnt[row * tiles + tile];
+  if (count == 0) return;
+  uint32_t* kd = keys_a + row * n + toff[row * tiles + tile];
+  uint32_t* id = idx_a + row * n + toff[row * tiles + tile];
+  const int64_t slot = row * n + int64_t(tile) * kTile;
+  for (uint32_t j = threadIdx.x; j < count; j += kThreads) {
+    kd[j] = slot_keys[slot + j];
+    id[j] = slot_idx[slot + j];
+  }
 }
 
 // ---- pass drivers ------------------------------------------------------------------------------
-void launch_scan(int64_t rows, int tiles, const SortBuffers& B, const RowSel* sel,
-                 RowSel* sel_out, hipStream_t st) {
+void launch_scan(int64_t rows, int64_t n, int tiles, const SortBuffers& B, const RowSel* sel,
+                 hipStream_t st) {
   if (tiles <= 32)
     hipLaunchKernelGGL(radix_scan_narrow_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                       B.hist, B.dtot, sel, B.tcnt, B.tabove, sel_out, tiles);
+                       B.hist, B.dtot, sel, n, tiles);
   else
     hipLaunchKernelGGL(radix_scan_wide_kernel, dim3(unsigned(rows * kRadix)), dim3(kThreads), 0,
-                       st, B.hist, B.dtot, sel, B.tcnt, B.tabove, sel_out, tiles);
+                       st, B.hist, B.dtot, sel, n, tiles);
 }
 
+// Four passes a -> b -> a -> b -> a over lists that are already in the "a" arrays (sel != nullptr:
+// the candidate lists longer than kFinishMax), or x -> b -> a -> b -> a over whole rows.
 template <bool MAG>
-void sort_passes(const float* x, int64_t rows, int64_t n, const SortBuffers& B, hipStream_t st) {
+void sort_passes(const float* x, int64_t rows, int64_t n, const SortBuffers& B, const RowSel* sel,
+                 hipStream_t st) {
   const int tiles = int((n + kTile - 1) / kTile);
-  const unsigned blocks = unsigned(rows * tiles);
-  uint32_t* kin = nullptr;
-  uint32_t* iin = nullptr;
+  // candidate lists: a capped grid, workgroups loop over the tiles a list really has
+  int grid_tiles = tiles;
+  if (sel != nullptr) {
+    const int64_t cap = 2048 / rows;
+    grid_tiles = int(cap < 1 ? 1 : (cap < tiles ? cap : tiles));
+  }
+  const unsigned blocks = unsigned(rows * grid_tiles);
+  const bool from_x = (sel == nullptr);
+  uint32_t* kin = from_x ? nullptr : B.keys_a;
+  uint32_t* iin = from_x ? nullptr : B.idx_a;
   uint32_t* kout = B.keys_b;
   uint32_t* iout = B.idx_b;
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 8 * pass;
-    if (pass == 0)
+    if (pass == 0 && from_x)
       hipLaunchKernelGGL((radix_hist_kernel<true, MAG>), dim3(blocks), dim3(kThreads), 0, st, x,
-                         kin, B.hist, nullptr, n, tiles, shift);
+                         kin, B.hist, sel, n, tiles, grid_tiles, shift);
     else
       hipLaunchKernelGGL((radix_hist_kernel<false, MAG>), dim3(blocks), dim3(kThreads), 0, st, x,
-                         kin, B.hist, nullptr, n, tiles, shift);
-    launch_scan(rows, tiles, B, nullptr, nullptr, st);
-    if (pass == 0)
+                         kin, B.hist, sel, n, tiles, grid_tiles, shift);
+    launch_scan(rows, n, tiles, B, sel, st);
+    if (pass == 0 && from_x)
       hipLaunchKernelGGL((radix_scatter_kernel<true, MAG>), dim3(blocks), dim3(kThreads), 0, st, x,
-                         kin, iin, kout, iout, B.hist, B.dtot, nullptr, nullptr, n, tiles, shift);
+                         kin, iin, kout, iout, B.hist, B.dtot, sel, n, tiles, grid_tiles, shift);
     else
       hipLaunchKernelGGL((radix_scatter_kernel<false, MAG>), dim3(blocks), dim3(kThreads), 0, st,
-                         x, kin, iin, kout, iout, B.hist, B.dtot, nullptr, nullptr, n, tiles,
-                         shift);
-    // ping-pong: pass 0 writes b, pass 1 writes a, pass 2 writes b, pass 3 writes a
-    kin = kout;
-    iin = iout;
-    kout = (kout == B.keys_b) ? B.keys_a : B.keys_b;
-    iout = (iout == B.idx_b) ? B.idx_a : B.idx_b;
+                         x, kin, iin, kout, iout, B.hist, B.dtot, sel, n, tiles, grid_tiles, shift);
+    if (pass == 0 && from_x) {
+      kin = B.keys_b; iin = B.idx_b; kout = B.keys_a; iout = B.idx_a;
+    } else {
+      uint32_t* t = kin; kin = kout; kout = t;
+      t = iin; iin = iout; iout = t;
+    }
   }
 }
 
 template <bool MAG>
-void candidate_passes(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& R,
-                      const SortBuffers& B, hipStream_t st) {
+void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& R,
+                     const SortBuffers& B, hipStream_t st) {
   const int tiles = int((n + kTile - 1) / kTile);
   const unsigned blocks = unsigned(rows * tiles);
-  const int sel_tiles = int((n + kSelTile - 1) / kSelTile);
-  const int64_t nbins = rows * kSelBins;
+  // about 1024 workgroups in all, each with a span of at least one chunk
+  int64_t span = (n * rows + 1023) / 1024;
+  span = (span + kSelChunk - 1) / kSelChunk * kSelChunk;
+  const int parts = int((n + span - 1) / span);
+  const int gcopies = sel_global_copies(rows);
+  const int64_t nbins = rows * (gcopies + 2) * kSelBins;       // both selection levels
   hipLaunchKernelGGL(fill_zero_kernel, dim3(unsigned((nbins + kThreads - 1) / kThreads)),
                      dim3(kThreads), 0, st, B.bins, nbins);
-  hipLaunchKernelGGL((select_hist_kernel<MAG>), dim3(unsigned(rows * sel_tiles)), dim3(kThreads), 0,
-                     st, x, B.bins, n, sel_tiles);
+  hipLaunchKernelGGL((select_hist_kernel<MAG>), dim3(unsigned(rows * parts)), dim3(kThreads), 0, st,
+                     x, B.bins, n, span, parts, gcopies);
   hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                     B.bins, B.sel, k, R);
-  // candidates into the per-tile slots of the "a" arrays, with the histogram of pass 0
+                     B.bins, B.sel, k, gcopies, R);
+  // first-level candidates into the per-tile slots of the "b" arrays; second level; slots
+  // narrowed in place; dense lists
   hipLaunchKernelGGL((select_compact_kernel<MAG>), dim3(blocks), dim3(kThreads), 0, st, x, B.sel,
-                     B.keys_a, B.idx_a, B.tcnt, B.tabove, B.hist, n, tiles);
-  launch_scan(rows, tiles, B, nullptr, B.sel, st);
-  hipLaunchKernelGGL((radix_scatter_kernel<false, MAG>), dim3(blocks), dim3(kThreads), 0, st, x,
-                     B.keys_a, B.idx_a, B.keys_b, B.idx_b, B.hist, B.dtot, B.tcnt, nullptr, n,
-                     tiles, 0);
-  // passes 1..3 on the dense candidate lists: b -> a -> b -> a
-  uint32_t* kin = B.keys_b;
-  uint32_t* iin = B.idx_b;
-  uint32_t* kout = B.keys_a;
-  uint32_t* iout = B.idx_a;
-  for (int pass = 1; pass < 4; ++pass) {
-    const int shift = 8 * pass;
-    hipLaunchKernelGGL((radix_hist_kernel<false, MAG>), dim3(blocks), dim3(kThreads), 0, st, x, kin,
-                       B.hist, B.sel, n, tiles, shift);
-    launch_scan(rows, tiles, B, B.sel, nullptr, st);
-    hipLaunchKernelGGL((radix_scatter_kernel<false, MAG>), dim3(blocks), dim3(kThreads), 0, st, x,
-                       kin, iin, kout, iout, B.hist, B.dtot, nullptr, B.sel, n, tiles, shift);
-    uint32_t* t = kin; kin = kout; kout = t;
-    t = iin; iin = iout; iout = t;
-  }
+                     B.keys_b, B.idx_b, B.tcnt, B.tabove, B.bins2, n, tiles);
+  hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
+                     B.bins2, B.sel, R);
+  hipLaunchKernelGGL(select_recompact_kernel, dim3(blocks), dim3(kThreads), 0, st, B.sel, B.keys_b,
+                     B.idx_b, B.tcnt, B.tabove, n, tiles);
+  hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
+                     B.tabove, B.toff, B.sel, tiles);
+  hipLaunchKernelGGL(select_gather_kernel, dim3(blocks), dim3(kThreads), 0, st, B.tcnt, B.toff,
+                     B.keys_b, B.idx_b, B.keys_a, B.idx_a, n, tiles);
 }
 
 }  // namespace
 
 int radix_tiles(int64_t n) { return int((n + kTile - 1) / kTile); }
 
+int sel_global_copies(int64_t rows) { return rows >= 64 ? 1 : int(64 / rows) > 16 ? 16 : int(64 / rows); }
+
 // Sorted keys end in B.keys_a, their index payload in B.idx_a.
 int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, const SortBuffers& B,
                           hipStream_t st) {
   const int64_t tiles = radix_tiles(n);
   if (rows * tiles > 0x7fffffffLL || rows * kRadix > 0x7fffffffLL) return -1;
-  if (mag) sort_passes<true>(x, rows, n, B, st);
-  else sort_passes<false>(x, rows, n, B, st);
+  if (mag) sort_passes<true>(x, rows, n, B, nullptr, st);
+  else sort_passes<false>(x, rows, n, B, nullptr, st);
   return 0;
 }
 
-// Candidate lists sorted in B.keys_a / B.idx_a (row stride n), B.sel[row] = {window, count, above}.
-int launch_candidate_sort(bool mag, const float* x, int64_t rows, int64_t n, int64_t k,
-                          const Reg& R, const SortBuffers& B, hipStream_t st) {
+int launch_candidate_lists(bool mag, const float* x, int64_t rows, int64_t n, int64_t k,
+                           const Reg& R, const SortBuffers& B, hipStream_t st) {
   const int64_t tiles = radix_tiles(n);
   if (k < 1 || k >= n) return -1;
   if (rows * tiles > 0x7fffffffLL || rows * kRadix > 0x7fffffffLL) return -1;
-  if (mag) candidate_passes<true>(x, rows, n, k, R, B, st);
-  else candidate_passes<false>(x, rows, n, k, R, B, st);
+  if (mag) candidate_lists<true>(x, rows, n, k, R, B, st);
+  else candidate_lists<false>(x, rows, n, k, R, B, st);
+  return 0;
+}
+
+int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& B, hipStream_t st) {
+  if (mag) sort_passes<true>(nullptr, rows, n, B, B.sel, st);
+  else sort_passes<false>(nullptr, rows, n, B, B.sel, st);
   return 0;
 }
 
