@@ -1,11 +1,12 @@
-// Long rows, after the segmented sort: isotonic solve on the sorted keys, then the sparse
-// un-sort scatter and the JVP.
+// Long rows, after the sort of the row (or of its candidate list): the launches that use it.
 //
-//   solve    : one workgroup per row grows the single pooled block [a, b] outwards from (k, k+1)
-//              in chunks of 1024 sorted positions, keeping float64 power sums of the block
-//              (centred on s_k for the mask); writes (a, b, gamma, d gamma) per row.
-//   fill     : dense zero fill of the outputs (everything below the block is exactly 0).
-//   epilogue : positions 1..b only: y (and dy) from (a, b, gamma), scattered through sigma.
+//   solve  : one workgroup per row grows the single pooled block [a, b] outwards from (k, k+1)
+//            (long_solve.hpp) and writes (a, b, gamma, d gamma, value window) per row; rows whose
+//            short candidate list was sorted and solved by one workgroup are skipped.
+//   dense  : one coalesced pass in original order for everything outside the block's value
+//            window: literal 1 (mask) or x/(1+lambda) (magnitude) above it, literal 0 below it.
+//   window : the sorted positions inside the window: y (and dy) from (a, b, gamma, d gamma),
+//            scattered through sigma.
 #include <hip/hip_runtime.h>
 
 #ifdef TOPK_PHASE_TRACE
