@@ -100,6 +100,20 @@ int topkmag_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, i
                 double p, double lambda, float* out, float* jvp_out, void* stream);
 
 /*
+ * Vector-Jacobian products, for reverse-mode differentiation: vjp_out = cotangent . (d y / d x).
+ * Both operators are gradients in their first argument of the convex function f_{phi,R}(., 1_k)
+ * (Prop. 2: y = grad_1 f_{phi,R}(x, 1_k)), so their Jacobians are symmetric wherever they exist
+ * (for the magnitude operator J = diag(sign x) J_s diag(sign x) with J_s symmetric), and the
+ * closed form of Prop. 7 serves both directions: these calls compute exactly what the *_jvp calls
+ * compute, with the cotangent in the place of the tangent.  Same arguments, layout and errors;
+ * `out` may be NULL.
+ */
+int topk_mask_vjp(const float* theta, const float* cotangent, int64_t rows, int64_t n, int64_t k,
+                  double p, double lambda, float* out, float* vjp_out, void* stream);
+int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n, int64_t k,
+                double p, double lambda, float* out, float* vjp_out, void* stream);
+
+/*
  * The sorting permutation itself (Sec. 3, argsort): perm_out[r][i] = original index of the i-th
  * largest value of row r (0-based).  This is the permutation the operators above use.
  */

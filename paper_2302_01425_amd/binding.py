@@ -17,8 +17,8 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
 TOPK_OP_MASK_FWD, TOPK_OP_MASK_JVP, TOPK_OP_MAG_FWD, TOPK_OP_MAG_JVP, TOPK_OP_ARGSORT = range(5)
 
 EXPORTS = (
-    "topk_mask_fwd", "topk_mask_jvp", "topkmag_fwd", "topkmag_jvp", "topk_argsort_desc",
-    "topk_workspace_bytes", "topk_set_workspace", "topk_strerror",
+    "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
+    "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace", "topk_strerror",
 )
 
 _lib = None
@@ -43,9 +43,11 @@ def load() -> ctypes.CDLL:
     L.topk_mask_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
     L.topkmag_fwd.argtypes = [vp, i64, i64, i64, dbl, dbl, vp, vp]
     L.topkmag_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
+    L.topk_mask_vjp.argtypes = L.topk_mask_jvp.argtypes
+    L.topkmag_vjp.argtypes = L.topkmag_jvp.argtypes
     L.topk_argsort_desc.argtypes = [vp, i64, i64, vp, vp]
-    for name in ("topk_mask_fwd", "topk_mask_jvp", "topkmag_fwd", "topkmag_jvp",
-                 "topk_argsort_desc"):
+    for name in ("topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp",
+                 "topkmag_vjp", "topk_argsort_desc"):
         getattr(L, name).restype = ci
     L.topk_workspace_bytes.argtypes = [ci, i64, i64, i64, dbl]
     L.topk_workspace_bytes.restype = ctypes.c_size_t
@@ -155,6 +157,35 @@ def topkmag_jvp(x, tangent, k, p, lam, out=None, jvp_out=None, want_out=True, st
                               float(lam), None if out is None else out.data_ptr(),
                               jvp_out.data_ptr(), _stream(stream)), "topkmag_jvp")
     return out, jvp_out
+
+
+def topk_mask_vjp(theta, cotangent, k, p, lam, out=None, vjp_out=None, want_out=True, stream=None):
+    """Returns (out, vjp_out); out is None when want_out is False and no out tensor was given."""
+    theta = _dev_f32(theta, "theta")
+    cotangent = _dev_f32(cotangent, "cotangent")
+    rows, n = theta.shape
+    if out is None and want_out:
+        out = torch.empty_like(theta)
+    vjp_out = torch.empty_like(theta) if vjp_out is None else _dev_f32(vjp_out, "vjp_out")
+    ensure_workspace(TOPK_OP_MASK_JVP, rows, n, k, p, theta.device)
+    _check(load().topk_mask_vjp(theta.data_ptr(), cotangent.data_ptr(), rows, n, int(k), float(p),
+                                float(lam), None if out is None else out.data_ptr(),
+                                vjp_out.data_ptr(), _stream(stream)), "topk_mask_vjp")
+    return out, vjp_out
+
+
+def topkmag_vjp(x, cotangent, k, p, lam, out=None, vjp_out=None, want_out=True, stream=None):
+    x = _dev_f32(x, "x")
+    cotangent = _dev_f32(cotangent, "cotangent")
+    rows, n = x.shape
+    if out is None and want_out:
+        out = torch.empty_like(x)
+    vjp_out = torch.empty_like(x) if vjp_out is None else _dev_f32(vjp_out, "vjp_out")
+    ensure_workspace(TOPK_OP_MAG_JVP, rows, n, k, p, x.device)
+    _check(load().topkmag_vjp(x.data_ptr(), cotangent.data_ptr(), rows, n, int(k), float(p),
+                              float(lam), None if out is None else out.data_ptr(),
+                              vjp_out.data_ptr(), _stream(stream)), "topkmag_vjp")
+    return out, vjp_out
 
 
 def topk_argsort_desc(theta, perm_out=None, stream=None):

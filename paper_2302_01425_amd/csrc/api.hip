@@ -185,6 +185,17 @@ int topkmag_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, i
   return run_operator(true, x, tangent, rows, n, k, p, lambda, out, jvp_out, false, true, stream);
 }
 
+// The Jacobians are symmetric (see the header): the VJP is the JVP of the cotangent.
+int topk_mask_vjp(const float* theta, const float* cotangent, int64_t rows, int64_t n, int64_t k,
+                  double p, double lambda, float* out, float* vjp_out, void* stream) {
+  return topk_mask_jvp(theta, cotangent, rows, n, k, p, lambda, out, vjp_out, stream);
+}
+
+int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n, int64_t k,
+                double p, double lambda, float* out, float* vjp_out, void* stream) {
+  return topkmag_jvp(x, cotangent, rows, n, k, p, lambda, out, vjp_out, stream);
+}
+
 int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm_out,
                       void* stream) {
   if (rows < 0 || n < 1 || n >= (int64_t(1) << 30)) return TOPK_ERR_INVALID;

@@ -287,9 +287,12 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 
     TOPK_MED_MARK(2);
     // ---- 3. ordered compaction of the candidates into (ka, ia) ----------------------------------
+    // the window in value space (key order is reversed value order, -0 == +0 either way; keys
+    // beyond the infinities are clamped, they would decode to NaN)
+    const float v_top = float(bound_value(klo)), v_bot = float(bound_value(khi));
     uint32_t above = 0;                    // per wavefront, summed at the end
     for (int tile_first = 0; tile_first < n; tile_first += kCTile) {
-      uint32_t key[kCItems], idx[kCItems], pos[kCItems];
+      uint32_t pos[kCItems];
       float xv[kCItems];
       uint32_t ncand = 0;
 #pragma unroll
@@ -301,16 +304,10 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
       for (int i = 0; i < kCItems; ++i) {
         const int e = tile_first + w * (kCItems * kWave) + i * kWave + lane;
         const bool valid = e < n;
-        key[i] = 0xffffffffu;
-        idx[i] = 0;
-        if (valid) {
-          const float v = xv[i];
-          key[i] = first_key<MAG>(v);
-          idx[i] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(v) >> 31)) : uint32_t(e);
-        }
-        const bool cand = valid && key[i] >= klo && key[i] <= khi;
+        const float v = MAG ? fabsf(xv[i]) : xv[i];
+        const bool cand = valid && v <= v_top && v >= v_bot;
         const unsigned long long cm = __ballot(cand);
-        above += __popcll(__ballot(valid && key[i] < klo));
+        above += __popcll(__ballot(valid && v > v_top));
         pos[i] = cand ? ncand + __popcll(cm & lanemask_lt()) : 0xffffffffu;
         ncand += __popcll(cm);
       }
@@ -327,8 +324,10 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 #pragma unroll
       for (int i = 0; i < kCItems; ++i) {
         if (pos[i] != 0xffffffffu) {
-          ka[cn + before + pos[i]] = key[i];
-          ia[cn + before + pos[i]] = idx[i];
+          const int e = tile_first + w * (kCItems * kWave) + i * kWave + lane;
+          ka[cn + before + pos[i]] = first_key<MAG>(xv[i]);
+          ia[cn + before + pos[i]] =
+              MAG ? ((uint32_t(e) << 1) | (__float_as_uint(xv[i]) >> 31)) : uint32_t(e);
         }
       }
       cn += total;

@@ -103,7 +103,11 @@ struct Pool {
     // the scale of gamma; steps below 1e-13 lambda are rounding noise of the expanded cubic
     // (the outputs need gamma to ~1e-7 lambda only).
     double a = lo, b = hi;
-    double x = 0.5 * (a + b);
+    // start from the root the cubic would have if all s_i sat at their mean:
+    // cnt (x - mean)^3 = -lambda^3 m  (float32 cube root: it is only a starting point)
+    const double rc = recip(cnt);
+    double x = S.s1 * rc - R.lambda * double(cbrtf(float(m * rc)));
+    if (!(x > a && x < b)) x = 0.5 * (a + b);
     const double tol = 1e-13 * R.lambda;
     for (int it = 0; it < 64; ++it) {
       const double F = cubic(x, cnt, m, S, R);

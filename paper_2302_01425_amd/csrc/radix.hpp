@@ -78,7 +78,11 @@ __device__ __forceinline__ void key_window(uint32_t bin_k, uint32_t bin_k1, cons
   khi = khi > 0xfffffffdu ? 0xffffffffu : khi + 2u;
   uint32_t klo = desc_key(float(left_lim));
   klo = klo < 2u ? 0u : klo - 2u;
-  *klo_out = klo < first_k ? klo : first_k;
+  klo = klo < first_k ? klo : first_k;
+  // 0x80000000 would be the key of -0.0, which desc_key folds onto +0.0 (0x7fffffff): start the
+  // window at the zeros, so that "key >= klo" and "value <= value(klo)" select the same elements
+  if (klo == 0x80000000u) klo = 0x7fffffffu;
+  *klo_out = klo;
   *khi_out = khi > last_k1 ? khi : last_k1;
 }
 

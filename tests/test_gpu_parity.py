@@ -233,6 +233,27 @@ def test_values_closer_than_the_truncated_sort_key(gpu, oracle):
             run_case(gpu, oracle, "mag", x, t, k, P2, 0.05)
 
 
+def test_vjp_against_the_transposed_jacobian_of_the_oracle(gpu, oracle):
+    """The oracle's Jacobian, column by column from its JVP on unit tangents, transposed and applied
+    to a cotangent, against the library's VJP entry points (which rely on the symmetry)."""
+    r = np.random.default_rng(21)
+    for op, n, k, p, lam in [("mask", 12, 3, P2, 0.7), ("mask", 20, 5, P43, 1.5), ("mag", 16, 4, P2, 0.4),
+                             ("mask", 1500, 40, P2, 0.3), ("mag", 1300, 100, P2, 0.05)]:
+        x = r.normal(size=(2, n)).astype(np.float32)
+        c = r.normal(size=(2, n)).astype(np.float32)
+        ofn = oracle.topk_mask if op == "mask" else oracle.topkmag
+        ref = np.zeros((2, n))
+        for j in range(n):                               # column j of J: JVP of the j-th unit vector
+            e = np.zeros((2, n), dtype=np.float32)
+            e[:, j] = 1.0
+            col = np.asarray(ofn(x, k, p, lam, tangent=e)["jvp"], dtype=np.float64)
+            ref[:, j] = (col * c.astype(np.float64)).sum(axis=1)       # (J^T c)_j = <column j, c>
+        fn = gpu.topk_mask_vjp if op == "mask" else gpu.topkmag_vjp
+        out, vjp = fn(dev(x), dev(c), k, p, lam)
+        close(host(vjp), ref, f"vjp {op} n={n}")
+        close(host(out), ofn(x, k, p, lam, tangent=c)["out"], "out")
+
+
 def test_determinism_and_streams(gpu):
     import torch
     from paper_2302_01425_amd.workloads import WORKLOADS
