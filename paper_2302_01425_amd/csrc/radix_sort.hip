@@ -620,8 +620,9 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
                      const SortBuffers& B, hipStream_t st) {
   const int tiles = int((n + kTile - 1) / kTile);
   const unsigned blocks = unsigned(rows * tiles);
-  // about 1024 workgroups in all, each with a span of at least one chunk
-  int64_t span = (n * rows + 1023) / 1024;
+  // about 2048 workgroups in all (fewer do not keep HBM busy), each with a span of at least one
+  // chunk
+  int64_t span = (n * rows + 2047) / 2048;
   span = (span + kSelChunk - 1) / kSelChunk * kSelChunk;
   const int parts = int((n + span - 1) / span);
   const int gcopies = sel_global_copies(rows);

@@ -157,6 +157,29 @@ def test_long_rows_kinks_ties_and_full_sort_agreement(gpu, oracle, monkeypatch):
             assert np.array_equal(o_def, o_alt) and np.array_equal(j_def, j_alt), (mode, op, p, k, lam)
 
 
+@pytest.mark.parametrize("mode", ["auto", "select"])
+def test_degenerate_windows(gpu, oracle, monkeypatch, mode):
+    """Rows whose candidate window degenerates: constant rows (one key), two values, windows that
+    touch +0 / -0, rows of mostly zeros where s_k itself is zero."""
+    if mode != "auto":
+        monkeypatch.setenv("TOPK_LONG_ROWS", mode)
+    r = np.random.default_rng(31)
+    n = 6000
+    t = r.normal(size=(6, n)).astype(np.float32)
+    x = np.empty((6, n), dtype=np.float32)
+    x[0] = 1.25                                               # constant
+    x[1] = np.where(r.random(n) < 0.3, 2.0, -1.0)             # two values
+    x[2] = np.where(r.random(n) < 0.5, 0.0, -0.0)             # zeros of both signs only
+    x[3] = r.normal(size=n) * (r.random(n) < 0.02)            # sparse: s_k is an exact zero for large k
+    x[3, ::7] = -0.0
+    x[4] = np.round(r.normal(size=n) * 2) * np.float32(1e-38)   # tiny values around zero (denormals)
+    x[5] = -np.abs(r.normal(size=n))                          # all negative
+    for k in (1, 100, n // 2, n - 1):
+        for p, lam in ((P2, 0.5), (P43, 0.5), (P2, 1e-3)):
+            run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
+        run_case(gpu, oracle, "mag", x, t, k, P2, 0.1, check_perm=False)
+
+
 @pytest.mark.parametrize("mode", ["select", "sort"])
 def test_long_rows_multi_launch_paths(gpu, oracle, monkeypatch, mode):
     """The multi-launch paths (candidate selection + sort of the candidates; full sort), which by
@@ -183,6 +206,13 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", x, t, n // 20, P2, 0.05, check_perm=False)
     run_case(gpu, oracle, "mask", x, t, n // 3, P43, 2.0, check_perm=False)
     run_case(gpu, oracle, "mag", x, t, n // 10, P2, 0.01, check_perm=False)
+    # mostly exact zeros of both signs: s_k is a zero, the window starts at the zeros
+    z = (r.normal(size=(2, n)) * (r.random((2, n)) < 0.02)).astype(np.float32)
+    z[:, ::5] = -0.0
+    z[1] = 3.5                                                # and a constant row
+    run_case(gpu, oracle, "mag", z, t, n // 10, P2, 0.1, check_perm=False)
+    run_case(gpu, oracle, "mask", z, t, n // 10, P2, 0.5, check_perm=False)
+    run_case(gpu, oracle, "mask", z, t, 100, P43, 0.2, check_perm=False)
 
 
 # ---- paper examples through the GPU path ----------------------------------------------------------
