@@ -361,7 +361,19 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
         constexpr int H = GL / 2;
         const int t = lr & (H - 1);
         const bool left = lr >= H;
+        bool first_chunk = true;
         while (pending) {
+          if (!first_chunk) {
+            // the tests are monotone along each side: if neither immediate neighbour of the block
+            // violates now, no position does, and the growth is over (this replaces a whole
+            // chunk step that would find nothing)
+            const double dj = double(ls[b < nn ? b : nn - 1]) - center;
+            const double di = double(ls[a >= 2 ? a - 2 : 0]) - center;
+            const bool add_r = grew & (b < nn) & P::right_violates(dj, cnt, m, S, R);
+            const bool add_l = grew & (a > 1) & P::left_violates(di, cnt, m, S, R);
+            if (!__any(add_r | add_l)) break;
+          }
+          first_chunk = false;
           const int q = left ? a - 2 - t : b + t;            // 0-based sorted position
           const bool ok = grew & (left ? q >= 0 : q < nn);
           const float v = ls[ok ? q : 0];
