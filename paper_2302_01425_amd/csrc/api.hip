@@ -58,7 +58,7 @@ LongMode long_mode() {
 }
 
 struct Layout {
-  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, bins, bins2, tcnt, tabove, toff, sel, total;
+  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, hpart, bins, tile_hist2, bins2, tcnt, tabove, toff, sel, total;
 };
 
 Layout layout_for(int64_t rows, int64_t n) {
@@ -73,8 +73,10 @@ Layout layout_for(int64_t rows, int64_t n) {
   L.hist = off; off += align_up(size_t(rows) * 256 * tiles * 4);
   L.dtot = off; off += align_up(size_t(rows) * 256 * 4);
   L.info = off; off += align_up(size_t(rows) * sizeof(RowInfo));
-  L.bins = off; off += size_t(rows) * topk::sel_global_copies(rows) * topk::kSelBins * 4;
-  L.bins2 = off; off += align_up(size_t(rows) * 2 * topk::kSelBins * 4);
+  L.hpart = off; off += align_up(size_t(rows) * topk::sel_parts(rows, n) * topk::kSelBins * 4);
+  L.bins = off; off += align_up(size_t(rows) * topk::kSelSlices * topk::kSelBins * 4);
+  L.tile_hist2 = off; off += align_up(size_t(rows) * tiles * 2 * topk::kSel2Bins * 4);
+  L.bins2 = off; off += align_up(size_t(rows) * topk::kSelSlices * 2 * topk::kSel2Bins * 4);
   L.tcnt = off; off += align_up(size_t(rows) * tiles * 4);
   L.tabove = off; off += align_up(size_t(rows) * tiles * 4);
   L.toff = off; off += align_up(size_t(rows) * tiles * 4);
@@ -94,7 +96,9 @@ int carve(int64_t rows, int64_t n, SortBuffers* B) {
   B->hist = reinterpret_cast<uint32_t*>(base + L.hist);
   B->dtot = reinterpret_cast<uint32_t*>(base + L.dtot);
   B->info = reinterpret_cast<RowInfo*>(base + L.info);
+  B->hpart = reinterpret_cast<uint32_t*>(base + L.hpart);
   B->bins = reinterpret_cast<uint32_t*>(base + L.bins);
+  B->tile_hist2 = reinterpret_cast<uint32_t*>(base + L.tile_hist2);
   B->bins2 = reinterpret_cast<uint32_t*>(base + L.bins2);
   B->tcnt = reinterpret_cast<uint32_t*>(base + L.tcnt);
   B->tabove = reinterpret_cast<uint32_t*>(base + L.tabove);

@@ -38,8 +38,11 @@ struct RowSel {
   uint32_t rank_k, rank_k1;
 };
 
-constexpr int kSelBits = 12;              // leading key bits of the selection histogram
+constexpr int kSelBits = 12;              // leading key bits of the first selection histogram
 constexpr int kSelBins = 1 << kSelBits;
+constexpr int kSel2Bits = 8;              // further key bits of the second one
+constexpr int kSel2Bins = 1 << kSel2Bits;
+constexpr int kSelSlices = 16;            // partial sums a histogram is left in (see radix_sort.hip)
 
 // Device scratch of the long-row path (all carved out of the caller's workspace).
 struct SortBuffers {
@@ -50,9 +53,10 @@ struct SortBuffers {
   uint32_t* hist;     // [rows][256][tiles]
   uint32_t* dtot;     // [rows][256]
   RowInfo* info;      // [rows]
-  uint32_t* bins;     // [rows][copies][kSelBins] histogram of the leading key bits
-  uint32_t* bins2;    // [rows][2][kSelBins] the next kSelBits key bits inside the bins of k and k+1
-                      // (directly behind `bins`: one fill zeroes both)
+  uint32_t* hpart;    // [rows][parts][kSelBins] partial histograms of the leading key bits
+  uint32_t* bins;     // [rows][slices][kSelBins] the same, summed down to <= kSelSlices slices
+  uint32_t* tile_hist2;  // [rows][tiles][2][kSel2Bins] per tile: the next key bits inside the bins of k, k+1
+  uint32_t* bins2;    // [rows][slices][2][kSel2Bins] the same, summed down to <= kSelSlices slices
   uint32_t* tcnt;     // [rows][tiles] candidates per tile
   uint32_t* tabove;   // [rows][tiles] elements above the candidate window per tile
   uint32_t* toff;     // [rows][tiles] start of the tile's candidates in the row's dense list
@@ -75,8 +79,9 @@ int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t*
 
 // Long rows: segmented radix sort (result in B.keys_a / B.idx_a), then solve + scatter.
 int radix_tiles(int64_t n);
-// copies of a row's selection histogram in B.bins: [rows][copies][kSelBins]
-int sel_global_copies(int64_t rows);
+// workgroups per row of the first selection histogram, and the elements each of them covers
+int sel_parts(int64_t rows, int64_t n);
+int64_t sel_span(int64_t rows, int64_t n);
 int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, const SortBuffers& B,
                           hipStream_t st);
 // Candidate lists of up to kFinishMax elements are sorted and solved by one workgroup

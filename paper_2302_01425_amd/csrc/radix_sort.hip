@@ -242,49 +242,75 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
 // Histogram of the leading kSelBits key bits of every row (global counters, zeroed before).
 constexpr int kSelShift = 32 - kSelBits;
 
-__global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* __restrict__ p, int64_t count) {
-  const int64_t i = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-  if (i < count) p[i] = 0u;
-}
+// Device-scope atomics are slow on this multi-die part (10-25 G/s), so no histogram here uses
+// them: every workgroup writes its own partial histogram, and reduce_partials_kernel adds them up
+// in two stages (the second stage is the loop over `slices` in the kernels that read the result).
 
 // Every workgroup histograms a contiguous span of its row (a multiple of kSelChunk elements) in
 // LDS (bin = LDS word: neighbouring bins, the ones a wavefront hits together, lie in different
-// banks) and adds its non-empty bins once, at the end, to one of `gcopies` global copies of the
-// row's counters, so that the chains of same-address global atomics stay short.
-constexpr int kSelChunk = kThreads * 16;
+// banks) and writes the whole histogram to its own slot: partial[row][part][kSelBins].
+constexpr int kSelThreads = 1024;
+constexpr int kSelChunk = kSelThreads * 16;
 
 template <bool MAG>
-__global__ __launch_bounds__(kThreads) void select_hist_kernel(const float* __restrict__ x,
-                                                               uint32_t* __restrict__ bins,
-                                                               int64_t n, int64_t span, int parts,
-                                                               int gcopies) {
+__global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const float* __restrict__ x,
+                                                                  uint32_t* __restrict__ partial,
+                                                                  int64_t n, int64_t span,
+                                                                  int parts) {
   __shared__ uint32_t h[kSelBins];
   const int64_t row = blockIdx.x / parts;
   const int part = blockIdx.x % parts;
   const int64_t first = int64_t(part) * span;
   const int64_t last = (first + span < n) ? first + span : n;
-  uint32_t* gb = bins + (row * gcopies + part % gcopies) * kSelBins;
-  for (int i = threadIdx.x; i < kSelBins; i += kThreads) h[i] = 0;
+  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) h[i] = 0;
   __syncthreads();
   const float* xr = x + row * n;
   for (int64_t c0 = first; c0 < last; c0 += kSelChunk) {
     float v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int64_t e = c0 + int64_t(i) * kThreads + threadIdx.x;
+      const int64_t e = c0 + int64_t(i) * kSelThreads + threadIdx.x;
       v[i] = e < last ? xr[e] : 0.0f;
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int64_t e = c0 + int64_t(i) * kThreads + threadIdx.x;
+      const int64_t e = c0 + int64_t(i) * kSelThreads + threadIdx.x;
       if (e < last) atomicAdd(&h[first_key<MAG>(v[i]) >> kSelShift], 1u);
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < kSelBins; i += kThreads) {
-    const uint32_t c = h[i];
-    if (c != 0) atomicAdd(&gb[i], c);
+  uint32_t* dst = partial + (row * parts + part) * kSelBins;
+  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) dst[i] = h[i];
+}
+
+// First stage of the sum of partial histograms: src[row][parts][counters] ->
+// dst[row][slices][counters]; slice s adds the parts s, s + slices, ...  One workgroup per
+// (row, slice, 128 counters): threads 0..127 and 128..255 take alternate parts.
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const uint32_t* __restrict__ src,
+                                                                   uint32_t* __restrict__ dst,
+                                                                   int parts, int slices,
+                                                                   int counters) {
+  __shared__ uint32_t other[128];
+  const int groups = counters / 128;
+  const int g = blockIdx.x % groups;
+  const int slice = (blockIdx.x / groups) % slices;
+  const int64_t row = blockIdx.x / (groups * slices);
+  const int c = g * 128 + (threadIdx.x & 127);
+  const int half = threadIdx.x >> 7;
+  const uint32_t* s = src + row * int64_t(parts) * counters + c;
+  uint32_t acc = 0;
+  int p = slice + half * slices;
+  for (; p + 14 * slices < parts; p += 16 * slices) {    // eight loads in flight
+    uint32_t a[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a[j] = s[int64_t(p + 2 * j * slices) * counters];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc += a[j];
   }
+  for (; p < parts; p += 2 * slices) acc += s[int64_t(p) * counters];
+  if (half == 1) other[threadIdx.x & 127] = acc;
+  __syncthreads();
+  if (half == 0) dst[(row * slices + slice) * counters + c] = acc + other[threadIdx.x];
 }
 
 // One workgroup per row: the histogram bins that hold sorted positions k and k+1 bound s_k from
@@ -341,13 +367,15 @@ __global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t*
   }
 }
 
-// Second level: the next kSelBits key bits of the elements inside the bins of positions k and
-// k+1 (counted by the compaction pass) narrow s_k and s_{k+1} down to 2*kSelBits leading bits;
-// the window is recomputed from those.
+// Second level: the next kSel2Bits key bits of the elements inside the bins of positions k and
+// k+1 (counted by the compaction pass: bins2[row][slices][2][kSel2Bins]) narrow s_k and s_{k+1}
+// down to kSelBits + kSel2Bits leading bits; the window is recomputed from those.  One sub-bin
+// per thread.
 template <bool MAG>
 __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t* __restrict__ bins2,
-                                                                 RowSel* __restrict__ sel, Reg R) {
-  constexpr int kPerThread = kSelBins / kThreads;
+                                                                 RowSel* __restrict__ sel,
+                                                                 int slices, Reg R) {
+  static_assert(kSel2Bins == kThreads, "one sub-bin per thread");
   __shared__ uint32_t wave_tot[kWaves];
   __shared__ uint32_t found[2];
   const int64_t row = blockIdx.x;
@@ -355,30 +383,23 @@ __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t*
   const uint32_t rank[2] = {sel[row].rank_k, sel[row].rank_k1};
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const uint4* src =
-        reinterpret_cast<const uint4*>(bins2 + (row * 2 + h) * kSelBins + threadIdx.x * kPerThread);
-    uint32_t c[kPerThread], mine = 0;
-#pragma unroll
-    for (int i = 0; i < kPerThread / 4; ++i) {
-      const uint4 v = src[i];
-      c[4 * i] = v.x; c[4 * i + 1] = v.y; c[4 * i + 2] = v.z; c[4 * i + 3] = v.w;
+    uint32_t c = 0;
+    const uint32_t* src = bins2 + (row * slices * 2 + h) * kSel2Bins + threadIdx.x;
+    int sl = 0;
+    for (; sl + 3 < slices; sl += 4) {                   // four loads in flight
+      const uint32_t a0 = src[(sl + 0) * 2 * kSel2Bins], a1 = src[(sl + 1) * 2 * kSel2Bins];
+      const uint32_t a2 = src[(sl + 2) * 2 * kSel2Bins], a3 = src[(sl + 3) * 2 * kSel2Bins];
+      c += a0 + a1 + a2 + a3;
     }
-#pragma unroll
-    for (int i = 0; i < kPerThread; ++i) mine += c[i];
-    uint32_t run = block_exclusive_scan(mine, wave_tot, nullptr);
-#pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-      const uint32_t next = run + c[i];
-      if (run < rank[h] && rank[h] <= next) found[h] = threadIdx.x * kPerThread + i;
-      run = next;
-    }
+    for (; sl < slices; ++sl) c += src[sl * 2 * kSel2Bins];
+    const uint32_t run = block_exclusive_scan(c, wave_tot, nullptr);
+    if (run < rank[h] && rank[h] <= run + c) found[h] = threadIdx.x;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    static_assert(2 * kSelBits <= 32, "two levels of kSelBits bits");
     uint32_t klo, khi;
-    key_window<MAG, 2 * kSelBits>((sel[row].bin_k << kSelBits) | found[0],
-                                  (sel[row].bin_k1 << kSelBits) | found[1], R, &klo, &khi);
+    key_window<MAG, kSelBits + kSel2Bits>((sel[row].bin_k << kSel2Bits) | found[0],
+                                          (sel[row].bin_k1 << kSel2Bits) | found[1], R, &klo, &khi);
     sel[row].klo = klo;
     sel[row].khi = khi;
   }
@@ -388,15 +409,17 @@ __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t*
 // output arrays (row stride n, tile stride kTile), with their count and the number of elements of
 // the tile above the window.  The candidates are staged in LDS in order, so that the slot is
 // written with full wavefronts; candidates inside the histogram bins of positions k and k+1 are
-// also counted by their next kSelBits key bits (second selection level).
+// also counted by their next kSel2Bits key bits (second selection level, one histogram per tile).
 template <bool MAG>
 __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     const float* __restrict__ x, const RowSel* __restrict__ sel, uint32_t* __restrict__ keys_out,
     uint32_t* __restrict__ idx_out, uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove,
-    uint32_t* __restrict__ bins2, int64_t n, int tiles) {
+    uint32_t* __restrict__ tile_hist2, int64_t n, int tiles) {
   __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
   __shared__ uint32_t kbuf[kTile];
   __shared__ uint32_t ibuf[kTile];
+  __shared__ uint32_t h2[2 * kSel2Bins];
+  for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads) h2[i] = 0;
   const int64_t row = blockIdx.x / tiles;
   const int tile = blockIdx.x % tiles;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
@@ -404,7 +427,6 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
   // (bound_value clamps the keys beyond the infinities, which would decode to NaN)
   const float v_top = float(bound_value(sel[row].klo)), v_bot = float(bound_value(sel[row].khi));
   const uint32_t bin_k = sel[row].bin_k, bin_k1 = sel[row].bin_k1;
-  uint32_t* b2 = bins2 + row * 2 * kSelBins;
   const int64_t row_base = row * n;
   const int64_t tile_first = int64_t(tile) * kTile;
   const int chunk = w * (kTile / kWaves);
@@ -453,14 +475,17 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     keys_out[row_base + tile_first + j] = key;
     idx_out[row_base + tile_first + j] = ibuf[j];
     const uint32_t top = key >> kSelShift;
-    const uint32_t sub = (key >> (32 - 2 * kSelBits)) & (kSelBins - 1);
-    if (top == bin_k) atomicAdd(&b2[sub], 1u);
-    if (top == bin_k1) atomicAdd(&b2[kSelBins + sub], 1u);
+    const uint32_t sub = (key >> (kSelShift - kSel2Bits)) & (kSel2Bins - 1);
+    if (top == bin_k) atomicAdd(&h2[sub], 1u);
+    if (top == bin_k1) atomicAdd(&h2[kSel2Bins + sub], 1u);
   }
   if (threadIdx.x == 0) {
     tcnt[row * tiles + tile] = total;
     tabove[row * tiles + tile] = above;
   }
+  __syncthreads();
+  uint32_t* dst = tile_hist2 + (row * tiles + tile) * (2 * kSel2Bins);
+  for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads) dst[i] = h2[i];
 }
 
 // Second compaction, in place, of every tile's slot to the refined window; adds the elements
@@ -620,25 +645,25 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
                      const SortBuffers& B, hipStream_t st) {
   const int tiles = int((n + kTile - 1) / kTile);
   const unsigned blocks = unsigned(rows * tiles);
-  // about 2048 workgroups in all (fewer do not keep HBM busy), each with a span of at least one
-  // chunk
-  int64_t span = (n * rows + 2047) / 2048;
-  span = (span + kSelChunk - 1) / kSelChunk * kSelChunk;
-  const int parts = int((n + span - 1) / span);
-  const int gcopies = sel_global_copies(rows);
-  const int64_t nbins = rows * (gcopies + 2) * kSelBins;       // both selection levels
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(unsigned((nbins + kThreads - 1) / kThreads)),
-                     dim3(kThreads), 0, st, B.bins, nbins);
-  hipLaunchKernelGGL((select_hist_kernel<MAG>), dim3(unsigned(rows * parts)), dim3(kThreads), 0, st,
-                     x, B.bins, n, span, parts, gcopies);
+  const int parts = sel_parts(rows, n);
+  const int64_t span = sel_span(rows, n);
+  const int slices = parts < kSelSlices ? parts : kSelSlices;
+  hipLaunchKernelGGL((select_hist_kernel<MAG>), dim3(unsigned(rows * parts)), dim3(kSelThreads), 0,
+                     st, x, B.hpart, n, span, parts);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(unsigned(rows * slices * (kSelBins / 128))),
+                     dim3(kThreads), 0, st, B.hpart, B.bins, parts, slices, kSelBins);
   hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                     B.bins, B.sel, k, gcopies, R);
+                     B.bins, B.sel, k, slices, R);
   // first-level candidates into the per-tile slots of the "b" arrays; second level; slots
   // narrowed in place; dense lists
+  const int slices2 = tiles < kSelSlices ? tiles : kSelSlices;
   hipLaunchKernelGGL((select_compact_kernel<MAG>), dim3(blocks), dim3(kThreads), 0, st, x, B.sel,
-                     B.keys_b, B.idx_b, B.tcnt, B.tabove, B.bins2, n, tiles);
+                     B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles);
+  hipLaunchKernelGGL(reduce_partials_kernel,
+                     dim3(unsigned(rows * slices2 * (2 * kSel2Bins / 128))), dim3(kThreads), 0, st,
+                     B.tile_hist2, B.bins2, tiles, slices2, 2 * kSel2Bins);
   hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                     B.bins2, B.sel, R);
+                     B.bins2, B.sel, slices2, R);
   hipLaunchKernelGGL(select_recompact_kernel, dim3(blocks), dim3(kThreads), 0, st, B.sel, B.keys_b,
                      B.idx_b, B.tcnt, B.tabove, n, tiles);
   hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
@@ -651,7 +676,16 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
 
 int radix_tiles(int64_t n) { return int((n + kTile - 1) / kTile); }
 
-int sel_global_copies(int64_t rows) { return rows >= 64 ? 1 : int(64 / rows) > 16 ? 16 : int(64 / rows); }
+// The first histogram level: about 512 workgroups of 1024 threads in all, each with a span of
+// at least one chunk of its row.
+int64_t sel_span(int64_t rows, int64_t n) {
+  int64_t span = (n * rows + 511) / 512;
+  return (span + kSelChunk - 1) / kSelChunk * kSelChunk;
+}
+int sel_parts(int64_t rows, int64_t n) {
+  const int64_t span = sel_span(rows, n);
+  return int((n + span - 1) / span);
+}
 
 // Sorted keys end in B.keys_a, their index payload in B.idx_a.
 int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, const SortBuffers& B,

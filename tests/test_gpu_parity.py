@@ -212,7 +212,9 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     z[1] = 3.5                                                # and a constant row
     run_case(gpu, oracle, "mag", z, t, n // 10, P2, 0.1, check_perm=False)
     run_case(gpu, oracle, "mask", z, t, n // 10, P2, 0.5, check_perm=False)
-    run_case(gpu, oracle, "mask", z, t, 100, P43, 0.2, check_perm=False)
+    # (p = 4/3 without the constant row: the oracle re-solves the cubic over the whole block at
+    # every merge, which is quadratic in the block length)
+    run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
 # ---- paper examples through the GPU path ----------------------------------------------------------
