@@ -50,7 +50,7 @@ enum {
   TOPK_OK = 0,
   TOPK_ERR_INVALID = -1,        /* rows < 0, n < 1, n >= 2^30, k < 0, k > n, lambda <= 0 or non-finite */
   TOPK_ERR_NULL = -2,           /* a required pointer is NULL */
-  TOPK_ERR_UNSUPPORTED_P = -3,  /* p is neither 2 nor 4/3, or the (operator, p) pair has no kernel */
+  TOPK_ERR_UNSUPPORTED_P = -3,  /* p is neither 2 nor 4/3 */
   TOPK_ERR_WORKSPACE = -4,      /* long rows and the registered workspace is missing or too small */
   TOPK_ERR_LAUNCH = -5          /* the HIP runtime refused a launch (see hipGetLastError) */
 };
@@ -89,7 +89,11 @@ int topk_mask_jvp(const float* theta, const float* tangent, int64_t rows, int64_
 /*
  * Relaxed top-k in magnitude, forward (phi(x) = x^2/2; Prop. 2 + Prop. 6): sort |x|, solve on the
  * non-negative monotone cone, restore the signs.  Pruned entries are +0.0f.  sign(0) = 0.
- * Supported: p = 2 (pooling step of Sec. 5 "Example").  p = 4/3 returns TOPK_ERR_UNSUPPORTED_P.
+ * p = 2: pooling step of Sec. 5 "Example", gamma = sum_B s / (|B| + lambda m); kept entries
+ * before the pooled block come out as x / (1 + lambda).
+ * p = 4/3: pooling step of App. "Subproblem derivation" with phi = x^2/2: gamma is the root of
+ * sum_B (gamma - s_i)^3 + lambda^3 m gamma = 0 (m = kept positions in B); kept entries before the
+ * block come out as sign(x) g with g the root of (g - |x|)^3 + lambda^3 g = 0.
  */
 int topkmag_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p, double lambda,
                 float* out, void* stream);

@@ -123,7 +123,6 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   if (rc != TOPK_OK) return rc;
   const int pc = p_code(p);
   if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
-  if (mag && pc != topk::kP2) return TOPK_ERR_UNSUPPORTED_P;
   if (rows == 0) return TOPK_OK;          // nothing to do; pointers of empty arrays may be NULL
   if (x == nullptr) return TOPK_ERR_NULL;
   if (need_out && out == nullptr) return TOPK_ERR_NULL;
@@ -150,7 +149,7 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   const bool trivial = (k == 0 || k == n);
   const bool selected = !trivial && mode != kFullSort;
   if (selected) {
-    if (topk::launch_candidate_lists(mag, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
+    if (topk::launch_candidate_lists(mag, pc, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
     if (topk::launch_finish(mag, pc, B, need_jvp ? tangent : nullptr, rows, n, k, R, st) != 0)
       return TOPK_ERR_INVALID;
     if (topk::launch_long_list_sort(mag, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
@@ -246,7 +245,7 @@ const char* topk_strerror(int code) {
     case TOPK_OK: return "ok";
     case TOPK_ERR_INVALID: return "invalid argument (rows, n, k, lambda or alignment out of range)";
     case TOPK_ERR_NULL: return "a required pointer is NULL";
-    case TOPK_ERR_UNSUPPORTED_P: return "unsupported p (only 2 and 4/3; magnitude operator only 2)";
+    case TOPK_ERR_UNSUPPORTED_P: return "unsupported p (only 2 and 4/3)";
     case TOPK_ERR_WORKSPACE: return "workspace missing or too small (see topk_workspace_bytes)";
     case TOPK_ERR_LAUNCH: return "HIP launch failed";
     default: return "unknown error code";

@@ -87,7 +87,7 @@ int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, con
 // Candidate lists of up to kFinishMax elements are sorted and solved by one workgroup
 // (launch_finish); longer ones by the passes of launch_long_list_sort and the solve of
 // launch_long_tail.  Every kernel of either route skips the rows of the other.
-constexpr int64_t kFinishMax = 131072;
+constexpr int64_t kFinishMax = 32768;
 
 // selected: B.sel describes candidate lists (see RowSel), and rows whose list is at most
 // kFinishMax long already have their RowInfo; otherwise the "a" arrays hold fully sorted rows.
@@ -106,7 +106,7 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
 // Long rows without a full sort (0 < k < n): two histogram levels of the leading key bits -> key
 // window around positions k, k+1 that holds every element able to pool -> those candidates, in
 // index order, as a dense list per row in the "a" arrays; B.sel[row] = {window, length, above}.
-int launch_candidate_lists(bool mag, const float* x, int64_t rows, int64_t n, int64_t k,
+int launch_candidate_lists(bool mag, int pc, const float* x, int64_t rows, int64_t n, int64_t k,
                            const Reg& R, const SortBuffers& B, hipStream_t st);
 // Lists of up to kFinishMax candidates: sort + solve by one workgroup per row -> B.info[row].
 int launch_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, int64_t rows,

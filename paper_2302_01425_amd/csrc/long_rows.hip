@@ -59,11 +59,11 @@ __global__ __launch_bounds__(kSolveThreads) void long_solve_kernel(
 
 // Dense pass in original order: everything whose value lies outside the block's value window.
 // Elements inside the window are left to long_window_kernel.
-template <bool MAG>
+template <bool MAG, int PC>
 __global__ __launch_bounds__(kThreads) void long_dense_kernel(
     const float* __restrict__ x_all, const float* __restrict__ tangent_all,
     const RowInfo* __restrict__ info, float* __restrict__ out_all, float* __restrict__ jvp_all,
-    int64_t n, int chunks, float inv_1pl) {
+    int64_t n, int chunks, Reg R) {
   const int64_t row = blockIdx.x / chunks;
   const int64_t chunk = blockIdx.x % chunks;
   const RowInfo ri = info[row];
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void long_dense_kernel(
   for (int i = 0; i < 8; ++i) {
     const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
     if (e >= n) continue;
-    emit_dense_element<MAG>(ri, x_all[base + e], e, tangent, out, jvp, inv_1pl);
+    emit_dense_element<MAG, PC>(ri, x_all[base + e], e, tangent, out, jvp, R);
   }
 }
 
@@ -112,8 +112,8 @@ void launch_tail(bool selected, const SortBuffers& B, const float* x, const floa
                      B.keys_a, B.idx_a, jvp ? tangent : nullptr, B.info,
                      selected ? B.sel : nullptr, n, k, R);
   const int chunks = int((n + kThreads * 8 - 1) / (kThreads * 8));
-  hipLaunchKernelGGL((long_dense_kernel<MAG>), dim3(unsigned(rows * chunks)), dim3(kThreads), 0, st,
-                     x, tangent, B.info, out, jvp, n, chunks, float(R.inv_1pl));
+  hipLaunchKernelGGL((long_dense_kernel<MAG, PC>), dim3(unsigned(rows * chunks)), dim3(kThreads), 0,
+                     st, x, tangent, B.info, out, jvp, n, chunks, R);
   const int64_t tiles = (n + 1023) / 1024;
   const int bpr = int(tiles < 64 ? tiles : 64);
   hipLaunchKernelGGL((long_window_kernel<MAG, PC>), dim3(unsigned(rows * bpr)), dim3(kThreads), 0,
@@ -133,6 +133,8 @@ int launch_long_tail(bool mag, int pc, bool selected, const SortBuffers& B, cons
     launch_tail<false, kP43>(selected, B, x, tangent, out, jvp, rows, n, k, R, st);
   else if (mag && pc == kP2)
     launch_tail<true, kP2>(selected, B, x, tangent, out, jvp, rows, n, k, R, st);
+  else if (mag && pc == kP43)
+    launch_tail<true, kP43>(selected, B, x, tangent, out, jvp, rows, n, k, R, st);
   else return -1;
   return 0;
 }

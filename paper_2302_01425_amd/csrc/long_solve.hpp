@@ -148,15 +148,15 @@ __device__ __forceinline__ bool grow_block(const uint32_t* __restrict__ skeys, i
       const double q = double(2 * t);
       const Sums run_r{S.s1 + (ir.s1 - tr0.s1), S.s2 + (ir.s2 - tr0.s2), S.s3 + (ir.s3 - tr0.s3)};
       const Sums run_l{S.s1 + (il.s1 - tl0.s1), S.s2 + (il.s2 - tl0.s2), S.s3 + (il.s3 - tl0.s3)};
-      okr[0] = __ballot(vr[0] & P::right_violates(dr[0], cnt0 + q, m0, run_r, R));
-      okl[0] = __ballot(vl[0] & P::left_violates(dl[0], cnt0 + q, m0 + q, run_l, R));
+      okr[0] = __ballot(vr[0] & P::right_violates(dr[0], cnt0 + q, m0, run_r, R, center));
+      okl[0] = __ballot(vl[0] & P::left_violates(dl[0], cnt0 + q, m0 + q, run_l, R, center));
     }
     {
       const double q = double(2 * t + 1);
       const Sums run_r{S.s1 + (ir.s1 - tr1.s1), S.s2 + (ir.s2 - tr1.s2), S.s3 + (ir.s3 - tr1.s3)};
       const Sums run_l{S.s1 + (il.s1 - tl1.s1), S.s2 + (il.s2 - tl1.s2), S.s3 + (il.s3 - tl1.s3)};
-      okr[1] = __ballot(vr[1] & P::right_violates(dr[1], cnt0 + q, m0, run_r, R));
-      okl[1] = __ballot(vl[1] & P::left_violates(dl[1], cnt0 + q, m0 + q, run_l, R));
+      okr[1] = __ballot(vr[1] & P::right_violates(dr[1], cnt0 + q, m0, run_r, R, center));
+      okl[1] = __ballot(vl[1] & P::left_violates(dl[1], cnt0 + q, m0 + q, run_l, R, center));
     }
     // length of the leading run of accepted positions of this wavefront's 128 positions
     auto leading = [](unsigned long long ok0, unsigned long long ok1) -> int {
@@ -288,9 +288,9 @@ struct RowSolver {
     if (k >= 1 && k < n) {
       const double sk = double(key_to_float(skeys[k - 1]));
       const double sk1 = double(key_to_float(skeys[k]));
-      if (!MAG) center = sk;
+      if (P::kCentered) center = sk;
       const double dk = sk - center, dk1 = sk1 - center;
-      grow = P::seed_violates(dk, dk1, R);
+      grow = P::seed_violates(dk, dk1, R, center);
       TOPK_SOLVE_MARK(7);
       if (grow) {
         a = k;
@@ -317,7 +317,10 @@ struct RowSolver {
         TOPK_SOLVE_MARK(8);
         const double da = double(key_to_float(skeys[a - 1])) - center;
         const double db = double(key_to_float(skeys[b - 1])) - center;
-        gamma = P::pooled(double(b - a + 1), double(k - a + 1), S, R, da - R.lambda, db);
+        // bracket of the pooled value: above the singleton minimiser of position a (mask:
+        // s_a - lambda; magnitude: at least 0), below s_b (magnitude: below s_a)
+        gamma = P::pooled(double(b - a + 1), double(k - a + 1), S, R, MAG ? -center : da - R.lambda,
+                          MAG ? da : db, center);
       }
     }
     TOPK_SOLVE_MARK(9);
@@ -398,7 +401,7 @@ __device__ __forceinline__ void emit_window_position(const RowInfo& ri, int64_t 
   const double v = double(sv) - ri.center;
   const bool before = pos1 < ri.a, after = pos1 > ri.b;
   if (out != nullptr) {
-    double y = before ? (MAG ? v * R.inv_1pl : 1.0) : P::y_in_block(v, ri.gamma, R);
+    double y = before ? P::above(v, R, ri.center) : P::y_in_block(v, ri.gamma, R);
     if (after) y = 0.0;
     const float yf = float(y);
     out[o] = (MAG && yf == 0.0f) ? 0.0f : (neg ? -yf : yf);
@@ -407,7 +410,8 @@ __device__ __forceinline__ void emit_window_position(const RowInfo& ri, int64_t 
     double t = double(tangent[o]);
     if (neg) t = -t;
     if (MAG && sv == 0.0f) t = 0.0;
-    double dy = before ? (MAG ? t * R.inv_1pl : 0.0) : P::hess(v, ri.gamma, R) * (t - ri.dgamma);
+    double dy = before ? P::above_slope(v, R, ri.center) * t
+                       : P::hess(v, ri.gamma, R) * (t - ri.dgamma);
     if (after) dy = 0.0;
     float df = float(dy);
     if (MAG && sv == 0.0f) df = 0.0f;
@@ -416,24 +420,40 @@ __device__ __forceinline__ void emit_window_position(const RowInfo& ri, int64_t 
 }
 
 // Dense part of the output for one element outside the value window of the block:
-// mask: 1 above, 0 below; magnitude: x/(1+lambda) above, 0 below; JVP 0 resp. t/(1+lambda).
+// mask: 1 above, 0 below; magnitude: the element's own singleton solution above (x/(1+lambda)
+// for p = 2, sign(x) times the root of the one-element cubic for p = 4/3), 0 below; JVP 0 resp.
+// the slope of that solution times the tangent.
 // Returns false (and writes nothing) for an element inside the window.
-template <bool MAG>
+template <bool MAG, int PC>
 __device__ __forceinline__ bool emit_dense_element(const RowInfo& ri, float xv, int64_t e,
                                                    const float* __restrict__ tangent,
                                                    float* __restrict__ out, float* __restrict__ jvp,
-                                                   float inv_1pl) {
+                                                   const Reg& R) {
+  using P = Pool<MAG, PC>;
   const bool empty = ri.wa > ri.wb;
   const float v = MAG ? fabsf(xv) : xv;
   // empty window: hi_incl = s_{k+1} < lo_incl = s_k, every value is > hi or < lo
   const bool above = v > ri.hi_incl;
   const bool below = v < ri.lo_incl;
   if (!empty && !above && !below) return false;
-  if (out != nullptr) out[e] = above ? (MAG ? xv * inv_1pl : 1.0f) : 0.0f;
-  if (jvp != nullptr) {
-    float d = 0.0f;
-    if (MAG && above && xv != 0.0f) d = tangent[e] * inv_1pl;
-    jvp[e] = d;
+  if constexpr (MAG && PC == kP43) {
+    float y = 0.0f, d = 0.0f;
+    if (above && xv != 0.0f) {
+      double g, slope;
+      P::above_both(double(v), R, 0.0, &g, &slope);
+      y = float(xv < 0.0f ? -g : g);
+      if (jvp != nullptr) d = float(slope * double(tangent[e]));
+    }
+    if (out != nullptr) out[e] = y;
+    if (jvp != nullptr) jvp[e] = d;
+  } else {
+    const float inv_1pl = float(R.inv_1pl);
+    if (out != nullptr) out[e] = above ? (MAG ? xv * inv_1pl : 1.0f) : 0.0f;
+    if (jvp != nullptr) {
+      float d = 0.0f;
+      if (MAG && above && xv != 0.0f) d = tangent[e] * inv_1pl;
+      jvp[e] = d;
+    }
   }
   return true;
 }

@@ -282,7 +282,7 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
     }
     __syncthreads();
     uint32_t klo, khi;
-    key_window<MAG>(sm.found[0], sm.found[1], R, &klo, &khi);
+    key_window<MAG>(sm.found[0], sm.found[1], R, PC == kP43, &klo, &khi);
     __syncthreads();                       // the histogram's memory is reused below
 
     TOPK_MED_MARK(2);
@@ -354,7 +354,6 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 
   TOPK_MED_MARK(5);
   // ---- 6. outputs ----------------------------------------------------------------------------------
-  const float inv_1pl = float(R.inv_1pl);
   for (int e0 = threadIdx.x; e0 < n; e0 += 8 * kMT) {
     float v[8];
 #pragma unroll
@@ -362,7 +361,7 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       if (e0 + i * kMT < n)
-        emit_dense_element<MAG>(ri, v[i], int64_t(e0 + i * kMT), tangent, out, jvp, inv_1pl);
+        emit_dense_element<MAG, PC>(ri, v[i], int64_t(e0 + i * kMT), tangent, out, jvp, R);
   }
   for (int64_t pos1 = ri.wa + threadIdx.x; pos1 <= ri.wb; pos1 += kMT)
     emit_window_position<MAG, PC>(ri, pos1, key_to_float(skeys[pos1 - 1]), sidx[pos1 - 1], tangent,
@@ -435,6 +434,7 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
   if (!mag && pc == kP2) launch<false, kP2>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
   else if (!mag && pc == kP43) launch<false, kP43>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
   else if (mag && pc == kP2) launch<true, kP2>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
+  else if (mag && pc == kP43) launch<true, kP43>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
   else return -1;
   return 0;
 }
@@ -452,6 +452,9 @@ int launch_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, 
   else if (mag && pc == kP2)
     hipLaunchKernelGGL((finish_kernel<true, kP2>), grid, block, 0, st, B.keys_a, B.idx_a, B.keys_b,
                        B.idx_b, tangent, B.sel, B.info, n, k, R);
+  else if (mag && pc == kP43)
+    hipLaunchKernelGGL((finish_kernel<true, kP43>), grid, block, 0, st, B.keys_a, B.idx_a,
+                       B.keys_b, B.idx_b, tangent, B.sel, B.info, n, k, R);
   else return -1;
   return 0;
 }

@@ -60,8 +60,9 @@ __device__ __forceinline__ double bound_value(uint32_t key) {
 // and s_{k+1} at most the largest value of its bin; the window holds both bins and every element
 // that passes the necessary conditions for joining the block (pooling.hpp: left_candidate,
 // right_candidate) for ANY s_k, s_{k+1} inside those bins.
+// cubic: p = 4/3 (matters for the magnitude operator only: the mask's conditions do not depend on p).
 template <bool MAG, int BITS = kSelBits>
-__device__ __forceinline__ void key_window(uint32_t bin_k, uint32_t bin_k1, const Reg& R,
+__device__ __forceinline__ void key_window(uint32_t bin_k, uint32_t bin_k1, const Reg& R, bool cubic,
                                            uint32_t* klo_out, uint32_t* khi_out) {
   constexpr int kShift = 32 - BITS;
   const uint32_t low_bits = (1u << kShift) - 1u;
@@ -72,8 +73,14 @@ __device__ __forceinline__ void key_window(uint32_t bin_k, uint32_t bin_k1, cons
   // right candidates: x > s_k - lambda (mask), x (1 + lambda) > s_k (magnitude);
   // left candidates: x - lambda < s_{k+1}, x < s_{k+1} (1 + lambda).  Two keys of slack cover
   // the rounding of the float conversions.
-  const double right_lim = MAG ? lo_k * R.inv_1pl : lo_k - R.lambda;
-  const double left_lim = MAG ? hi_k1 * R.one_p_lambda : hi_k1 + R.lambda;
+  double right_lim = MAG ? lo_k * R.inv_1pl : lo_k - R.lambda;
+  double left_lim = MAG ? hi_k1 * R.one_p_lambda : hi_k1 + R.lambda;
+  if (MAG && cubic) {
+    // right: x above the singleton root of s_k (increasing in s_k, taken a little low);
+    // left: the singleton root of x below s_{k+1}  <=>  x < s_{k+1} + lambda s_{k+1}^(1/3)
+    right_lim = singleton_root_mag43(lo_k > 0.0 ? lo_k : 0.0, R) * (1.0 - 1e-6);
+    left_lim = hi_k1 > 0.0 ? hi_k1 + R.lambda * cbrt(hi_k1) * (1.0 + 1e-6) : R.lambda;
+  }
   uint32_t khi = desc_key(float(right_lim));
   khi = khi > 0xfffffffdu ? 0xffffffffu : khi + 2u;
   uint32_t klo = desc_key(float(left_lim));

@@ -320,7 +320,8 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const uint32_
 template <bool MAG>
 __global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t* __restrict__ bins,
                                                                  RowSel* __restrict__ sel,
-                                                                 int64_t k, int gcopies, Reg R) {
+                                                                 int64_t k, int gcopies, Reg R,
+                                                                 bool cubic) {
   constexpr int kPerThread = kSelBins / kThreads;
   __shared__ uint32_t wave_tot[kWaves];
   __shared__ uint32_t found[2];
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t*
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t klo, khi;
-    key_window<MAG>(found[0], found[1], R, &klo, &khi);
+    key_window<MAG>(found[0], found[1], R, cubic, &klo, &khi);
     sel[row].klo = klo;
     sel[row].khi = khi;
   }
@@ -374,7 +375,7 @@ __global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t*
 template <bool MAG>
 __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t* __restrict__ bins2,
                                                                  RowSel* __restrict__ sel,
-                                                                 int slices, Reg R) {
+                                                                 int slices, Reg R, bool cubic) {
   static_assert(kSel2Bins == kThreads, "one sub-bin per thread");
   __shared__ uint32_t wave_tot[kWaves];
   __shared__ uint32_t found[2];
@@ -399,7 +400,8 @@ __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t*
   if (threadIdx.x == 0) {
     uint32_t klo, khi;
     key_window<MAG, kSelBits + kSel2Bits>((sel[row].bin_k << kSel2Bits) | found[0],
-                                          (sel[row].bin_k1 << kSel2Bits) | found[1], R, &klo, &khi);
+                                          (sel[row].bin_k1 << kSel2Bits) | found[1], R, cubic,
+                                          &klo, &khi);
     sel[row].klo = klo;
     sel[row].khi = khi;
   }
@@ -641,7 +643,7 @@ void sort_passes(const float* x, int64_t rows, int64_t n, const SortBuffers& B, 
 }
 
 template <bool MAG>
-void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& R,
+void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& R, bool cubic,
                      const SortBuffers& B, hipStream_t st) {
   const int tiles = int((n + kTile - 1) / kTile);
   const unsigned blocks = unsigned(rows * tiles);
@@ -653,7 +655,7 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(unsigned(rows * slices * (kSelBins / 128))),
                      dim3(kThreads), 0, st, B.hpart, B.bins, parts, slices, kSelBins);
   hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                     B.bins, B.sel, k, slices, R);
+                     B.bins, B.sel, k, slices, R, cubic);
   // first-level candidates into the per-tile slots of the "b" arrays; second level; slots
   // narrowed in place; dense lists
   const int slices2 = tiles < kSelSlices ? tiles : kSelSlices;
@@ -663,7 +665,7 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
                      dim3(unsigned(rows * slices2 * (2 * kSel2Bins / 128))), dim3(kThreads), 0, st,
                      B.tile_hist2, B.bins2, tiles, slices2, 2 * kSel2Bins);
   hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                     B.bins2, B.sel, slices2, R);
+                     B.bins2, B.sel, slices2, R, cubic);
   hipLaunchKernelGGL(select_recompact_kernel, dim3(blocks), dim3(kThreads), 0, st, B.sel, B.keys_b,
                      B.idx_b, B.tcnt, B.tabove, n, tiles);
   hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
@@ -697,13 +699,13 @@ int launch_segmented_sort(bool mag, const float* x, int64_t rows, int64_t n, con
   return 0;
 }
 
-int launch_candidate_lists(bool mag, const float* x, int64_t rows, int64_t n, int64_t k,
+int launch_candidate_lists(bool mag, int pc, const float* x, int64_t rows, int64_t n, int64_t k,
                            const Reg& R, const SortBuffers& B, hipStream_t st) {
   const int64_t tiles = radix_tiles(n);
   if (k < 1 || k >= n) return -1;
   if (rows * tiles > 0x7fffffffLL || rows * kRadix > 0x7fffffffLL) return -1;
-  if (mag) candidate_lists<true>(x, rows, n, k, R, B, st);
-  else candidate_lists<false>(x, rows, n, k, R, B, st);
+  if (mag) candidate_lists<true>(x, rows, n, k, R, pc == kP43, B, st);
+  else candidate_lists<false>(x, rows, n, k, R, pc == kP43, B, st);
   return 0;
 }
 

@@ -215,9 +215,9 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
   double center = 0.0, gamma = 0.0;
   if (k >= 1 && k < n) {                 // uniform
     const double sk = double(ls[k - 1]), sk1 = double(ls[k]);
-    if (!MAG) center = sk;
+    if (P::kCentered) center = sk;
     const double dk = sk - center, dk1 = sk1 - center;
-    bool active = P::seed_violates(dk, dk1, R);
+    bool active = P::seed_violates(dk, dk1, R, center);
     if (__any(active)) {
       Sums S{dk + dk1, 0.0, 0.0};
       if (CUBIC) {
@@ -231,8 +231,8 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
         const double dj = double(ls[can_r ? b : 0]) - center;
         const double di = double(ls[can_l ? a - 2 : 0]) - center;
         const double cnt = double(b - a + 1), m = double(k - a + 1);
-        const bool add_r = can_r && P::right_violates(dj, cnt, m, S, R);
-        const bool add_l = can_l && P::left_violates(di, cnt, m, S, R);
+        const bool add_r = can_r && P::right_violates(dj, cnt, m, S, R, center);
+        const bool add_l = can_l && P::left_violates(di, cnt, m, S, R, center);
         if (add_r) {
           S.s1 += dj;
           if (CUBIC) { S.s2 += dj * dj; S.s3 += dj * dj * dj; }
@@ -247,21 +247,25 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
       }
       if (grew) {
         const double da = double(ls[a - 1]) - center, db = double(ls[b - 1]) - center;
-        gamma = P::pooled(double(b - a + 1), double(k - a + 1), S, R, da - R.lambda, db);
+        // bracket of the pooled value: above the singleton minimiser of position a (mask:
+        // s_a - lambda; magnitude: at least 0), below s_b (magnitude, p = 4/3: below s_a)
+        const double lo = MAG ? -center : da - R.lambda;
+        gamma = P::pooled(double(b - a + 1), double(k - a + 1), S, R, lo, MAG ? da : db, center);
       }
     }
   }
 
   // ---- y in sorted order, scattered to the original index (in LDS) ---------------------------
   // Positions before the block keep their singleton solution (mask: exactly 1; magnitude:
-  // s/(1+lambda)); positions after it are exactly 0.
+  // s/(1+lambda) for p = 2, the root of the one-element cubic for p = 4/3); positions after it
+  // are exactly 0.
   if (out != nullptr) {
 #pragma unroll
     for (int r = 0; r < E; ++r) {
       const int pos1 = e0 + r + 1;
       const double v = double(s32[r]) - center;
       const double yb = P::y_in_block(v, gamma, R);
-      const double ya = MAG ? v * R.inv_1pl : 1.0;
+      const double ya = P::above(v, R, center);
       double y = (pos1 < a) ? ya : yb;
       y = (pos1 > b) ? 0.0 : y;
       float yf = float(y);
@@ -305,7 +309,7 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
     for (int r = 0; r < E; ++r) {
       const int pos1 = e0 + r + 1;
       const double hb = P::hess(double(s32[r]) - center, gamma, R) * (tau[r] - dgamma);
-      const double ha = MAG ? tau[r] * R.inv_1pl : 0.0;
+      const double ha = P::above_slope(double(s32[r]) - center, R, center) * tau[r];
       double dy = (pos1 < a) ? ha : hb;
       dy = (pos1 > b) ? 0.0 : dy;
       float df = float(dy);
@@ -347,6 +351,8 @@ int launch_shape(bool mag, int pc, const float* x, const float* t, float* out, f
     hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP43, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
   else if (mag && pc == kP2)
     hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP2, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+  else if (mag && pc == kP43)
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP43, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
   else
     return -1;
   return 0;

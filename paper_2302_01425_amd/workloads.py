@@ -132,4 +132,8 @@ WORKLOADS = {
     # magnitude pruning of one flattened 4096 x 4096 layer, keep ceil(n / 10)
     "magnitude_pruning": Workload("magnitude_pruning", "mag", 1, _N5, -(-_N5 // 10), 2.0, 1e-3, 5,
                                   "laplace", 0.02),
+    # the same layer with the p = 4/3 regulariser (not one of the five headline configurations:
+    # the operator x p combination added after them)
+    "magnitude_pruning_smooth": Workload("magnitude_pruning_smooth", "mag", 1, _N5, -(-_N5 // 10),
+                                         4.0 / 3.0, 1e-3, 6, "laplace", 0.02),
 }

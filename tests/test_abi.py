@@ -50,7 +50,7 @@ def test_argument_validation_without_gpu(lib):
     assert f(None, 4, 8, 2, 2.0, 1.0, one, None) == -2          # null input
     assert f(one, 4, 8, 2, 2.0, 1.0, None, None) == -2          # null output
     assert f(one, 0, 8, 2, 2.0, 1.0, one, None) == 0            # rows == 0: no-op
-    assert lib.topkmag_fwd(one, 4, 8, 2, 4.0 / 3.0, 1.0, one, None) == -3
+    assert lib.topkmag_fwd(one, 4, 8, 2, 1.0, 1.0, one, None) == -3         # p = 1: no pooling step
     assert lib.topk_mask_jvp(one, None, 4, 8, 2, 2.0, 1.0, None, one, None) == -2
     assert lib.topk_mask_jvp(one, one, 4, 8, 2, 2.0, 1.0, None, None, None) == -2
     assert lib.topk_argsort_desc(one, 4, 8, None, None) == -2

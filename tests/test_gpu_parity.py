@@ -69,7 +69,7 @@ def run_case(gpu, oracle, op, x, t, k, p, lam, check_perm=True):
 
 # ---- the five workloads at full size ---------------------------------------------------------
 @pytest.mark.parametrize("name", ["tiny", "moe_router", "moe_router_smooth", "expert_choice",
-                                  "magnitude_pruning"])
+                                  "magnitude_pruning", "magnitude_pruning_smooth"])
 def test_workload_parity(gpu, oracle, name):
     from paper_2302_01425_amd.workloads import WORKLOADS
     w = WORKLOADS[name]
@@ -102,6 +102,8 @@ def test_short_rows(gpu, oracle, n):
         for k in sorted({0, 1, n // 3, n} & set(range(n + 1))):
             run_case(gpu, oracle, "mag", x, t, k, P2, float(r.choice([1e-3, 0.1, 1.0])),
                      check_perm=(k == 1))
+            run_case(gpu, oracle, "mag", x, t, k, P43, float(r.choice([0.05, 0.3, 1.0])),
+                     check_perm=False)
 
 
 # ---- long rows: several tiles, ragged tails, several rows -----------------------------------------
@@ -120,6 +122,8 @@ def test_long_rows(gpu, oracle, rows, n):
     for k in (0, n // 10, n):
         run_case(gpu, oracle, "mag", x * np.float32(0.02), t, k, P2, float(r.choice([1e-3, 0.05])),
                  check_perm=(k == 0))
+    for k, lam in ((0, 0.1), (n // 10, 0.02), (n // 3, 0.3), (n, 0.1)):
+        run_case(gpu, oracle, "mag", x[:2] * np.float32(0.5), t[:2], k, P43, lam, check_perm=False)
     # large lambda: the block spans most of the row (many sweep chunks)
     run_case(gpu, oracle, "mask", x, t, n // 3, P2, 50.0, check_perm=False)
     run_case(gpu, oracle, "mask", x, t, n // 3, P43, 50.0, check_perm=False)
@@ -206,6 +210,7 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", x, t, n // 20, P2, 0.05, check_perm=False)
     run_case(gpu, oracle, "mask", x, t, n // 3, P43, 2.0, check_perm=False)
     run_case(gpu, oracle, "mag", x, t, n // 10, P2, 0.01, check_perm=False)
+    run_case(gpu, oracle, "mag", x[:1], t[:1], n // 10, P43, 0.05, check_perm=False)
     # mostly exact zeros of both signs: s_k is a zero, the window starts at the zeros
     z = (r.normal(size=(2, n)) * (r.random((2, n)) < 0.02)).astype(np.float32)
     z[:, ::5] = -0.0
@@ -241,6 +246,15 @@ def test_strict_merge_kinks(gpu, oracle):
         run_case(gpu, oracle, "mag", th, t, k, P2, lam)
 
 
+def test_fig2_points_through_the_library(gpu, oracle):
+    """Fig. 2 of the paper (phi = x^2/2, k = 2, x = (x1, x2, 1/2, 1), lambda = 0.3), both p."""
+    pts = np.linspace(-0.6, 0.6, 7)
+    x = np.array([[a, b, 0.5, 1.0] for a in pts for b in pts], dtype=np.float32)
+    t = np.tile(np.array([[1.0, -2.0, 0.5, 3.0]], dtype=np.float32), (x.shape[0], 1))
+    for p in (P2, P43):
+        run_case(gpu, oracle, "mag", x, t, 2, p, 0.3, check_perm=False)
+
+
 def test_values_closer_than_the_truncated_sort_key(gpu, oracle):
     """Rows whose values differ only in the last few mantissa bits (and mixtures of such clusters
     with exact ties): the permutation must still be the exact stable argsort."""
@@ -263,6 +277,7 @@ def test_values_closer_than_the_truncated_sort_key(gpu, oracle):
             for p in (P2, P43):
                 run_case(gpu, oracle, "mask", x, t, k, p, 0.3)
             run_case(gpu, oracle, "mag", x, t, k, P2, 0.05)
+            run_case(gpu, oracle, "mag", x, t, k, P43, 0.2)
 
 
 def test_vjp_against_the_transposed_jacobian_of_the_oracle(gpu, oracle):
@@ -311,4 +326,4 @@ def test_rows_zero_and_errors(gpu):
     with pytest.raises(gpu.TopkError):
         gpu.topk_mask_fwd(y, 2, 1.7, 1.0)
     with pytest.raises(gpu.TopkError):
-        gpu.topkmag_fwd(y, 2, P43, 1.0)
+        gpu.topkmag_fwd(y, 2, 3.0, 1.0)
