@@ -1,8 +1,8 @@
 // Medium rows (1024 < n <= 131072): the whole operator for one row in ONE workgroup of 1024
 // threads, one launch.
 //
-//   1. histogram of the leading key bits of the row (LDS, four lane-rotated copies per bin so
-//      that skewed exponents do not serialise the atomics)
+//   1. histogram of the leading key bits of the row (LDS atomics; bin = LDS word, so that
+//      neighbouring bins, the ones a wavefront hits together, lie in different banks)
 //   2. the bins of sorted positions k and k+1 give the key window that holds every element able
 //      to pool (radix.hpp: key_window)
 //   3. ordered compaction of those candidates (key, index payload) into the row's scratch
@@ -47,13 +47,13 @@ constexpr int kMItems = 8;                 // elements per thread and tile of a 
 constexpr int kCItems = 16;                // elements per thread and tile of the compaction
 constexpr int kCTile = kMT * kCItems;
 constexpr int kLdsCap = 2048;              // candidate lists up to this length are sorted in LDS
-constexpr int kCopies = 4;
-constexpr int kLdsKeys = kSelBins * kCopies;   // sorted keys of a list this long fit the LDS for the solve
+constexpr int kCopies = 1;
+constexpr int kLdsKeys = 16384;   // sorted keys of a list this long fit the LDS for the solve
 constexpr int kSelShift = 32 - kSelBits;
 
 struct MedShared {
   union {
-    uint32_t hist[kSelBins * kCopies];     // steps 1-2
+    uint32_t hist[kLdsKeys];               // steps 1-2: kSelBins * kCopies counters; later sorted keys
     struct {
       uint32_t cnt[kMW][kRadix];           // per-wave digit counts, then per-wave offsets
       uint32_t base[kRadix];               // running start of every digit in the output
@@ -268,7 +268,9 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       const uint32_t* h = &sm.u.hist[(threadIdx.x * kPerThread + i) * kCopies];
-      c[i] = h[0] + h[1] + h[2] + h[3];
+      c[i] = 0;
+#pragma unroll
+      for (int q = 0; q < kCopies; ++q) c[i] += h[q];
       mine += c[i];
     }
     uint32_t run = med_exclusive_scan(mine, sm.wave_a, nullptr);

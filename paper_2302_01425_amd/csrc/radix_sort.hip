@@ -10,7 +10,7 @@
 //
 // The operators do not need the whole permutation: only elements in a value window around
 // s_k and s_{k+1} can pool (pooling.hpp).  The second half of this file selects those candidates
-// in two histogram levels (12 + 12 leading key bits) and gathers them, in index order, into a
+// in two histogram levels (12 + 8 leading key bits) and gathers them, in index order, into a
 // dense list per row.  Short lists are then sorted and solved by one workgroup
 // (medium_rows.hip); only rows whose list is longer go through the passes of this file.
 // topk_argsort_desc sorts whole rows with them.
@@ -239,7 +239,6 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
 }
 
 // ---- candidate selection ---------------------------------------------------------------------
-// Histogram of the leading kSelBits key bits of every row (global counters, zeroed before).
 constexpr int kSelShift = 32 - kSelBits;
 
 // Device-scope atomics are slow on this multi-die part (10-25 G/s), so no histogram here uses
