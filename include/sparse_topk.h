@@ -118,6 +118,20 @@ int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n,
                 double p, double lambda, float* out, float* vjp_out, void* stream);
 
 /*
+ * Smooth top-k loss (Sec. 6, "Smooth top-k loss"): the Fenchel-Young loss of the relaxed top-k
+ * mask, per row
+ *     loss = f_{phi,R}(theta, 1_k) - <theta, target>,   phi(x) = x,
+ * and its gradient in theta, grad = y - target with y the mask of topk_mask_fwd (Prop. 2:
+ * y = grad_1 f_{phi,R}).  f is evaluated through the maximisation form of Prop. 2 at its maximiser
+ * y: f = <y, theta> - (lambda / p) sum_i y_i^p.
+ *   theta, target [rows][n] in (target: usually a 0/1 encoding of the wanted classes),
+ *   loss_out [rows] out, grad_out [rows][n] out (required: it also carries the mask between the
+ *   two kernels).  Same shape rules, p values, workspace needs and errors as topk_mask_fwd.
+ */
+int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_t n, int64_t k,
+                   double p, double lambda, float* loss_out, float* grad_out, void* stream);
+
+/*
  * The sorting permutation itself (Sec. 3, argsort): perm_out[r][i] = original index of the i-th
  * largest value of row r (0-based).  This is the permutation the operators above use.
  */

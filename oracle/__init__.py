@@ -54,6 +54,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_pav.argtypes = [f64p, f64p, i64, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                  f64p, i64p]
         L.oracle_pav.restype = ctypes.c_int
+        L.oracle_topk_value.argtypes = [ctypes.c_int, f64p, i64, i64, i64, ctypes.c_int,
+                                        ctypes.c_double, f64p]
+        L.oracle_topk_value.restype = ctypes.c_int
         L.oracle_max_threads.restype = ctypes.c_int
         L.oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = L
@@ -132,6 +135,27 @@ def topkmag(x, k, p, lam, tangent=None, want_perm=False, want_block=False, f64=F
     """Relaxed top-k in magnitude (phi = x^2/2) of each row; float64 results in a dict."""
     fn = lib().oracle_topkmag_f64 if f64 else lib().oracle_topkmag
     return _run(fn, x, k, p, lam, tangent, want_perm, want_block, f64)
+
+
+def value(x, k, p, lam, phi: str = "id") -> np.ndarray:
+    """f_{phi,R}(x, 1_k) of each row (paper Prop. 2, the minimisation form), float64."""
+    x = np.atleast_2d(np.ascontiguousarray(x, dtype=np.float64))
+    out = np.empty(x.shape[0], dtype=np.float64)
+    rc = lib().oracle_topk_value({"id": 0, "half_sq": 1}[phi], _ptr(x, ctypes.c_double), x.shape[0],
+                                 x.shape[1], int(k), p_code(p), float(lam), _ptr(out, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"oracle_topk_value failed: {rc}")
+    return out
+
+
+def fenchel_young_loss(theta, target, k, p, lam):
+    """Smooth top-k loss of the paper's Sec. 6: l(x, t) = f_{phi,R}(x, 1_k) - <x, t> with phi = id,
+    and its gradient in x, y - t.  Returns (loss per row, gradient), float64."""
+    theta = np.atleast_2d(np.asarray(theta))
+    target = np.atleast_2d(np.asarray(target, dtype=np.float64))
+    f = value(theta, k, p, lam, "id")
+    y = topk_mask(theta, k, p, lam, f64=(theta.dtype == np.float64))["out"].reshape(theta.shape)
+    return f - (theta.astype(np.float64) * target).sum(axis=1), y - target
 
 
 def pav(s, w, phi: str, p, lam):

@@ -212,9 +212,11 @@ inline double hess_rstar(const Problem& P, double t) {
 //   perm     : the sorting permutation (0-based), or nullptr
 //   ab       : ab[0], ab[1] = 0-based half-open range of the one block with more than one
 //              element (lo == hi when every block is a singleton), or nullptr
+//   value    : f_{phi,R}(x, 1_k) itself (Prop. 2, second line: min_u R*(x - u) + f_phi(u, 1_k),
+//              evaluated at u*, i.e. the optimal value of Eq. (isotonic_separable)), or nullptr
 template <class T>
 void one_row(const Problem& P, const T* x, const T* tangent, int64_t n, int64_t k,
-             double* out, double* jvp, int32_t* perm, int64_t* ab) {
+             double* out, double* jvp, int32_t* perm, int64_t* ab, double* value = nullptr) {
   std::vector<int32_t> sigma(n);
   std::vector<T> z(n);
   std::vector<double> s(n), w(n), v(n), sgn(n);
@@ -240,6 +242,17 @@ void one_row(const Problem& P, const T* x, const T* tangent, int64_t n, int64_t 
   }
   // y* = grad R*(x - u*),  u* = sign(x) o v*_{sigma^-1}
   for (int64_t i = 0; i < n; ++i) out[sigma[i]] = sgn[i] * grad_rstar(P, s[i] - v[i]);
+  if (value) {
+    // sum_i r*(s_i - v_i) + w_i phi(v_i),  r*(t) = |t|^q / (q lambda^(q-1)),  q = 2 or 4
+    const double q = (P.p == P_2) ? 2.0 : 4.0;
+    const double lam_qm1 = (P.p == P_2) ? P.lambda : P.lambda * P.lambda * P.lambda;
+    double f = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+      const double t = std::fabs(s[i] - v[i]);
+      f += std::pow(t, q) / (q * lam_qm1) + w[i] * (mag ? 0.5 * v[i] * v[i] : v[i]);
+    }
+    *value = f;
+  }
   if (perm) std::memcpy(perm, sigma.data(), sizeof(int32_t) * size_t(n));
   if (ab) {
     ab[0] = ab[1] = 0;
@@ -343,6 +356,22 @@ int oracle_topkmag_f64(const double* x, const double* tangent, int64_t rows, int
                        int p_code, double lambda, double* out, double* jvp, int32_t* perm,
                        int64_t* ab) {
   return run_rows(PHI_HALF_SQ, x, tangent, rows, n, k, p_code, lambda, out, jvp, perm, ab);
+}
+
+// f_{phi,R}(x, 1_k) of every row (Prop. 2), the function whose gradient in x the operators are;
+// the Fenchel-Young top-k loss of Sec. 6 ("Smooth top-k loss") is value - <x, t>.
+int oracle_topk_value(int phi_code, const double* x, int64_t rows, int64_t n, int64_t k, int p_code,
+                      double lambda, double* value) {
+  if (!x || !value || rows < 0 || n < 1 || k < 0 || k > n) return -1;
+  if (!(lambda > 0.0) || !std::isfinite(lambda)) return -2;
+  if (phi_code < 0 || phi_code > 1 || p_code < 0 || p_code > 1) return -3;
+  Problem P{Phi(phi_code), Pcode(p_code), lambda};
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t r = 0; r < rows; ++r) {
+    std::vector<double> out(n);
+    one_row<double>(P, x + r * n, nullptr, n, k, out.data(), nullptr, nullptr, nullptr, value + r);
+  }
+  return 0;
 }
 
 // The isotonic solver alone, for any weights w (sorted s, float64):

@@ -18,7 +18,8 @@ TOPK_OP_MASK_FWD, TOPK_OP_MASK_JVP, TOPK_OP_MAG_FWD, TOPK_OP_MAG_JVP, TOPK_OP_AR
 
 EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
-    "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace", "topk_strerror",
+    "topk_mask_loss", "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace",
+    "topk_strerror",
 )
 
 _lib = None
@@ -46,6 +47,8 @@ def load() -> ctypes.CDLL:
     L.topk_mask_vjp.argtypes = L.topk_mask_jvp.argtypes
     L.topkmag_vjp.argtypes = L.topkmag_jvp.argtypes
     L.topk_argsort_desc.argtypes = [vp, i64, i64, vp, vp]
+    L.topk_mask_loss.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
+    L.topk_mask_loss.restype = ci
     for name in ("topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp",
                  "topkmag_vjp", "topk_argsort_desc"):
         getattr(L, name).restype = ci
@@ -186,6 +189,21 @@ def topkmag_vjp(x, cotangent, k, p, lam, out=None, vjp_out=None, want_out=True, 
                               float(lam), None if out is None else out.data_ptr(),
                               vjp_out.data_ptr(), _stream(stream)), "topkmag_vjp")
     return out, vjp_out
+
+
+def topk_mask_loss(theta, target, k, p, lam, loss_out=None, grad_out=None, stream=None):
+    """Returns (loss [rows], grad [rows][n])."""
+    theta = _dev_f32(theta, "theta")
+    target = _dev_f32(target, "target")
+    rows, n = theta.shape
+    loss_out = (torch.empty(rows, dtype=torch.float32, device=theta.device) if loss_out is None
+                else loss_out)
+    grad_out = torch.empty_like(theta) if grad_out is None else _dev_f32(grad_out, "grad_out")
+    ensure_workspace(TOPK_OP_MASK_FWD, rows, n, k, p, theta.device)
+    _check(load().topk_mask_loss(theta.data_ptr(), target.data_ptr(), rows, n, int(k), float(p),
+                                 float(lam), loss_out.data_ptr(), grad_out.data_ptr(),
+                                 _stream(stream)), "topk_mask_loss")
+    return loss_out, grad_out
 
 
 def topk_argsort_desc(theta, perm_out=None, stream=None):

@@ -188,6 +188,23 @@ int topkmag_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, i
   return run_operator(true, x, tangent, rows, n, k, p, lambda, out, jvp_out, false, true, stream);
 }
 
+int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_t n, int64_t k,
+                   double p, double lambda, float* loss_out, float* grad_out, void* stream) {
+  if (rows > 0 && (target == nullptr || loss_out == nullptr)) {
+    const int rc = check_shape(rows, n, k, lambda);
+    return rc != TOPK_OK ? rc : (p_code(p) < 0 ? TOPK_ERR_UNSUPPORTED_P : TOPK_ERR_NULL);
+  }
+  // the mask goes to grad_out, the reduction turns it into y - target
+  const int rc = run_operator(false, theta, nullptr, rows, n, k, p, lambda, grad_out, nullptr, true,
+                              false, stream);
+  if (rc != TOPK_OK || rows == 0) return rc;
+  const double p_exact = p_code(p) == topk::kP2 ? 2.0 : 4.0 / 3.0;
+  if (topk::launch_mask_loss(p_code(p), theta, target, grad_out, loss_out, rows, n, lambda,
+                             p_exact, static_cast<hipStream_t>(stream)) != 0)
+    return TOPK_ERR_INVALID;
+  return finish();
+}
+
 // The Jacobians are symmetric (see the header): the VJP is the JVP of the cotangent.
 int topk_mask_vjp(const float* theta, const float* cotangent, int64_t rows, int64_t n, int64_t k,
                   double p, double lambda, float* out, float* vjp_out, void* stream) {

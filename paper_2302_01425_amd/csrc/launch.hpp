@@ -114,4 +114,8 @@ int launch_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, 
 // Longer lists: four radix passes, sorted lists end in the "a" arrays.
 int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& B, hipStream_t st);
 
+// Fenchel-Young top-k loss from the mask: grad holds y on entry, y - target on exit; loss[rows].
+int launch_mask_loss(int pc, const float* x, const float* target, float* grad, float* loss,
+                     int64_t rows, int64_t n, double lambda, double p, hipStream_t st);
+
 }  // namespace topk

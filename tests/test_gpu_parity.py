@@ -301,6 +301,25 @@ def test_vjp_against_the_transposed_jacobian_of_the_oracle(gpu, oracle):
         close(host(out), ofn(x, k, p, lam, tangent=c)["out"], "out")
 
 
+def test_fenchel_young_loss(gpu, oracle):
+    """Smooth top-k loss (Sec. 6) and its gradient against the oracle's value of f (computed from
+    the minimisation form of Prop. 2, the library uses the maximisation form)."""
+    r = np.random.default_rng(23)
+    for rows, n, k, lam in [(64, 10, 3, 0.5), (300, 100, 3, 1.0), (33, 1000, 5, 0.2), (4, 5000, 50, 0.3),
+                            (2, 150000, 100, 0.5)]:
+        x = (r.normal(size=(rows, n)) * 2).astype(np.float32)
+        t = np.zeros((rows, n), dtype=np.float32)
+        t[np.arange(rows), r.integers(0, n, size=rows)] = 1.0          # one-hot classes
+        for p in (P2, P43):
+            print(f"loss rows={rows} n={n} k={k} p={p:.3f} lam={lam}", flush=True)
+            ref_loss, ref_grad = oracle.fenchel_young_loss(x, t, k, p, lam)
+            loss, grad = gpu.topk_mask_loss(dev(x), dev(t), k, p, lam)
+            close(host(grad), ref_grad, "grad")
+            scale = np.abs(x).sum(axis=1) if n <= 1000 else np.abs(x).max(axis=1) * 4 * k
+            err = np.abs(host(loss).astype(np.float64) - ref_loss)
+            assert (err <= 1e-5 + 3e-7 * scale).all(), (rows, n, p, float(err.max()))
+
+
 def test_determinism_and_streams(gpu):
     import torch
     from paper_2302_01425_amd.workloads import WORKLOADS

@@ -447,3 +447,68 @@ def test_edge_cases(oracle):
     assert z["out"][0] == 0.0 and z["out"][1] == 0.0
     one = oracle.topk_mask(np.array([5.0], np.float32), 1, P2, 1.0, tangent=np.ones(1, np.float32))
     assert abs(one["out"][0] - 1.0) < 1e-15 and one["jvp"][0] == 0.0
+
+
+# ----------------------------------------------------------------------------------------------
+# The function f_{phi,R}(x, 1_k) itself (Prop. 2) and the Fenchel-Young top-k loss of Sec. 6.
+# The oracle evaluates the minimisation form at u*; these checks come from the other side.
+@pytest.mark.parametrize("p", [P2, P43])
+def test_value_is_the_regularised_lp_over_the_permutahedron(oracle, p):
+    """phi = id: f = max_{y in P(1_k)} <y, x> - R(y) with P(1_k) = {0 <= y <= 1, sum y = k}
+    (Sec. 4), solved here as a smooth constrained program; and f = <y*, x> - R(y*) at the
+    operator's own output (strong duality)."""
+    r = rng(40)
+    for _ in range(30):
+        n = int(r.integers(2, 8))
+        k = int(r.integers(1, n + 1))
+        lam = float(r.choice([0.2, 1.0, 3.0]))
+        x = r.normal(size=n)
+        f = float(oracle.value(x, k, p, lam)[0])
+        obj = lambda y: -(y @ x - lam / p * np.sum(np.abs(y) ** p))
+        res = optimize.minimize(obj, np.full(n, k / n), method="SLSQP", bounds=[(0, 1)] * n,
+                                constraints=[{"type": "eq", "fun": lambda y: y.sum() - k}],
+                                options={"ftol": 1e-14, "maxiter": 500})
+        assert abs(f + res.fun) < 1e-6 * max(1.0, abs(f)), (x, k, lam, f, -res.fun)
+        y = oracle.topk_mask(x, k, p, lam, f64=True)["out"]
+        assert abs(f - (y @ x - lam / p * np.sum(y ** p))) < 1e-11 * max(1.0, abs(f))
+
+
+@pytest.mark.parametrize("phi", ["id", "half_sq"])
+@pytest.mark.parametrize("p", [P2, P43])
+def test_operator_is_the_gradient_of_the_value(oracle, phi, p):
+    """y = grad_1 f_{phi,R}(x, 1_k) (Prop. 2): central differences of the value."""
+    r = rng(41)
+    op = oracle.topk_mask if phi == "id" else oracle.topkmag
+    for _ in range(40):
+        n = int(r.integers(2, 12))
+        k = int(r.integers(1, n))
+        lam = float(r.choice([0.3, 1.0]))
+        x = r.normal(size=n)
+        y = op(x, k, p, lam, f64=True)["out"]
+        h = 1e-6
+        g = np.array([(oracle.value(x + h * e, k, p, lam, phi)[0] -
+                       oracle.value(x - h * e, k, p, lam, phi)[0]) / (2 * h) for e in np.eye(n)])
+        assert np.abs(g - y).max() < 5e-6 / min(1.0, lam), (phi, p, x, k, lam)
+
+
+def test_value_small_lambda_and_loss_lower_bound(oracle):
+    r = rng(42)
+    for p in (P2, P43):
+        x = r.normal(size=(5, 9))
+        top = -np.sort(-x, axis=1)[:, :3]
+        assert np.abs(oracle.value(x, 3, p, 1e-7) - top.sum(axis=1)).max() < 1e-6
+        ax = -np.sort(-np.abs(x), axis=1)[:, :3]
+        assert np.abs(oracle.value(x, 3, p, 1e-7, "half_sq") - 0.5 * (ax ** 2).sum(axis=1)).max() < 1e-6
+        # Fenchel-Young inequality: f(x) + f*(t) - <x, t> >= 0 with f*(t) = R(t) = k' lambda / p for
+        # a 0/1 target with k' <= k ones (t in P(1_k) needs sum t = k: use k ones)
+        for lam in (0.3, 2.0):
+            t = np.zeros_like(x)
+            for i in range(x.shape[0]):
+                t[i, r.permutation(9)[:3]] = 1.0
+            loss, grad = oracle.fenchel_young_loss(x, t, 3, p, lam)
+            assert (loss + 3 * lam / p > -1e-12).all()
+            # equality when the target is the hard top-k of a well separated x and lambda is small
+        xs = np.array([[10.0, 8.0, 6.0, -5.0, -7.0]])
+        ts = np.array([[1.0, 1.0, 1.0, 0.0, 0.0]])
+        loss, grad = oracle.fenchel_young_loss(xs, ts, 3, p, 0.5)
+        assert abs(loss[0] + 3 * 0.5 / p) < 1e-12 and np.abs(grad).max() < 1e-12
