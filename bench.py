@@ -43,6 +43,10 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the operator, time a plain device copy of the same footprint "
                          "(theta|tangent -> out|jvp); used to scale the rocprofv3 byte counters")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the one JSON line: time the mask forward + JVP over row lengths "
+                         "64 .. 2^24 at a constant 2^24 elements, k = ceil(n/10) (the paper's timing "
+                         "sweep uses k = ceil(n/10)), lambda = 0.1, one JSON line per row length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=4.0)
     return ap.parse_args()
@@ -155,6 +159,31 @@ def cpu_baseline(w, seconds):
     }
 
 
+def sweep(a):
+    """Row-length sweep at a constant element count (all three kernel families and the
+    transitions between them).  Not the benchmark contract: one JSON line per row length."""
+    import torch
+    from paper_2302_01425_amd.workloads import Workload
+    total = 1 << 24
+    for p in (2.0, 4.0 / 3.0):
+        for lg in (6, 8, 10, 11, 13, 15, 17, 18, 20, 22, 24):
+            n = 1 << lg
+            rows = total // n
+            w = Workload(f"sweep_n{n}", "mask", rows, n, -(-n // 10), p, 0.1, 7, "normal", 1.0)
+            set_bytes = 4 * 4 * rows * n
+            sets = max(2, -(-a.cold_mib * (1 << 20) // set_bytes))
+            r = Runner(w, sets, "cuda:0")
+            steps = max(10, min(200, int(2e5 / max(50.0, 1e-6 * total))))
+            ms = r.timed(steps, 5, a.mode, rotate=True) / steps
+            print(json.dumps({"sweep": "mask fwd+JVP, 2^24 elements, k = ceil(n/10), lambda = 0.1",
+                              "p": round(p, 4), "n": n, "rows": rows, "us_per_step": ms * 1e3,
+                              "gbps": BYTES_PER_ELEMENT * total / (ms * 1e-3) / 1e9,
+                              "frac_of_hbm_peak": BYTES_PER_ELEMENT * total / (ms * 1e-3) / 1e9
+                              / HBM_PEAK_GBPS}), flush=True)
+            del r
+            torch.cuda.empty_cache()
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -167,6 +196,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if a.sweep:
+        sweep(a)
+        return
     w = WORKLOADS[a.workload]
     algo_bytes = BYTES_PER_ELEMENT * w.rows * w.n
     set_bytes = 4 * 4 * w.rows * w.n

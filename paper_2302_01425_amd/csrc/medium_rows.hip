@@ -41,35 +41,45 @@ extern "C" int topk_debug_read_med_trace(unsigned long long* host_out) {
 namespace topk {
 namespace {
 
-constexpr int kMT = 1024;                  // threads
-constexpr int kMW = kMT / kWave;           // wavefronts
+// Workgroups of NT = 1024 threads for long rows; of 256 threads for rows up to kSmallRowMax
+// elements, where the per-row latency is what counts and four times as many rows are in flight.
+constexpr int kSmallRowMax = 8192;
 constexpr int kMItems = 8;                 // elements per thread and tile of a sorting pass
 constexpr int kCItems = 16;                // elements per thread and tile of the compaction
-constexpr int kCTile = kMT * kCItems;
-constexpr int kLdsCap = 2048;              // candidate lists up to this length are sorted in LDS
-constexpr int kCopies = 1;
-constexpr int kLdsKeys = 16384;   // sorted keys of a list this long fit the LDS for the solve
 constexpr int kSelShift = 32 - kSelBits;
 
+template <int NT>
+struct MedCfg {
+  static constexpr int kMW = NT / kWave;                     // wavefronts
+  static constexpr int kCTile = NT * kCItems;
+  static constexpr int kLdsCap = NT >= 1024 ? 2048 : 1024;   // lists up to this length are sorted in LDS
+  // words of the union below: the selection histogram, later the sorted keys of a list for the solve
+  static constexpr int kLdsKeys = NT >= 1024 ? 16384 : kSelBins;
+};
+
+template <int NT>
 struct MedShared {
+  using C = MedCfg<NT>;
   union {
-    uint32_t hist[kLdsKeys];               // steps 1-2: kSelBins * kCopies counters; later sorted keys
+    uint32_t hist[C::kLdsKeys];            // steps 1-2: kSelBins counters; later sorted keys
     struct {
-      uint32_t cnt[kMW][kRadix];           // per-wave digit counts, then per-wave offsets
+      uint32_t cnt[C::kMW][kRadix];        // per-wave digit counts, then per-wave offsets
       uint32_t base[kRadix];               // running start of every digit in the output
       uint32_t gofs[kRadix];               // start of the current tile's items of every digit
-      uint32_t lk[2][kLdsCap];             // short candidate lists: keys, ping-pong
-      uint32_t li[2][kLdsCap];             //                        index payloads
+      uint32_t lk[2][C::kLdsCap];          // short candidate lists: keys, ping-pong
+      uint32_t li[2][C::kLdsCap];          //                        index payloads
     } sort;                                // steps 3-6
   } u;
-  SolveShared<kMT> solve;
-  uint32_t wave_a[kMW], wave_b[kMW];
+  SolveShared<NT> solve;
+  uint32_t wave_a[C::kMW], wave_b[C::kMW];
   uint32_t found[2];
 };
 
 // exclusive scan of one value per thread over the workgroup; *total gets the sum
+template <int NT>
 __device__ __forceinline__ uint32_t med_exclusive_scan(uint32_t v, uint32_t* wave_tot,
                                                        uint32_t* total) {
+  constexpr int kMW = NT / kWave;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   uint32_t inc = v;
 #pragma unroll
@@ -93,10 +103,11 @@ __device__ __forceinline__ uint32_t med_exclusive_scan(uint32_t v, uint32_t* wav
 
 // One LSD pass over the cn candidates: (kin, iin) -> (kout, iout), stable, by the 8-bit digit of
 // (key - klo) at `shift`.  Tiles of ni*1024 elements; wave w owns elements w*ni*64 .. of a tile.
-template <int ITEMS>
+template <int NT, int ITEMS>
 __device__ __forceinline__ void med_sort_pass(const uint32_t* kin, const uint32_t* iin, uint32_t* kout,
                               uint32_t* iout, uint32_t cn, uint32_t klo, int shift, int ni,
-                              MedShared& sm) {
+                              MedShared<NT>& sm) {
+  constexpr int kMT = NT, kMW = NT / kWave;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   const uint32_t tile_elems = uint32_t(ni) * kMT;
   const uint32_t wave_elems = uint32_t(ni) * kWave;
@@ -123,7 +134,7 @@ __device__ __forceinline__ void med_sort_pass(const uint32_t* kin, const uint32_
 #pragma unroll
       for (int q = 0; q < kMW; ++q) tot += sm.u.sort.cnt[q][threadIdx.x];
     }
-    const uint32_t ex = med_exclusive_scan(tot, sm.wave_a, nullptr);
+    const uint32_t ex = med_exclusive_scan<NT>(tot, sm.wave_a, nullptr);
     if (threadIdx.x < kRadix) sm.u.sort.base[threadIdx.x] = ex;
   }
   // tile by tile: rank inside the wavefront, offsets of the wavefronts, scatter
@@ -161,7 +172,7 @@ __device__ __forceinline__ void med_sort_pass(const uint32_t* kin, const uint32_
       }
     }
     if (single) {
-      const uint32_t ex = med_exclusive_scan(run, sm.wave_a, nullptr);
+      const uint32_t ex = med_exclusive_scan<NT>(run, sm.wave_a, nullptr);
       if (threadIdx.x < kRadix) sm.u.sort.gofs[threadIdx.x] = ex;
     } else if (threadIdx.x < kRadix) {
       const uint32_t b = sm.u.sort.base[threadIdx.x];
@@ -196,9 +207,10 @@ struct SortedList {
 // Stable LSD sort of the cn candidates in (ka, ia) on key - klo, one pass per 8 significant bits
 // of khi - klo.  The passes alternate between two buffers: in LDS for short lists, else (kb, ib)
 // and (ka, ia).
-template <int ITEMS>
+template <int NT, int ITEMS>
 __device__ __forceinline__ SortedList sort_candidates(uint32_t* ka, uint32_t* ia, uint32_t* kb, uint32_t* ib,
-                                      uint32_t cn, uint32_t klo, uint32_t khi, MedShared& sm) {
+                                      uint32_t cn, uint32_t klo, uint32_t khi, MedShared<NT>& sm) {
+  constexpr int kMT = NT, kLdsCap = MedCfg<NT>::kLdsCap;
   const uint32_t span = khi - klo;
   const int nbits = span == 0 ? 0 : 32 - __clz(int(span));
   int ni = int((cn + kMT - 1) / kMT);
@@ -215,7 +227,7 @@ __device__ __forceinline__ SortedList sort_candidates(uint32_t* ka, uint32_t* ia
   for (int shift = 0; shift < nbits; shift += 8) {
     uint32_t* kout = even ? k0 : k1;
     uint32_t* iout = even ? i0 : i1;
-    med_sort_pass<ITEMS>(kin, iin, kout, iout, cn, klo, shift, ni, sm);
+    med_sort_pass<NT, ITEMS>(kin, iin, kout, iout, cn, klo, shift, ni, sm);
     kin = kout;
     iin = iout;
     even = !even;
@@ -224,12 +236,13 @@ __device__ __forceinline__ SortedList sort_candidates(uint32_t* ka, uint32_t* ia
   return SortedList{kin, iin, even ? 0 : 1, false};    // even: an even number of passes was made
 }
 
-template <bool MAG, int PC>
-__global__ __launch_bounds__(kMT) void medium_rows_kernel(
+template <bool MAG, int PC, int NT>
+__global__ __launch_bounds__(NT) void medium_rows_kernel(
     const float* __restrict__ x_all, const float* __restrict__ tangent_all,
     float* __restrict__ out_all, float* __restrict__ jvp_all, uint32_t* keys_a, uint32_t* idx_a,
     uint32_t* keys_b, uint32_t* idx_b, int n, int k_row, Reg R) {
-  __shared__ MedShared sm;
+  constexpr int kMT = NT, kMW = NT / kWave, kCTile = MedCfg<NT>::kCTile;
+  __shared__ MedShared<NT> sm;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   const int64_t base = int64_t(blockIdx.x) * n;
   const float* x = x_all + base;
@@ -248,7 +261,7 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
   const uint32_t* sidx = ia;
   if (k_row >= 1 && k_row < n) {
     // ---- 1. histogram of the leading key bits ---------------------------------------------------
-    for (int i = threadIdx.x; i < kSelBins * kCopies; i += kMT) sm.u.hist[i] = 0;
+    for (int i = threadIdx.x; i < kSelBins; i += kMT) sm.u.hist[i] = 0;
     __syncthreads();
     for (int e0 = threadIdx.x; e0 < n; e0 += 16 * kMT) {
       float v[16];
@@ -257,7 +270,7 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const uint32_t bin = first_key<MAG>(v[i]) >> kSelShift;
-        if (e0 + i * kMT < n) atomicAdd(&sm.u.hist[bin * kCopies + (lane & (kCopies - 1))], 1u);
+        if (e0 + i * kMT < n) atomicAdd(&sm.u.hist[bin], 1u);
       }
     }
     __syncthreads();
@@ -267,13 +280,10 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
     uint32_t c[kPerThread], mine = 0;
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
-      const uint32_t* h = &sm.u.hist[(threadIdx.x * kPerThread + i) * kCopies];
-      c[i] = 0;
-#pragma unroll
-      for (int q = 0; q < kCopies; ++q) c[i] += h[q];
+      c[i] = sm.u.hist[threadIdx.x * kPerThread + i];
       mine += c[i];
     }
-    uint32_t run = med_exclusive_scan(mine, sm.wave_a, nullptr);
+    uint32_t run = med_exclusive_scan<NT>(mine, sm.wave_a, nullptr);
     const uint32_t q0 = uint32_t(k_row), q1 = uint32_t(k_row) + 1u;
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
@@ -343,7 +353,7 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 
     TOPK_MED_MARK(3);
     // ---- 4. sort the candidates -------------------------------------------------------------------
-    const SortedList sorted = sort_candidates<kMItems>(ka, ia, kb, ib, cn, klo, khi, sm);
+    const SortedList sorted = sort_candidates<NT, kMItems>(ka, ia, kb, ib, cn, klo, khi, sm);
     skeys = sorted.keys;
     sidx = sorted.idx;
   }
@@ -351,7 +361,7 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
   TOPK_MED_MARK(4);
   // ---- 5. solve ---------------------------------------------------------------------------------------
   const int64_t n_sorted = (k_row >= 1 && k_row < n) ? int64_t(cn) : int64_t(n);
-  const RowInfo ri = RowSolver<kMT>::solve<MAG, PC>(skeys, sidx, tangent, n_sorted, int64_t(k), R,
+  const RowInfo ri = RowSolver<NT>::template solve<MAG, PC>(skeys, sidx, tangent, n_sorted, int64_t(k), R,
                                                     sm.solve);
 
   TOPK_MED_MARK(5);
@@ -374,14 +384,17 @@ __global__ __launch_bounds__(kMT) void medium_rows_kernel(
 // Long rows: sort and solve of a candidate list of up to kFinishMax elements (the dense list in
 // the "a" arrays, described by sel[row]) by one workgroup; writes the row's RowInfo.  Longer
 // lists are left to the multi-workgroup passes.
+constexpr int kFinishThreads = 1024;
+
 template <bool MAG, int PC>
-__global__ __launch_bounds__(kMT) void finish_kernel(uint32_t* keys_a, uint32_t* idx_a,
+__global__ __launch_bounds__(kFinishThreads) void finish_kernel(uint32_t* keys_a, uint32_t* idx_a,
                                                      uint32_t* keys_b, uint32_t* idx_b,
                                                      const float* __restrict__ tangent_all,
                                                      const RowSel* __restrict__ sel,
                                                      RowInfo* __restrict__ info, int64_t n,
                                                      int64_t k_row, Reg R) {
-  __shared__ MedShared sm;
+  constexpr int kMT = kFinishThreads, kLdsKeys = MedCfg<kFinishThreads>::kLdsKeys;
+  __shared__ MedShared<kFinishThreads> sm;
   const int64_t row = blockIdx.x;
   const RowSel rs = sel[row];
   if (int64_t(rs.cn) > kFinishMax) return;
@@ -391,7 +404,7 @@ __global__ __launch_bounds__(kMT) void finish_kernel(uint32_t* keys_a, uint32_t*
   TOPK_MED_MARK(0);
   uint32_t* kb = keys_b + base;
   uint32_t* ib = idx_b + base;
-  const SortedList sorted = sort_candidates<16>(ka, ia, kb, ib, rs.cn, rs.klo, rs.khi, sm);
+  const SortedList sorted = sort_candidates<kFinishThreads, 16>(ka, ia, kb, ib, rs.cn, rs.klo, rs.khi, sm);
   const uint32_t* skeys = sorted.keys;
   const uint32_t* sidx = sorted.idx;
   int src = sorted.global_src;
@@ -423,8 +436,12 @@ __global__ __launch_bounds__(kMT) void finish_kernel(uint32_t* keys_a, uint32_t*
 template <bool MAG, int PC>
 void launch(const SortBuffers& B, const float* x, const float* tangent, float* out, float* jvp,
             int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
-  hipLaunchKernelGGL((medium_rows_kernel<MAG, PC>), dim3(unsigned(rows)), dim3(kMT), 0, st, x,
-                     tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R);
+  if (n <= kSmallRowMax)
+    hipLaunchKernelGGL((medium_rows_kernel<MAG, PC, 256>), dim3(unsigned(rows)), dim3(256), 0, st, x,
+                       tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R);
+  else
+    hipLaunchKernelGGL((medium_rows_kernel<MAG, PC, 1024>), dim3(unsigned(rows)), dim3(1024), 0, st,
+                       x, tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R);
 }
 
 }  // namespace
@@ -444,7 +461,7 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
 int launch_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, int64_t rows,
                   int64_t n, int64_t k, const Reg& R, hipStream_t st) {
   if (rows > 0x7fffffffLL) return -1;
-  const dim3 grid{unsigned(rows)}, block{kMT};
+  const dim3 grid{unsigned(rows)}, block{kFinishThreads};
   if (!mag && pc == kP2)
     hipLaunchKernelGGL((finish_kernel<false, kP2>), grid, block, 0, st, B.keys_a, B.idx_a, B.keys_b,
                        B.idx_b, tangent, B.sel, B.info, n, k, R);
