@@ -43,11 +43,13 @@ def lib() -> ctypes.CDLL:
         i64 = ctypes.c_int64
         L.oracle_argsort_desc.argtypes = [f32p, i64, i64, i32p]
         L.oracle_argsort_desc.restype = ctypes.c_int
-        for fn in (L.oracle_topk_mask, L.oracle_topkmag):
+        for fn in (L.oracle_topk_mask, L.oracle_topkmag, L.oracle_topk_signed_mask,
+                   L.oracle_topk_masked_value):
             fn.argtypes = [f32p, f32p, i64, i64, i64, ctypes.c_int, ctypes.c_double, f64p, f64p,
                            i32p, i64p]
             fn.restype = ctypes.c_int
-        for fn in (L.oracle_topk_mask_f64, L.oracle_topkmag_f64):
+        for fn in (L.oracle_topk_mask_f64, L.oracle_topkmag_f64, L.oracle_topk_signed_mask_f64,
+                   L.oracle_topk_masked_value_f64):
             fn.argtypes = [f64p, f64p, i64, i64, i64, ctypes.c_int, ctypes.c_double, f64p, f64p,
                            i32p, i64p]
             fn.restype = ctypes.c_int
@@ -137,11 +139,23 @@ def topkmag(x, k, p, lam, tangent=None, want_perm=False, want_block=False, f64=F
     return _run(fn, x, k, p, lam, tangent, want_perm, want_block, f64)
 
 
+def topk_signed_mask(x, k, p, lam, tangent=None, want_perm=False, want_block=False, f64=False):
+    """Signed relaxed top-k mask (phi = |x|, paper Sec. 4 on the OWL norm): float64 results."""
+    fn = lib().oracle_topk_signed_mask_f64 if f64 else lib().oracle_topk_signed_mask
+    return _run(fn, x, k, p, lam, tangent, want_perm, want_block, f64)
+
+
+def topk_masked_value(x, k, p, lam, tangent=None, f64=False):
+    """x o mask_R(|x|), the alternative top-k in magnitude of the paper's Sec. 7."""
+    fn = lib().oracle_topk_masked_value_f64 if f64 else lib().oracle_topk_masked_value
+    return _run(fn, x, k, p, lam, tangent, False, False, f64)
+
+
 def value(x, k, p, lam, phi: str = "id") -> np.ndarray:
     """f_{phi,R}(x, 1_k) of each row (paper Prop. 2, the minimisation form), float64."""
     x = np.atleast_2d(np.ascontiguousarray(x, dtype=np.float64))
     out = np.empty(x.shape[0], dtype=np.float64)
-    rc = lib().oracle_topk_value({"id": 0, "half_sq": 1}[phi], _ptr(x, ctypes.c_double), x.shape[0],
+    rc = lib().oracle_topk_value({"id": 0, "half_sq": 1, "abs": 2}[phi], _ptr(x, ctypes.c_double), x.shape[0],
                                  x.shape[1], int(k), p_code(p), float(lam), _ptr(out, ctypes.c_double))
     if rc != 0:
         raise RuntimeError(f"oracle_topk_value failed: {rc}")

@@ -37,7 +37,10 @@
 
 namespace {
 
-enum Phi { PHI_ID = 0, PHI_HALF_SQ = 1 };   // phi(x) = x   |   phi(x) = x^2 / 2
+// phi(x) = x  |  phi(x) = x^2 / 2  |  phi(x) = |x| (the signed top-k mask of Sec. 4, "Connection
+// with k-support and OWL norms": on the non-negative cone of Prop. 6 it is the identity, so the
+// pooling steps are those of phi(x) = x, followed by the truncation at zero)
+enum Phi { PHI_ID = 0, PHI_HALF_SQ = 1, PHI_ABS = 2 };
 enum Pcode { P_2 = 0, P_4_3 = 1 };          // p = 2       |   p = 4/3
 
 struct Problem {
@@ -126,12 +129,12 @@ double cubic_root(const double* s, int64_t lo, int64_t hi, double lambda, double
 double pool(const Problem& P, const double* s, int64_t lo, int64_t hi, double S, double W) {
   const double cnt = double(hi - lo);
   if (P.p == P_2) {
-    if (P.phi == PHI_ID) return (S - P.lambda * W) / cnt;
+    if (P.phi != PHI_HALF_SQ) return (S - P.lambda * W) / cnt;
     return S / (P.lambda * W + cnt);
   }
   if (hi - lo == 1) {
     // singleton minimisers by direct solution
-    if (P.phi == PHI_ID) return s[lo] - P.lambda * std::cbrt(W);
+    if (P.phi != PHI_HALF_SQ) return s[lo] - P.lambda * std::cbrt(W);
     if (W == 0.0) return s[lo];
   }
   return cubic_root(s, lo, hi, P.lambda, W, P.phi == PHI_HALF_SQ);
@@ -222,18 +225,19 @@ void one_row(const Problem& P, const T* x, const T* tangent, int64_t n, int64_t 
   std::vector<double> s(n), w(n), v(n), sgn(n);
   std::vector<int64_t> blo(n), bhi(n);
 
-  const bool mag = (P.phi == PHI_HALF_SQ);
-  for (int64_t i = 0; i < n; ++i) z[i] = mag ? std::fabs(x[i]) : x[i];
+  const bool mag = (P.phi == PHI_HALF_SQ);   // quadratic phi: pooling steps with the w v^2/2 term
+  const bool even = (P.phi != PHI_ID);       // even phi: Prop. 6 (sort |x|, sign, v >= 0)
+  for (int64_t i = 0; i < n; ++i) z[i] = even ? std::fabs(x[i]) : x[i];
   argsort_desc(z.data(), n, sigma.data());
   for (int64_t i = 0; i < n; ++i) {
     s[i] = double(z[sigma[i]]);
     w[i] = (i < k) ? 1.0 : 0.0;                 // w = 1_k, Eq. (topk_mask)
     double xv = double(x[sigma[i]]);
-    sgn[i] = mag ? double((xv > 0.0) - (xv < 0.0)) : 1.0;   // sign(0) = 0
+    sgn[i] = even ? double((xv > 0.0) - (xv < 0.0)) : 1.0;   // sign(0) = 0
   }
   pav(P, s.data(), w.data(), n, v.data(), blo.data(), bhi.data());
   std::vector<char> clipped(n, 0);
-  if (mag) {
+  if (even) {
     // Prop. 6: non-negative monotone cone, handled by truncation of the unconstrained solution.
     for (int64_t i = 0; i < n; ++i) {
       clipped[i] = v[i] < 0.0;
@@ -297,9 +301,12 @@ void one_row(const Problem& P, const T* x, const T* tangent, int64_t n, int64_t 
       }
       dgamma = num / den;
     }
-    if (clipped[lo]) dgamma = 0.0;   // v is pinned at 0 there
-    for (int64_t j = lo; j < hi; ++j)
-      jvp[sigma[j]] = sgn[j] * hess_rstar(P, s[j] - v[j]) * (tau[j] - dgamma);
+    for (int64_t j = lo; j < hi; ++j) {
+      if (clipped[lo])   // v is pinned at 0 there: y = grad r*(x) itself (an odd function of x)
+        jvp[sigma[j]] = hess_rstar(P, s[j]) * double(tangent[sigma[j]]);
+      else
+        jvp[sigma[j]] = sgn[j] * hess_rstar(P, s[j] - v[j]) * (tau[j] - dgamma);
+    }
     i = hi;
   }
 }
@@ -316,6 +323,37 @@ int run_rows(Phi phi, const T* x, const T* tangent, int64_t rows, int64_t n, int
   for (int64_t r = 0; r < rows; ++r) {
     one_row<T>(P, x + r * n, tangent ? tangent + r * n : nullptr, n, k, out + r * n,
             jvp ? jvp + r * n : nullptr, perm ? perm + r * n : nullptr, ab ? ab + 2 * r : nullptr);
+  }
+  return 0;
+}
+
+// Sec. 7 ("Advantage of the non-linearity"): the alternative top-k in magnitude that applies the
+// relaxed top-k mask to |x| and multiplies the result by x,
+//     y = x o m(|x|),      dy = t o m(|x|) + x o J_m(|x|) (sign(x) o t),   sign(0) = 0.
+template <class T>
+int run_masked_value(const T* x, const T* tangent, int64_t rows, int64_t n, int64_t k, int p_code,
+                     double lambda, double* out, double* jvp) {
+  if (!x || !out) return -1;
+  if (rows < 0 || n < 1 || k < 0 || k > n) return -2;
+  if (!(lambda > 0.0) || !std::isfinite(lambda)) return -2;
+  if (p_code != P_2 && p_code != P_4_3) return -3;
+  Problem P{PHI_ID, Pcode(p_code), lambda};
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t r = 0; r < rows; ++r) {
+    const T* xr = x + r * n;
+    const T* tr = tangent ? tangent + r * n : nullptr;
+    std::vector<T> z(n), st(n);
+    std::vector<double> m(n), jm(n);
+    for (int64_t i = 0; i < n; ++i) {
+      z[i] = std::fabs(xr[i]);
+      if (tr) st[i] = T((xr[i] > 0) - (xr[i] < 0)) * tr[i];
+    }
+    one_row<T>(P, z.data(), tr ? st.data() : nullptr, n, k, m.data(), tr ? jm.data() : nullptr,
+               nullptr, nullptr);
+    for (int64_t i = 0; i < n; ++i) {
+      out[r * n + i] = double(xr[i]) * m[i];
+      if (tr && jvp) jvp[r * n + i] = double(tr[i]) * m[i] + double(xr[i]) * jm[i];
+    }
   }
   return 0;
 }
@@ -358,13 +396,37 @@ int oracle_topkmag_f64(const double* x, const double* tangent, int64_t rows, int
   return run_rows(PHI_HALF_SQ, x, tangent, rows, n, k, p_code, lambda, out, jvp, perm, ab);
 }
 
+// Signed relaxed top-k mask (phi = |x|), float32 and float64 inputs.
+int oracle_topk_signed_mask(const float* x, const float* tangent, int64_t rows, int64_t n,
+                            int64_t k, int p_code, double lambda, double* out, double* jvp,
+                            int32_t* perm, int64_t* ab) {
+  return run_rows(PHI_ABS, x, tangent, rows, n, k, p_code, lambda, out, jvp, perm, ab);
+}
+int oracle_topk_signed_mask_f64(const double* x, const double* tangent, int64_t rows, int64_t n,
+                                int64_t k, int p_code, double lambda, double* out, double* jvp,
+                                int32_t* perm, int64_t* ab) {
+  return run_rows(PHI_ABS, x, tangent, rows, n, k, p_code, lambda, out, jvp, perm, ab);
+}
+
+// x o mask(|x|); perm and ab are not produced (always pass null).
+int oracle_topk_masked_value(const float* x, const float* tangent, int64_t rows, int64_t n,
+                             int64_t k, int p_code, double lambda, double* out, double* jvp,
+                             int32_t*, int64_t*) {
+  return run_masked_value(x, tangent, rows, n, k, p_code, lambda, out, jvp);
+}
+int oracle_topk_masked_value_f64(const double* x, const double* tangent, int64_t rows, int64_t n,
+                                 int64_t k, int p_code, double lambda, double* out, double* jvp,
+                                 int32_t*, int64_t*) {
+  return run_masked_value(x, tangent, rows, n, k, p_code, lambda, out, jvp);
+}
+
 // f_{phi,R}(x, 1_k) of every row (Prop. 2), the function whose gradient in x the operators are;
 // the Fenchel-Young top-k loss of Sec. 6 ("Smooth top-k loss") is value - <x, t>.
 int oracle_topk_value(int phi_code, const double* x, int64_t rows, int64_t n, int64_t k, int p_code,
                       double lambda, double* value) {
   if (!x || !value || rows < 0 || n < 1 || k < 0 || k > n) return -1;
   if (!(lambda > 0.0) || !std::isfinite(lambda)) return -2;
-  if (phi_code < 0 || phi_code > 1 || p_code < 0 || p_code > 1) return -3;
+  if (phi_code < 0 || phi_code > 2 || p_code < 0 || p_code > 1) return -3;
   Problem P{Phi(phi_code), Pcode(p_code), lambda};
 #pragma omp parallel for schedule(dynamic, 16)
   for (int64_t r = 0; r < rows; ++r) {
@@ -380,7 +442,7 @@ int oracle_topk_value(int phi_code, const double* x, int64_t rows, int64_t n, in
 int oracle_pav(const double* s, const double* w, int64_t n, int phi_code, int p_code,
                double lambda, double* v, int64_t* block_id) {
   if (!s || !w || !v || n < 1 || !(lambda > 0.0)) return -1;
-  if (phi_code < 0 || phi_code > 1 || p_code < 0 || p_code > 1) return -3;
+  if (phi_code < 0 || phi_code > 2 || p_code < 0 || p_code > 1) return -3;
   Problem P{Phi(phi_code), Pcode(p_code), lambda};
   std::vector<int64_t> lo(n), hi(n);
   pav(P, s, w, n, v, lo.data(), hi.data());

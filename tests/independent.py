@@ -108,7 +108,10 @@ def simplex_projection(z):
 # Relaxed top-k in magnitude by its definition (Prop. 2): u* = argmin_u R*(x - u) + f_phi(u, 1_k),
 # f_phi(u, 1_k) = sum of the k largest u_i^2/2 = max over index sets I, |I| = k, of sum_I u_i^2/2;
 # y* = grad R*(x - u*).  Epigraph form, solved with SLSQP over all C(n, k) sets (n <= 6).
-def topkmag_by_definition(x, k, p, lam):
+#
+# phi = "abs": f_phi(u, 1_k) = sum of the k largest |u_i| (the OWL norm with w = 1_k, Sec. 4) =
+# max over index sets and sign patterns of sum_I eps_i u_i: linear constraints.
+def topkmag_by_definition(x, k, p, lam, phi="half_sq"):
     x = np.asarray(x, dtype=np.float64)
     n = x.size
     q = q_of(p)
@@ -134,6 +137,14 @@ def topkmag_by_definition(x, k, p, lam):
 
     cons = []
     for I in sets:
+        if phi == "abs":
+            for eps in itertools.product((-1.0, 1.0), repeat=k):
+                a = np.zeros(n + 1)
+                a[I] = -np.array(eps)
+                a[n] = 1.0
+                cons.append({"type": "ineq", "fun": lambda z, a=a: a @ z, "jac": lambda z, a=a: a})
+            continue
+
         def c(z, I=I):
             return z[n] - 0.5 * (z[I] ** 2).sum()
 
@@ -143,9 +154,14 @@ def topkmag_by_definition(x, k, p, lam):
             g[n] = 1.0
             return g
         cons.append({"type": "ineq", "fun": c, "jac": cj})
+
+    def f_phi(u):
+        a = np.sort(np.abs(u))[::-1][:k]
+        return a.sum() if phi == "abs" else 0.5 * (a ** 2).sum()
+
     best = None
     for start in (x.copy(), x / (1.0 + lam), 0.5 * x):
-        z0 = np.concatenate([start, [0.5 * np.sort(start ** 2)[::-1][:k].sum() + 1e-3]])
+        z0 = np.concatenate([start, [f_phi(start) + 1e-3]])
         res = optimize.minimize(obj, z0, jac=obj_grad, constraints=cons, method="SLSQP",
                                 options={"ftol": 1e-15, "maxiter": 500})
         if best is None or res.fun < best.fun:

@@ -512,3 +512,105 @@ def test_value_small_lambda_and_loss_lower_bound(oracle):
         ts = np.array([[1.0, 1.0, 1.0, 0.0, 0.0]])
         loss, grad = oracle.fenchel_young_loss(xs, ts, 3, p, 0.5)
         assert abs(loss[0] + 3 * 0.5 / p) < 1e-12 and np.abs(grad).max() < 1e-12
+
+
+# ----------------------------------------------------------------------------------------------
+# The two variants on |x|.  Signed mask (phi = |x|, Sec. 4): the definition of Prop. 2 with the
+# OWL norm f_phi(u, 1_k) = sum of the k largest |u_i|, solved as a constrained program; the value
+# lambda -> infinity where u* = 0 and y = grad R*(x) exactly; agreement with sign(x) o mask(|x|)
+# whenever the truncation at zero is inactive; the JVP by central differences.
+@pytest.mark.parametrize("p", [P2, P43])
+def test_signed_mask_vs_definition(oracle, p):
+    r = rng(21)
+    clipped_cases = 0
+    for trial in range(30):
+        n = int(r.integers(2, 6))
+        k = int(r.integers(1, n + 1))
+        lam = float(r.choice([0.1, 0.5, 2.0]))
+        x = r.normal(size=n).astype(np.float32)
+        y = oracle.topk_signed_mask(x, k, p, lam)["out"]
+        ref = ind.topkmag_by_definition(x.astype(np.float64), k, p, lam, phi="abs")
+        assert np.abs(y - ref).max() < 5e-5, (x, k, lam, y, ref)
+        m = oracle.topk_mask(np.abs(x), k, p, lam)["out"]
+        clipped_cases += int(np.abs(np.abs(y) - m).max() > 1e-3)
+    assert clipped_cases >= 3          # the truncation at zero was exercised
+
+
+def test_signed_mask_limits_and_jvp(oracle):
+    r = rng(22)
+    for p, q in ((P2, 2), (P43, 4)):
+        x = r.normal(size=(4, 9))
+        t = r.normal(size=(4, 9))
+        # lambda >= max |x|: every v is truncated to 0, y = grad r*(x), dy = hess r*(x) t
+        lam = 5.0
+        res = oracle.topk_signed_mask(x, 3, p, lam, tangent=t, f64=True)
+        assert np.allclose(res["out"], np.sign(x) * np.abs(x / lam) ** (q - 1), rtol=0, atol=1e-14)
+        assert np.allclose(res["jvp"], (q - 1) * np.abs(x / lam) ** (q - 2) / lam * t, rtol=0, atol=1e-14)
+        # top-k magnitudes above lambda: no truncation, the signed mask of |x|
+        xs = x * 3.0 + np.sign(x) * 2.0
+        lam = 0.5
+        res = oracle.topk_signed_mask(xs, 3, p, lam, tangent=t, f64=True)
+        m = oracle.topk_mask(np.abs(xs), 3, p, lam, tangent=np.sign(xs) * t, f64=True)
+        assert np.array_equal(res["out"], np.sign(xs) * m["out"])
+        assert np.array_equal(res["jvp"], np.sign(xs) * m["jvp"])
+        # hard limit: sign(x) o (top-k mask of |x|)
+        hard = oracle.topk_signed_mask(xs, 3, p, 1e-9, f64=True)["out"]
+        top = np.argsort(-np.abs(xs), axis=1)[:, :3]
+        ref = np.zeros_like(xs)
+        np.put_along_axis(ref, top, np.take_along_axis(np.sign(xs), top, 1), 1)
+        assert np.abs(hard - ref).max() < 1e-6
+    checked = 0
+    for _ in range(200):
+        p = P2 if r.random() < 0.5 else P43
+        n = int(r.integers(2, 20))
+        k = int(r.integers(1, n))
+        lam = float(r.choice([0.3, 1.0, 2.0]))
+        x, t = r.normal(size=n), r.normal(size=n)
+        fn = oracle.topk_signed_mask
+        if not _same_piece(fn, x, t, 1e-6, k, p, lam):
+            continue
+        # also stay on one side of the truncation at zero
+        o = [fn(x + d * t, k, p, lam, f64=True)["out"] for d in (-4e-6, 0.0, 4e-6)]
+        m = [oracle.topk_mask(np.abs(x + d * t), k, p, lam, f64=True)["out"] for d in (-4e-6, 0.0, 4e-6)]
+        cl = [np.abs(np.abs(a) - b) > 1e-12 for a, b in zip(o, m)]
+        if not (np.array_equal(cl[0], cl[1]) and np.array_equal(cl[1], cl[2])):
+            continue
+        jvp = fn(x, k, p, lam, tangent=t, f64=True)["jvp"]
+        fd = ind.central_diff_jvp(lambda z: fn(z, k, p, lam, f64=True)["out"], x, t, 1e-6)
+        assert np.abs(jvp - fd).max() < 2e-6 * max(1.0, np.abs(jvp).max()) / min(1.0, lam)
+        checked += 1
+    assert checked > 100
+
+
+# x o mask(|x|) (Sec. 7): lambda -> infinity gives (k / n) x, lambda -> 0 the hard top-k in
+# magnitude (both stated in the paper), in between the product with the mask pinned above; the
+# JVP by central differences.
+def test_masked_value_limits_and_jvp(oracle):
+    r = rng(23)
+    for p in (P2, P43):
+        x = r.normal(size=(5, 12))
+        k = 4
+        big = oracle.topk_masked_value(x, k, p, 1e8, f64=True)["out"]
+        assert np.abs(big - (k / 12) * x).max() < 1e-5
+        hard = oracle.topk_masked_value(x, k, p, 1e-9, f64=True)["out"]
+        keep = np.argsort(-np.abs(x), axis=1)[:, :k]
+        ref = np.zeros_like(x)
+        np.put_along_axis(ref, keep, np.take_along_axis(x, keep, 1), 1)
+        assert np.abs(hard - ref).max() < 1e-6
+        y = oracle.topk_masked_value(x, k, p, 0.4, f64=True)["out"]
+        assert np.array_equal(y, x * oracle.topk_mask(np.abs(x), k, p, 0.4, f64=True)["out"])
+    checked = 0
+    for _ in range(150):
+        p = P2 if r.random() < 0.5 else P43
+        n = int(r.integers(2, 20))
+        k = int(r.integers(1, n))
+        lam = float(r.choice([0.3, 1.0, 2.0]))
+        x, t = r.normal(size=n), r.normal(size=n)
+        if not _same_piece(oracle.topk_signed_mask, x, t, 1e-6, k, p, lam):
+            continue
+        fn = oracle.topk_masked_value
+        jvp = fn(x, k, p, lam, tangent=t, f64=True)["jvp"]
+        fd = ind.central_diff_jvp(lambda z: fn(z, k, p, lam, f64=True)["out"], x, t, 1e-6)
+        assert np.abs(jvp - fd).max() < 4e-6 * max(1.0, np.abs(jvp).max()) / min(1.0, lam)
+        checked += 1
+    assert checked > 80
