@@ -61,7 +61,9 @@ enum {
   TOPK_OP_MASK_JVP = 1,
   TOPK_OP_MAG_FWD = 2,
   TOPK_OP_MAG_JVP = 3,
-  TOPK_OP_ARGSORT = 4
+  TOPK_OP_ARGSORT = 4,
+  TOPK_OP_SIGNED_MASK = 5,   /* topk_signed_mask_fwd and _jvp */
+  TOPK_OP_MASKED_VALUE = 6   /* topk_masked_value_fwd and _jvp */
 };
 
 /* Rows up to this length are handled by one wavefront in registers (no workspace needed). */
@@ -118,6 +120,34 @@ int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n,
                 double p, double lambda, float* out, float* vjp_out, void* stream);
 
 /*
+ * Two more operators on the magnitudes, both built on the relaxed top-k mask m(.) of |x|.
+ *
+ * Signed relaxed top-k mask (phi(x) = |x|; Sec. 4, "Connection with k-support and OWL norms":
+ * with this phi the operator in magnitude becomes a signed top-k mask).  By the reduction of
+ * Prop. 6 the isotonic problem is the mask's on s = sort(|x|) with the constraint v >= 0, handled
+ * by truncation (Sec. 5), so per element y = sign(x) min(m_i, grad r*(|x_i|)): where the
+ * truncation is active (magnitudes below about lambda) y_i = grad r*(x_i) = sign(x_i) (|x_i| /
+ * lambda)^(q-1) and dy_i = hess r*(x_i) t_i, elsewhere y = sign(x) o m(|x|) and
+ * dy = sign(x) o J_m (sign(x) o t).  sign(0) = 0.
+ *
+ * Masked value (Sec. 7, "Advantage of the non-linearity": the alternative top-k in magnitude):
+ * y = x o m(|x|), dy = t o m(|x|) + x o J_m (sign(x) o t).
+ *
+ *   x, tangent [rows][n] in; out, jvp_out [rows][n] out (out is required by the *_jvp calls too).
+ *   Both need workspace for every row length (two float arrays of the input's size, plus the
+ *   mask's own for long rows): topk_workspace_bytes(TOPK_OP_SIGNED_MASK / TOPK_OP_MASKED_VALUE).
+ *   Otherwise the arguments, p values and errors of topk_mask_fwd / topk_mask_jvp.
+ */
+int topk_signed_mask_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p,
+                         double lambda, float* out, void* stream);
+int topk_signed_mask_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                         double p, double lambda, float* out, float* jvp_out, void* stream);
+int topk_masked_value_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p,
+                          double lambda, float* out, void* stream);
+int topk_masked_value_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                          double p, double lambda, float* out, float* jvp_out, void* stream);
+
+/*
  * Smooth top-k loss (Sec. 6, "Smooth top-k loss"): the Fenchel-Young loss of the relaxed top-k
  * mask, per row
  *     loss = f_{phi,R}(theta, 1_k) - <theta, target>,   phi(x) = x,
@@ -138,8 +168,9 @@ int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_
 int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm_out, void* stream);
 
 /*
- * Scratch memory (bytes) that `op` (a TOPK_OP_* code) needs for this shape; 0 when rows fit one
- * wavefront (n <= TOPK_SHORT_ROW_MAX).  Returns 0 for invalid arguments as well.
+ * Scratch memory (bytes) that `op` (a TOPK_OP_* code) needs for this shape; for the first five
+ * codes 0 when rows fit one wavefront (n <= TOPK_SHORT_ROW_MAX).  Returns 0 for invalid
+ * arguments as well.
  */
 size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p);
 

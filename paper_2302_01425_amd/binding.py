@@ -14,10 +14,12 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
 
-TOPK_OP_MASK_FWD, TOPK_OP_MASK_JVP, TOPK_OP_MAG_FWD, TOPK_OP_MAG_JVP, TOPK_OP_ARGSORT = range(5)
+(TOPK_OP_MASK_FWD, TOPK_OP_MASK_JVP, TOPK_OP_MAG_FWD, TOPK_OP_MAG_JVP, TOPK_OP_ARGSORT,
+ TOPK_OP_SIGNED_MASK, TOPK_OP_MASKED_VALUE) = range(7)
 
 EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
+    "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
     "topk_mask_loss", "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace",
     "topk_strerror",
 )
@@ -44,6 +46,12 @@ def load() -> ctypes.CDLL:
     L.topk_mask_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
     L.topkmag_fwd.argtypes = [vp, i64, i64, i64, dbl, dbl, vp, vp]
     L.topkmag_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
+    for name in ("topk_signed_mask_fwd", "topk_masked_value_fwd"):
+        getattr(L, name).argtypes = L.topk_mask_fwd.argtypes
+        getattr(L, name).restype = ci
+    for name in ("topk_signed_mask_jvp", "topk_masked_value_jvp"):
+        getattr(L, name).argtypes = L.topk_mask_jvp.argtypes
+        getattr(L, name).restype = ci
     L.topk_mask_vjp.argtypes = L.topk_mask_jvp.argtypes
     L.topkmag_vjp.argtypes = L.topkmag_jvp.argtypes
     L.topk_argsort_desc.argtypes = [vp, i64, i64, vp, vp]
@@ -160,6 +168,44 @@ def topkmag_jvp(x, tangent, k, p, lam, out=None, jvp_out=None, want_out=True, st
                               float(lam), None if out is None else out.data_ptr(),
                               jvp_out.data_ptr(), _stream(stream)), "topkmag_jvp")
     return out, jvp_out
+
+
+def _abs_variant(name, op, x, tangent, k, p, lam, out, jvp_out, stream):
+    x = _dev_f32(x, "x")
+    rows, n = x.shape
+    out = torch.empty_like(x) if out is None else _dev_f32(out, "out")
+    ensure_workspace(op, rows, n, k, p, x.device)
+    if tangent is None:
+        _check(getattr(load(), name + "_fwd")(x.data_ptr(), rows, n, int(k), float(p), float(lam),
+                                              out.data_ptr(), _stream(stream)), name + "_fwd")
+        return out
+    tangent = _dev_f32(tangent, "tangent")
+    jvp_out = torch.empty_like(x) if jvp_out is None else _dev_f32(jvp_out, "jvp_out")
+    _check(getattr(load(), name + "_jvp")(x.data_ptr(), tangent.data_ptr(), rows, n, int(k),
+                                          float(p), float(lam), out.data_ptr(), jvp_out.data_ptr(),
+                                          _stream(stream)), name + "_jvp")
+    return out, jvp_out
+
+
+def topk_signed_mask_fwd(x, k, p, lam, out=None, stream=None):
+    return _abs_variant("topk_signed_mask", TOPK_OP_SIGNED_MASK, x, None, k, p, lam, out, None, stream)
+
+
+def topk_signed_mask_jvp(x, tangent, k, p, lam, out=None, jvp_out=None, stream=None):
+    """Returns (out, jvp_out)."""
+    return _abs_variant("topk_signed_mask", TOPK_OP_SIGNED_MASK, x, tangent, k, p, lam, out, jvp_out,
+                        stream)
+
+
+def topk_masked_value_fwd(x, k, p, lam, out=None, stream=None):
+    return _abs_variant("topk_masked_value", TOPK_OP_MASKED_VALUE, x, None, k, p, lam, out, None,
+                        stream)
+
+
+def topk_masked_value_jvp(x, tangent, k, p, lam, out=None, jvp_out=None, stream=None):
+    """Returns (out, jvp_out)."""
+    return _abs_variant("topk_masked_value", TOPK_OP_MASKED_VALUE, x, tangent, k, p, lam, out,
+                        jvp_out, stream)
 
 
 def topk_mask_vjp(theta, cotangent, k, p, lam, out=None, vjp_out=None, want_out=True, stream=None):

@@ -85,10 +85,11 @@ Layout layout_for(int64_t rows, int64_t n) {
   return L;
 }
 
-int carve(int64_t rows, int64_t n, SortBuffers* B) {
+// `skip`: bytes at the start of the workspace that the caller keeps for itself
+int carve(int64_t rows, int64_t n, SortBuffers* B, size_t skip = 0) {
   const Layout L = layout_for(rows, n);
-  if (g_ws.ptr == nullptr || g_ws.bytes < L.total) return TOPK_ERR_WORKSPACE;
-  char* base = static_cast<char*>(g_ws.ptr);
+  if (g_ws.ptr == nullptr || g_ws.bytes < skip + L.total) return TOPK_ERR_WORKSPACE;
+  char* base = static_cast<char*>(g_ws.ptr) + skip;
   B->keys_a = reinterpret_cast<uint32_t*>(base + L.keys_a);
   B->keys_b = reinterpret_cast<uint32_t*>(base + L.keys_b);
   B->idx_a = reinterpret_cast<uint32_t*>(base + L.idx_a);
@@ -118,7 +119,7 @@ int finish() { return hipGetLastError() == hipSuccess ? TOPK_OK : TOPK_ERR_LAUNC
 // shared body of the four operator entry points
 int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, int64_t n,
                  int64_t k, double p, double lambda, float* out, float* jvp, bool need_out,
-                 bool need_jvp, void* stream) {
+                 bool need_jvp, void* stream, size_t ws_skip = 0) {
   int rc = check_shape(rows, n, k, lambda);
   if (rc != TOPK_OK) return rc;
   const int pc = p_code(p);
@@ -136,7 +137,7 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
     return finish();
   }
   SortBuffers B;
-  rc = carve(rows, n, &B);
+  rc = carve(rows, n, &B, ws_skip);
   if (rc != TOPK_OK) return rc;
   const LongMode mode = long_mode();
   if (mode == kAuto && n <= topk::kMediumRowMax) {
@@ -162,9 +163,60 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   return finish();
 }
 
+// The operators on |x|: |x| and sign(x) t go to the first two arrays of the workspace, the mask
+// kernels run on them into (out, jvp), an element-wise pass turns those into the results.
+size_t abs_scratch_bytes(int64_t rows, int64_t n) { return 2 * align_up(size_t(rows) * size_t(n) * 4); }
+
+int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int64_t rows,
+                     int64_t n, int64_t k, double p, double lambda, float* out, float* jvp,
+                     bool need_jvp, void* stream) {
+  int rc = check_shape(rows, n, k, lambda);
+  if (rc != TOPK_OK) return rc;
+  const int pc = p_code(p);
+  if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
+  if (rows == 0) return TOPK_OK;
+  if (x == nullptr || out == nullptr) return TOPK_ERR_NULL;
+  if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
+  const size_t skip = abs_scratch_bytes(rows, n);
+  if (g_ws.ptr == nullptr || g_ws.bytes < skip) return TOPK_ERR_WORKSPACE;
+  float* ax = static_cast<float*>(g_ws.ptr);
+  float* st = reinterpret_cast<float*>(static_cast<char*>(g_ws.ptr) + skip / 2);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t count = rows * n;
+  if (topk::launch_abs_prepare(x, need_jvp ? tangent : nullptr, ax, st, count, s) != 0)
+    return TOPK_ERR_INVALID;
+  rc = run_operator(false, ax, need_jvp ? st : nullptr, rows, n, k, p, lambda, out,
+                    need_jvp ? jvp : nullptr, true, need_jvp, stream, skip);
+  if (rc != TOPK_OK) return rc;
+  if (topk::launch_abs_finish(signed_mask, pc, x, tangent, out, need_jvp ? jvp : nullptr, count,
+                              make_reg(lambda), s) != 0)
+    return TOPK_ERR_INVALID;
+  return finish();
+}
+
 }  // namespace
 
 extern "C" {
+
+int topk_signed_mask_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p,
+                         double lambda, float* out, void* stream) {
+  return run_abs_operator(true, x, nullptr, rows, n, k, p, lambda, out, nullptr, false, stream);
+}
+
+int topk_signed_mask_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                         double p, double lambda, float* out, float* jvp_out, void* stream) {
+  return run_abs_operator(true, x, tangent, rows, n, k, p, lambda, out, jvp_out, true, stream);
+}
+
+int topk_masked_value_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p,
+                          double lambda, float* out, void* stream) {
+  return run_abs_operator(false, x, nullptr, rows, n, k, p, lambda, out, nullptr, false, stream);
+}
+
+int topk_masked_value_jvp(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                          double p, double lambda, float* out, float* jvp_out, void* stream) {
+  return run_abs_operator(false, x, tangent, rows, n, k, p, lambda, out, jvp_out, true, stream);
+}
 
 int topk_mask_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double p, double lambda,
                   float* out, void* stream) {
@@ -239,10 +291,12 @@ int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm
 size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p) {
   (void)k;
   (void)p;
-  if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_ARGSORT) return 0;
+  if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_MASKED_VALUE) return 0;
   if (rows <= 0 || n < 1 || n >= (int64_t(1) << 30)) return 0;
-  if (!is_long(n)) return 0;
-  return layout_for(rows, n).total;
+  const size_t own = (op == TOPK_OP_SIGNED_MASK || op == TOPK_OP_MASKED_VALUE)
+                         ? abs_scratch_bytes(rows, n) : 0;
+  if (!is_long(n)) return own;
+  return own + layout_for(rows, n).total;
 }
 
 int topk_set_workspace(void* dev_ptr, size_t bytes) {

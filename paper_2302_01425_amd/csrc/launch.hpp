@@ -118,4 +118,12 @@ int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& 
 int launch_mask_loss(int pc, const float* x, const float* target, float* grad, float* loss,
                      int64_t rows, int64_t n, double lambda, double p, hipStream_t st);
 
+// Element-wise passes of the operators built on the mask of |x| (signed mask, x o mask):
+// ax = |x| and st = sign(x) t before the mask kernels; afterwards, in place, out (holding the
+// mask) and jvp (holding its JVP) become the operator's outputs.  t / st / jvp may be null.
+int launch_abs_prepare(const float* x, const float* t, float* ax, float* st, int64_t count,
+                       hipStream_t stream);
+int launch_abs_finish(bool signed_mask, int pc, const float* x, const float* t, float* out,
+                      float* jvp, int64_t count, const Reg& R, hipStream_t stream);
+
 }  // namespace topk

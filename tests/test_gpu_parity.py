@@ -224,6 +224,36 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
+# ---- the operators on |x|: signed mask (phi = |x|) and x o mask(|x|) --------------------------------
+@pytest.mark.parametrize("rows,n", [(1, 1), (37, 64), (5, 300), (3, 5000), (1, 200000)])
+def test_signed_mask_and_masked_value(gpu, oracle, rows, n):
+    r = np.random.default_rng(31 * n + rows)
+    x = r.normal(size=(rows, n)).astype(np.float32)
+    x[0, 0] = 0.0
+    if n >= 8:
+        x[:, 3] = -x[:, 2]                                   # equal magnitudes, opposite signs
+        x[-1, n // 2:] = np.float32(-0.0)
+    t = r.normal(size=(rows, n)).astype(np.float32)
+    xd, td = dev(x), dev(t)
+    for p in (P2, P43):
+        # lambda = 0.05: no truncation at zero; 1.5: the pooled block is truncated for small k;
+        # 40: everything is
+        for k, lam in ((max(1, n // 10), 0.05), (max(1, n // 3), 1.5), (min(n, 2), 40.0), (n, 0.7),
+                       (0, 0.7)):
+            if p == P43 and n > 10000 and lam > 1.0 and 0 < k < n:
+                continue          # the oracle's p = 4/3 pooling is quadratic in the block length
+            print(f"case shape={x.shape} k={k} p={p:.4f} lam={lam}", flush=True)
+            for name, ofn in (("topk_signed_mask", oracle.topk_signed_mask),
+                              ("topk_masked_value", oracle.topk_masked_value)):
+                ref = ofn(x, k, p, lam, tangent=t)
+                out1 = host(getattr(gpu, name + "_fwd")(xd, k, p, lam))
+                out2, jv = (host(a) for a in getattr(gpu, name + "_jvp")(xd, td, k, p, lam))
+                assert np.array_equal(out1, out2), name
+                close(out1, ref["out"], name + " fwd")
+                close(jv, ref["jvp"], name + " jvp")
+                assert np.all(out1[ref["out"] == 0.0] == 0.0)
+
+
 # ---- paper examples through the GPU path ----------------------------------------------------------
 def test_fig1_points(gpu, oracle):
     for lam in (0.25, 1.0):
