@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the operator, time a plain device copy of the same footprint "
                          "(theta|tangent -> out|jvp); used to scale the rocprofv3 byte counters")
+    ap.add_argument("--sweep-solvers", action="store_true",
+                    help="instead of the one JSON line: forward pass of the mask (p = 2) over row "
+                         "lengths 16 .. 2^22, exact solve vs 100 Dykstra iterations vs torch.topk")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the one JSON line: time the mask forward + JVP over row lengths "
                          "64 .. 2^24 at a constant 2^24 elements, k = ceil(n/10) (the paper's timing "
@@ -184,6 +187,54 @@ def sweep(a):
             torch.cuda.empty_cache()
 
 
+def sweep_solvers(a):
+    """Forward pass of the relaxed top-k mask (p = 2, lambda = 0.1) against the row length, with
+    k = ceil(n / 10) as in the paper's run-time comparison (Sec. 5, figure "Runtime comparison"):
+    the library's exact solve, 100 iterations of Dykstra's algorithm (rows up to 1024 elements),
+    and a hard top-k (torch.topk, the framework's own primitive).  2^22 elements per call,
+    stream launches timed with events.  Not the benchmark contract: one JSON line per length."""
+    import torch
+    from paper_2302_01425_amd import binding
+    from paper_2302_01425_amd.workloads import Workload
+    total = 1 << 22
+    stream = torch.cuda.Stream()
+
+    def timed(fn, steps=20, warmup=3):
+        with torch.cuda.stream(stream):
+            for _ in range(warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            stream.synchronize()
+            e0.record(stream)
+            for _ in range(steps):
+                fn()
+            e1.record(stream)
+            stream.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e3
+
+    for lg in (4, 6, 8, 10, 12, 14, 16, 18, 20, 22):
+        n = 1 << lg
+        rows = total // n
+        k = -(-n // 10)
+        w = Workload(f"solvers_n{n}", "mask", rows, n, k, 2.0, 0.1, 8, "normal", 1.0)
+        x = torch.from_numpy(w.inputs()[0]).cuda()
+        out = torch.empty_like(x)
+        binding.ensure_workspace(binding.TOPK_OP_MASK_FWD, rows, n, k, 2.0, x.device)
+        line = {"sweep": "mask fwd, p = 2, lambda = 0.1, 2^22 elements, k = ceil(n/10)", "n": n,
+                "rows": rows}
+        line["exact_us"] = timed(lambda: binding.topk_mask_fwd(x, k, 2.0, 0.1, out=out, stream=stream))
+        if n <= 1024:
+            line["dykstra100_us"] = timed(
+                lambda: binding.topk_mask_dykstra_fwd(x, k, 0.1, 100, out=out, stream=stream))
+            exact = binding.topk_mask_fwd(x, k, 2.0, 0.1)
+            approx = binding.topk_mask_dykstra_fwd(x, k, 0.1, 100)
+            line["dykstra100_max_abs_diff"] = float((exact - approx).abs().max())
+        line["hard_topk_us"] = timed(lambda: torch.topk(x, k, dim=1))
+        print(json.dumps(line), flush=True)
+        del x, out
+        torch.cuda.empty_cache()
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -198,6 +249,9 @@ def main():
     torch.cuda.set_device(0)
     if a.sweep:
         sweep(a)
+        return
+    if a.sweep_solvers:
+        sweep_solvers(a)
         return
     w = WORKLOADS[a.workload]
     algo_bytes = BYTES_PER_ELEMENT * w.rows * w.n

@@ -120,6 +120,18 @@ int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n,
                 double p, double lambda, float* out, float* vjp_out, void* stream);
 
 /*
+ * Relaxed top-k mask for p = 2 by Dykstra's alternating projection algorithm (Sec. 5, Alg. 1)
+ * instead of the exact solve: `iters` rounds of projections onto the even-pair and odd-pair
+ * constraint sets, started from s - lambda 1_k on the sorted row (the linear term enters once).
+ * An approximation that converges to topk_mask_fwd's result as iters grows (the paper uses 100);
+ * iters == 0 returns the hard top-k mask.  The alternative solver for comparisons: rows up to
+ * TOPK_SHORT_ROW_MAX elements only (TOPK_ERR_INVALID beyond, and for iters < 0), float64
+ * iterates in registers, no workspace.  Other arguments and errors as topk_mask_fwd.
+ */
+int topk_mask_dykstra_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double lambda,
+                          int iters, float* out, void* stream);
+
+/*
  * Two more operators on the magnitudes, both built on the relaxed top-k mask m(.) of |x|.
  *
  * Signed relaxed top-k mask (phi(x) = |x|; Sec. 4, "Connection with k-support and OWL norms":

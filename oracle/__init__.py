@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
             fn.argtypes = [f64p, f64p, i64, i64, i64, ctypes.c_int, ctypes.c_double, f64p, f64p,
                            i32p, i64p]
             fn.restype = ctypes.c_int
+        L.oracle_topk_mask_dykstra.argtypes = [f32p, i64, i64, i64, ctypes.c_double, i64, f64p]
+        L.oracle_topk_mask_dykstra.restype = ctypes.c_int
         L.oracle_pav.argtypes = [f64p, f64p, i64, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                  f64p, i64p]
         L.oracle_pav.restype = ctypes.c_int
@@ -149,6 +151,17 @@ def topk_masked_value(x, k, p, lam, tangent=None, f64=False):
     """x o mask_R(|x|), the alternative top-k in magnitude of the paper's Sec. 7."""
     fn = lib().oracle_topk_masked_value_f64 if f64 else lib().oracle_topk_masked_value
     return _run(fn, x, k, p, lam, tangent, False, False, f64)
+
+
+def topk_mask_dykstra(theta, k, lam, iters) -> np.ndarray:
+    """Relaxed top-k mask, p = 2, after ``iters`` iterations of Dykstra's algorithm (Alg. 1)."""
+    x2 = _as_rows(theta)
+    out = np.empty(x2.shape, dtype=np.float64)
+    rc = lib().oracle_topk_mask_dykstra(_ptr(x2, ctypes.c_float), x2.shape[0], x2.shape[1], int(k),
+                                        float(lam), int(iters), _ptr(out, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"oracle_topk_mask_dykstra failed: {rc}")
+    return out.reshape(np.shape(theta))
 
 
 def value(x, k, p, lam, phi: str = "id") -> np.ndarray:

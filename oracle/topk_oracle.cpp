@@ -420,6 +420,47 @@ int oracle_topk_masked_value_f64(const double* x, const double* tangent, int64_t
   return run_masked_value(x, tangent, rows, n, k, p_code, lambda, out, jvp);
 }
 
+// Sec. 5, Alg. 1: Dykstra's alternating projections for the relaxed top-k mask with p = 2, as an
+// approximation with a fixed number of iterations.  Sorted row s, w = 1_k; the problem is the
+// Euclidean projection of s - lambda w onto C1 n C2, so the linear term is applied once, to the
+// starting point (the listing prints it inside both argmins, which would count it twice).
+//   v^0 = s - lambda w,  p^0 = q^0 = 0
+//   y^t = P_C1(v^t + p^t),  p^{t+1} = v^t + p^t - y^t,
+//   v^{t+1} = P_C2(y^t + q^t),  q^{t+1} = y^t + q^t - v^{t+1}
+// P_C1 / P_C2: every pair (1,2),(3,4),.. / (2,3),(4,5),.. that violates z_i >= z_{i+1} is replaced
+// by its mean.  Output y = (s - v^iters) / lambda in the original order.
+int oracle_topk_mask_dykstra(const float* theta, int64_t rows, int64_t n, int64_t k, double lambda,
+                             int64_t iters, double* out) {
+  if (!theta || !out || rows < 0 || n < 1 || k < 0 || k > n || iters < 0) return -1;
+  if (!(lambda > 0.0) || !std::isfinite(lambda)) return -2;
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t r = 0; r < rows; ++r) {
+    const float* x = theta + r * n;
+    std::vector<int32_t> sigma(n);
+    argsort_desc(x, n, sigma.data());
+    std::vector<double> s(n), v(n), p(n, 0.0), q(n, 0.0), z(n), y(n);
+    for (int64_t i = 0; i < n; ++i) {
+      s[i] = double(x[sigma[i]]);
+      v[i] = s[i] - lambda * (i < k ? 1.0 : 0.0);
+    }
+    auto project = [&](const std::vector<double>& in, std::vector<double>& res, int64_t first) {
+      res = in;
+      for (int64_t i = first; i + 1 < n; i += 2)
+        if (in[i] < in[i + 1]) res[i] = res[i + 1] = 0.5 * (in[i] + in[i + 1]);
+    };
+    for (int64_t t = 0; t < iters; ++t) {
+      for (int64_t i = 0; i < n; ++i) z[i] = v[i] + p[i];
+      project(z, y, 0);
+      for (int64_t i = 0; i < n; ++i) p[i] = z[i] - y[i];
+      for (int64_t i = 0; i < n; ++i) z[i] = y[i] + q[i];
+      project(z, v, 1);
+      for (int64_t i = 0; i < n; ++i) q[i] = z[i] - v[i];
+    }
+    for (int64_t i = 0; i < n; ++i) out[r * n + sigma[i]] = (s[i] - v[i]) / lambda;
+  }
+  return 0;
+}
+
 // f_{phi,R}(x, 1_k) of every row (Prop. 2), the function whose gradient in x the operators are;
 // the Fenchel-Young top-k loss of Sec. 6 ("Smooth top-k loss") is value - <x, t>.
 int oracle_topk_value(int phi_code, const double* x, int64_t rows, int64_t n, int64_t k, int p_code,

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
 
 EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
-    "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
+    "topk_mask_dykstra_fwd", "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
     "topk_mask_loss", "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace",
     "topk_strerror",
 )
@@ -52,6 +52,8 @@ def load() -> ctypes.CDLL:
     for name in ("topk_signed_mask_jvp", "topk_masked_value_jvp"):
         getattr(L, name).argtypes = L.topk_mask_jvp.argtypes
         getattr(L, name).restype = ci
+    L.topk_mask_dykstra_fwd.argtypes = [vp, i64, i64, i64, dbl, ci, vp, vp]
+    L.topk_mask_dykstra_fwd.restype = ci
     L.topk_mask_vjp.argtypes = L.topk_mask_jvp.argtypes
     L.topkmag_vjp.argtypes = L.topkmag_jvp.argtypes
     L.topk_argsort_desc.argtypes = [vp, i64, i64, vp, vp]
@@ -185,6 +187,15 @@ def _abs_variant(name, op, x, tangent, k, p, lam, out, jvp_out, stream):
                                           float(p), float(lam), out.data_ptr(), jvp_out.data_ptr(),
                                           _stream(stream)), name + "_jvp")
     return out, jvp_out
+
+
+def topk_mask_dykstra_fwd(theta, k, lam, iters, out=None, stream=None):
+    theta = _dev_f32(theta, "theta")
+    rows, n = theta.shape
+    out = torch.empty_like(theta) if out is None else _dev_f32(out, "out")
+    _check(load().topk_mask_dykstra_fwd(theta.data_ptr(), rows, n, int(k), float(lam), int(iters),
+                                        out.data_ptr(), _stream(stream)), "topk_mask_dykstra_fwd")
+    return out
 
 
 def topk_signed_mask_fwd(x, k, p, lam, out=None, stream=None):

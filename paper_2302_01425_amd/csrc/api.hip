@@ -198,6 +198,19 @@ int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int
 
 extern "C" {
 
+int topk_mask_dykstra_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double lambda,
+                          int iters, float* out, void* stream) {
+  const int rc = check_shape(rows, n, k, lambda);
+  if (rc != TOPK_OK) return rc;
+  if (iters < 0 || n > TOPK_SHORT_ROW_MAX) return TOPK_ERR_INVALID;
+  if (rows == 0) return TOPK_OK;
+  if (theta == nullptr || out == nullptr) return TOPK_ERR_NULL;
+  if (topk::launch_short_dykstra(theta, out, rows, int(n), int(k), lambda, iters,
+                                 static_cast<hipStream_t>(stream)) != 0)
+    return TOPK_ERR_INVALID;
+  return finish();
+}
+
 int topk_signed_mask_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p,
                          double lambda, float* out, void* stream) {
   return run_abs_operator(true, x, nullptr, rows, n, k, p, lambda, out, nullptr, false, stream);

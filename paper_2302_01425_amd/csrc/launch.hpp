@@ -118,6 +118,11 @@ int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& 
 int launch_mask_loss(int pc, const float* x, const float* target, float* grad, float* loss,
                      int64_t rows, int64_t n, double lambda, double p, hipStream_t st);
 
+// Relaxed top-k mask, p = 2, by `iters` iterations of Dykstra's alternating projections (Alg. 1)
+// on the sorted row instead of the exact block search; n <= 1024.
+int launch_short_dykstra(const float* x, float* out, int64_t rows, int n, int k, double lambda,
+                         int iters, hipStream_t st);
+
 // Element-wise passes of the operators built on the mask of |x| (signed mask, x o mask):
 // ax = |x| and st = sign(x) t before the mask kernels; afterwards, in place, out (holding the
 // mask) and jvp (holding its JVP) become the operator's outputs.  t / st / jvp may be null.

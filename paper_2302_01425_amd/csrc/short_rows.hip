@@ -336,6 +336,107 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
   }
 }
 
+// ---- Dykstra's alternating projections (Sec. 5, Alg. 1) as an alternative solver ----------------
+// p = 2, phi = identity.  The isotonic problem is the Euclidean projection of s - lambda w onto
+// the monotone cone C1 n C2 (C1: v_1 >= v_2, v_3 >= v_4, ..; C2: v_2 >= v_3, ..).  The linear term
+// is applied once, to the starting point; each iteration is
+//     z = v + p,  y = P_C1(z),  p = z - y,   z' = y + q,  v = P_C2(z'),  q = z' - v,
+// where a projection replaces every violating pair (z_i < z_{i+1}) by its mean.  Everything stays
+// in float64 registers: the C1 pairs lie inside a lane (E is even), the C2 pairs inside a lane or
+// between the last position of a lane and the first of the next.  Output (s - v) / lambda.
+template <int GL, int E, bool VEC>
+__global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void dykstra_rows_kernel(
+    const float* __restrict__ x, float* __restrict__ out, int64_t rows, int n, int k, double lambda,
+    double inv_lambda, int iters) {
+  using C = ShortCfg<GL, E>;
+  constexpr int NP = C::NP, RPW = C::RPW, RS = C::RS, IDXB = C::IDXB;
+  static_assert(E % 2 == 0, "pairs of C1 must not straddle lanes");
+  __shared__ __attribute__((aligned(16))) float lds[C::WPB][RPW * RS];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int lr = lane_in_group<GL>();
+  const int wv = threadIdx.x / kWave;
+  const int64_t wave = int64_t(blockIdx.x) * C::WPB + wv;
+  int64_t row = wave * RPW + lane / GL;
+  const bool valid = row < rows;
+  if (!valid) row = rows - 1;            // keep the lanes alive for the exchanges; no stores
+  const int64_t base = row * n;
+  const int e0 = lr * E;
+  float* ly = &lds[wv][(lane / GL) * RS];
+
+  float xin[E];
+  load_elems<E, VEC>(x, base, e0, n, xin);
+  double K[E];
+  make_keys<E, false, IDXB>(xin, e0, n, K);
+  SortRuns<GL, E, NP>::run(K, lr);
+
+  double s[E], v[E], pc[E], qc[E];
+  uint32_t field[E];
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    uint32_t key;
+    unpack<IDXB>(K[r], key, field[r]);
+    s[r] = double(key_to_float(key));
+    v[r] = (e0 + r < k) ? s[r] - lambda : s[r];
+    pc[r] = 0.0;
+    qc[r] = 0.0;
+  }
+  // pairs (i, i+1), 0-based sorted positions, exist for i + 1 < n
+  const bool pair_up = (GL > 1) && (lr < GL - 1) && (e0 + E < n);   // (last of this lane, first of the next)
+  const bool pair_dn = (GL > 1) && (lr > 0) && (e0 < n);            // (last of the previous lane, first of this)
+  for (int it = 0; it < iters; ++it) {
+    double z[E], y[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) { z[r] = v[r] + pc[r]; y[r] = z[r]; }
+#pragma unroll
+    for (int r = 0; r + 1 < E; r += 2) {
+      const bool viol = (e0 + r + 1 < n) && (z[r] < z[r + 1]);
+      const double mean = 0.5 * (z[r] + z[r + 1]);
+      y[r] = viol ? mean : z[r];
+      y[r + 1] = viol ? mean : z[r + 1];
+    }
+#pragma unroll
+    for (int r = 0; r < E; ++r) { pc[r] = z[r] - y[r]; z[r] = y[r] + qc[r]; v[r] = z[r]; }
+#pragma unroll
+    for (int r = 1; r + 1 < E; r += 2) {
+      const bool viol = (e0 + r + 1 < n) && (z[r] < z[r + 1]);
+      const double mean = 0.5 * (z[r] + z[r + 1]);
+      v[r] = viol ? mean : z[r];
+      v[r + 1] = viol ? mean : z[r + 1];
+    }
+    if constexpr (GL > 1) {
+      const double next_first = __shfl_down(z[0], 1, GL);
+      const double prev_last = __shfl_up(z[E - 1], 1, GL);
+      const bool viol_up = pair_up && (z[E - 1] < next_first);
+      const bool viol_dn = pair_dn && (prev_last < z[0]);
+      v[E - 1] = viol_up ? 0.5 * (z[E - 1] + next_first) : v[E - 1];
+      v[0] = viol_dn ? 0.5 * (prev_last + z[0]) : v[0];
+    }
+#pragma unroll
+    for (int r = 0; r < E; ++r) qc[r] = z[r] - v[r];
+  }
+#pragma unroll
+  for (int r = 0; r < E; ++r)
+    if (e0 + r < n) ly[field[r]] = float((s[r] - v[r]) * inv_lambda);
+  __builtin_amdgcn_wave_barrier();
+  if (!valid) return;
+  float yv[E];
+  lds_load<E>(ly + e0, yv);
+  store_elems<E, VEC>(out, base, e0, n, yv);
+}
+
+template <int GL, int E, bool VEC>
+int launch_dykstra_shape(const float* x, float* out, int64_t rows, int n, int k, double lambda,
+                         int iters, hipStream_t st) {
+  using C = ShortCfg<GL, E>;
+  const int64_t waves = (rows + C::RPW - 1) / C::RPW;
+  const int64_t blocks = (waves + C::WPB - 1) / C::WPB;
+  if (blocks > 0x7fffffffLL) return -1;
+  hipLaunchKernelGGL((dykstra_rows_kernel<GL, E, VEC>), dim3((unsigned)blocks),
+                     dim3(C::WPB * kWave), 0, st, x, out, rows, n, k, lambda, 1.0 / lambda, iters);
+  return 0;
+}
+
 // ---------------------------------------------------------------------------------------------
 template <int GL, int E, bool VEC>
 int launch_shape(bool mag, int pc, const float* x, const float* t, float* out, float* jvp,
@@ -435,6 +536,19 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
     const int rc = launch_short_rows_fast(np, lg, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
     if (rc != -2) return rc;
   }
+  TOPK_SHAPE_TABLE
+#undef CALL
+  return -1;
+}
+
+int launch_short_dykstra(const float* x, float* out, int64_t rows, int n, int k, double lambda,
+                         int iters, hipStream_t st) {
+  const bool vec = (n % 4 == 0) && aligned16(x) && aligned16(out);
+  int np = 2;
+  while (np < n) np <<= 1;
+#define CALL(GL, E, V) launch_dykstra_shape<GL, E, V>(x, out, rows, n, k, lambda, iters, st)
+  if (np == 2) return CALL(1, 2, false);
+  const int lg = pick_log_gl(np, rows);
   TOPK_SHAPE_TABLE
 #undef CALL
   return -1;

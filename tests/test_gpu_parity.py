@@ -224,6 +224,32 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
+# ---- Dykstra's algorithm with a fixed number of iterations ----------------------------------------
+@pytest.mark.parametrize("n", [1, 2, 3, 16, 63, 64, 100, 400, 1024])
+def test_dykstra_iterations(gpu, oracle, n):
+    r = np.random.default_rng(400 + n)
+    for rows in (1, 50):
+        x = r.normal(size=(rows, n)).astype(np.float32)
+        if n >= 4:
+            x[:, 1] = x[:, 0]
+            x[-1] = np.round(x[-1] * 2) / 2
+        xd = dev(x)
+        for k in sorted({0, 1, max(1, n // 10), n // 2, n}):
+            for lam, iters in ((0.1, 100), (1.0, 100), (2.5, 7), (0.5, 0), (1.0, 1)):
+                print(f"case shape={x.shape} k={k} lam={lam} iters={iters}", flush=True)
+                ref = oracle.topk_mask_dykstra(x, k, lam, iters)
+                got = host(gpu.topk_mask_dykstra_fwd(xd, k, lam, iters))
+                close(got, ref, "dykstra")
+    # the iterates approach the exact operator (how fast depends on the length of the pooled block)
+    x = r.normal(size=(20, n)).astype(np.float32)
+    k = max(1, n // 10)
+    exact = host(gpu.topk_mask_fwd(dev(x), k, P2, 1.0))
+    err = [np.abs(exact - host(gpu.topk_mask_dykstra_fwd(dev(x), k, 1.0, it))).max()
+           for it in (10, 100, 1000, 20000)]
+    assert err[1] <= err[0] + 1e-6 and err[2] <= err[1] + 1e-6 and err[3] <= err[2] + 1e-6, err
+    assert err[3] < 1e-2, err
+
+
 # ---- the operators on |x|: signed mask (phi = |x|) and x o mask(|x|) --------------------------------
 @pytest.mark.parametrize("rows,n", [(1, 1), (37, 64), (5, 300), (3, 5000), (1, 200000)])
 def test_signed_mask_and_masked_value(gpu, oracle, rows, n):

@@ -614,3 +614,50 @@ def test_masked_value_limits_and_jvp(oracle):
         assert np.abs(jvp - fd).max() < 4e-6 * max(1.0, np.abs(jvp).max()) / min(1.0, lam)
         checked += 1
     assert checked > 80
+
+
+# ----------------------------------------------------------------------------------------------
+# Dykstra's algorithm (Alg. 1) with a fixed iteration count: the first iterations of a three-
+# element row worked out by hand; the limit is the exact operator (the Euclidean projection onto
+# the monotone cone, i.e. the library isotonic regression of s - lambda w); the iterates of a
+# separately written numpy version; zero iterations give the hard mask.
+def test_dykstra_iterations(oracle):
+    # s = (1, 0.8, 0), k = 1, lambda = 1: v0 = (0, 0.8, 0).
+    # iteration 1: C1 pair (1,2): 0 < 0.8 -> (0.4, 0.4, 0), p = (-0.4, 0.4, 0); C2 pair (2,3): fine
+    #   -> v1 = (0.4, 0.4, 0), q = 0, y = s - v1 = (0.6, 0.4, 0)
+    # iteration 2: z = v1 + p = (0, 0.8, 0) -> same projection, v2 = v1: converged after one.
+    x = np.array([0.8, 0.0, 1.0], dtype=np.float32)                 # un-sorted on purpose
+    a = float(np.float32(0.8))
+    for it in (1, 2, 7):
+        y = oracle.topk_mask_dykstra(x, 1, 1.0, it)
+        assert np.allclose(y, [a - 0.5 * a, 0.0, 1.0 - 0.5 * a], rtol=0, atol=1e-15), (it, y)
+    # s = (3, 2, 2.5, 1) sorted (3, 2.5, 2, 1), k = 2, lambda = 2: v0 = (1, 0.5, 2, 1)
+    # it 1: C1 pairs (1,2): 1 >= 0.5 ok; (3,4): 2 >= 1 ok -> y = v0, p = 0;
+    #       C2 pair (2,3): 0.5 < 2 -> 1.25, 1.25 -> v1 = (1, 1.25, 1.25, 1), q = (0, -0.75, 0.75, 0)
+    x = np.array([3.0, 2.0, 2.5, 1.0], dtype=np.float32)
+    y1 = oracle.topk_mask_dykstra(x, 2, 2.0, 1)
+    assert np.allclose(y1, [(3 - 1) / 2, (2 - 1.25) / 2, (2.5 - 1.25) / 2, 0.0], rtol=0, atol=1e-15)
+    # it 2: z = v1 + p = v1: C1 (1,2): 1 < 1.25 -> 1.125 both; (3,4) ok -> y = (1.125, 1.125, 1.25, 1)
+    #       p = (-0.125, 0.125, 0, 0); z' = y + q = (1.125, 0.375, 2, 1): C2 (2,3): -> 1.1875 both
+    #       v2 = (1.125, 1.1875, 1.1875, 1)
+    y2 = oracle.topk_mask_dykstra(x, 2, 2.0, 2)
+    assert np.allclose(y2, [(3 - 1.125) / 2, (2 - 1.1875) / 2, (2.5 - 1.1875) / 2, 0.0], rtol=0,
+                       atol=1e-15)
+    r = rng(31)
+    for _ in range(30):
+        n = int(r.integers(1, 40))
+        k = int(r.integers(0, n + 1))
+        lam = float(r.choice([0.1, 1.0, 3.0]))
+        x = r.normal(size=n).astype(np.float32)
+        hard = oracle.topk_mask_dykstra(x, k, lam, 0)
+        ref = np.zeros(n)
+        ref[np.argsort(-x, kind="stable")[:k]] = 1.0
+        assert np.abs(hard - ref).max() < 1e-12
+        exact = oracle.topk_mask(x, k, P2, lam)["out"]
+        assert np.abs(oracle.topk_mask_dykstra(x, k, lam, 20000) - exact).max() < 1e-8
+        s = np.sort(x.astype(np.float64))[::-1]
+        w = (np.arange(n) < k).astype(np.float64)
+        for it in (1, 3, 10):
+            v = ind.dykstra_mask_p2(s, w, lam, iters=it)
+            got = oracle.topk_mask_dykstra(s.astype(np.float32), k, lam, it)
+            assert np.abs(got - (s - v) / lam).max() < 1e-13
