@@ -55,6 +55,12 @@ def lib() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
         L.oracle_topk_mask_dykstra.argtypes = [f32p, i64, i64, i64, ctypes.c_double, i64, f64p]
         L.oracle_topk_mask_dykstra.restype = ctypes.c_int
+        L.oracle_topk_general.argtypes = [ctypes.c_int, f32p, f32p, i64, f32p, i64, i64, ctypes.c_int,
+                                          ctypes.c_double, f64p, f64p]
+        L.oracle_topk_general.restype = ctypes.c_int
+        L.oracle_topk_general_f64.argtypes = [ctypes.c_int, f64p, f32p, i64, f64p, i64, i64,
+                                              ctypes.c_int, ctypes.c_double, f64p, f64p]
+        L.oracle_topk_general_f64.restype = ctypes.c_int
         L.oracle_pav.argtypes = [f64p, f64p, i64, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                  f64p, i64p]
         L.oracle_pav.restype = ctypes.c_int
@@ -162,6 +168,30 @@ def topk_mask_dykstra(theta, k, lam, iters) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"oracle_topk_mask_dykstra failed: {rc}")
     return out.reshape(np.shape(theta))
+
+
+def topk_general(x, w, p, lam, phi: str = "id", tangent=None, f64=False):
+    """Relaxed operator y_{phi,R}(x, w) for non-increasing weights w ([n], or one row per row of
+    x) and its JVP in x: dict with "out" (and "jvp"), float64."""
+    dt, cty = (np.float64, ctypes.c_double) if f64 else (np.float32, ctypes.c_float)
+    x2 = _as_rows(x, dt)
+    rows, n = x2.shape
+    w2 = np.ascontiguousarray(w, dtype=np.float32)
+    assert w2.shape in ((n,), (rows, n))
+    stride = 0 if w2.ndim == 1 else n
+    t2 = None if tangent is None else _as_rows(tangent, dt)
+    out = np.empty((rows, n), dtype=np.float64)
+    jvp = np.empty((rows, n), dtype=np.float64) if t2 is not None else None
+    fn = lib().oracle_topk_general_f64 if f64 else lib().oracle_topk_general
+    rc = fn({"id": 0, "half_sq": 1}[phi], _ptr(x2, cty), _ptr(w2, ctypes.c_float), stride,
+            _ptr(t2, cty), rows, n, p_code(p), float(lam), _ptr(out, ctypes.c_double),
+            _ptr(jvp, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"oracle_topk_general failed: {rc}")
+    res = {"out": out.reshape(np.shape(x))}
+    if jvp is not None:
+        res["jvp"] = jvp.reshape(np.shape(x))
+    return res
 
 
 def value(x, k, p, lam, phi: str = "id") -> np.ndarray:

@@ -217,9 +217,12 @@ inline double hess_rstar(const Problem& P, double t) {
 //              element (lo == hi when every block is a singleton), or nullptr
 //   value    : f_{phi,R}(x, 1_k) itself (Prop. 2, second line: min_u R*(x - u) + f_phi(u, 1_k),
 //              evaluated at u*, i.e. the optimal value of Eq. (isotonic_separable)), or nullptr
+//   weights  : nullptr for w = 1_k, else n non-increasing weights (w_1 >= ... >= w_n), the
+//              general second argument of the operators of Sec. 4 (k is then ignored)
 template <class T>
 void one_row(const Problem& P, const T* x, const T* tangent, int64_t n, int64_t k,
-             double* out, double* jvp, int32_t* perm, int64_t* ab, double* value = nullptr) {
+             double* out, double* jvp, int32_t* perm, int64_t* ab, double* value = nullptr,
+             const double* weights = nullptr) {
   std::vector<int32_t> sigma(n);
   std::vector<T> z(n);
   std::vector<double> s(n), w(n), v(n), sgn(n);
@@ -231,7 +234,7 @@ void one_row(const Problem& P, const T* x, const T* tangent, int64_t n, int64_t 
   argsort_desc(z.data(), n, sigma.data());
   for (int64_t i = 0; i < n; ++i) {
     s[i] = double(z[sigma[i]]);
-    w[i] = (i < k) ? 1.0 : 0.0;                 // w = 1_k, Eq. (topk_mask)
+    w[i] = weights ? weights[i] : ((i < k) ? 1.0 : 0.0);   // w = 1_k, Eq. (topk_mask)
     double xv = double(x[sigma[i]]);
     sgn[i] = even ? double((xv > 0.0) - (xv < 0.0)) : 1.0;   // sign(0) = 0
   }
@@ -358,6 +361,24 @@ int run_masked_value(const T* x, const T* tangent, int64_t rows, int64_t n, int6
   return 0;
 }
 
+// General non-increasing weights (see oracle_topk_general below).
+template <class T>
+int run_general(int phi_code, const T* x, const float* w, int64_t w_stride, const T* tangent,
+                int64_t rows, int64_t n, int p_code, double lambda, double* out, double* jvp) {
+  if (!x || !w || !out || rows < 0 || n < 1) return -1;
+  if (!(lambda > 0.0) || !std::isfinite(lambda)) return -2;
+  if (phi_code < 0 || phi_code > 1 || p_code < 0 || p_code > 1) return -3;
+  if (w_stride != 0 && w_stride != n) return -1;
+  Problem P{Phi(phi_code), Pcode(p_code), lambda};
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t r = 0; r < rows; ++r) {
+    std::vector<double> wd(n);
+    for (int64_t i = 0; i < n; ++i) wd[i] = double(w[r * w_stride + i]);
+    one_row<T>(P, x + r * n, tangent ? tangent + r * n : nullptr, n, 0, out + r * n,
+               (tangent && jvp) ? jvp + r * n : nullptr, nullptr, nullptr, nullptr, wd.data());
+  }
+  return 0;
+}
 }  // namespace
 
 extern "C" {
@@ -418,6 +439,21 @@ int oracle_topk_masked_value_f64(const double* x, const double* tangent, int64_t
                                  int64_t k, int p_code, double lambda, double* out, double* jvp,
                                  int32_t*, int64_t*) {
   return run_masked_value(x, tangent, rows, n, k, p_code, lambda, out, jvp);
+}
+
+// The relaxed operator y_{phi,R}(x, w) of Prop. 2 for a general non-increasing w (soft rank:
+// w = (n, .., 1) on -theta; soft sort: input (n, .., 1), w = sort(theta); partial ranks; Sec. 3
+// "LP formulations" and Sec. 4) and its JVP in x.  w: [n] shared by all rows (w_stride = 0) or
+// [rows][n] (w_stride = n), float32 like the library's input, widened exactly.  phi_code 0 / 1.
+int oracle_topk_general(int phi_code, const float* x, const float* w, int64_t w_stride,
+                        const float* tangent, int64_t rows, int64_t n, int p_code, double lambda,
+                        double* out, double* jvp) {
+  return run_general(phi_code, x, w, w_stride, tangent, rows, n, p_code, lambda, out, jvp);
+}
+int oracle_topk_general_f64(int phi_code, const double* x, const float* w, int64_t w_stride,
+                            const double* tangent, int64_t rows, int64_t n, int p_code,
+                            double lambda, double* out, double* jvp) {
+  return run_general(phi_code, x, w, w_stride, tangent, rows, n, p_code, lambda, out, jvp);
 }
 
 // Sec. 5, Alg. 1: Dykstra's alternating projections for the relaxed top-k mask with p = 2, as an

@@ -202,3 +202,77 @@ def central_diff_jvp(fwd, x, t, h=1e-6):
     x = np.asarray(x, dtype=np.float64)
     t = np.asarray(t, dtype=np.float64)
     return (fwd(x + h * t) - fwd(x - h * t)) / (2.0 * h)
+
+
+# ---------------------------------------------------------------------------------------------
+# General non-increasing w.  phi = identity (Prop. 2, first line): y* = argmax over the
+# permutahedron P(w) of <y, x> - R(y).  P(w) by its inequalities: every subset S of indices has
+# sum_S y_i <= w_1 + .. + w_|S|, with equality for the full set (n <= 5: 31 constraints).
+def general_mask_by_definition(x, w, p, lam):
+    x = np.asarray(x, dtype=np.float64)
+    w = np.sort(np.asarray(w, dtype=np.float64))[::-1]
+    n = x.size
+    cw = np.concatenate([[0.0], np.cumsum(w)])
+
+    def obj(y):
+        return -(y @ x) + lam / p * (np.abs(y) ** p).sum()
+
+    def grad(y):
+        return -x + lam * np.sign(y) * np.abs(y) ** (p - 1)
+
+    cons = [{"type": "eq", "fun": lambda y: y.sum() - cw[n], "jac": lambda y: np.ones(n)}]
+    for m in range(1, n):
+        for S in itertools.combinations(range(n), m):
+            a = np.zeros(n)
+            a[list(S)] = -1.0
+            cons.append({"type": "ineq", "fun": lambda y, a=a, m=m: cw[m] + a @ y,
+                         "jac": lambda y, a=a: a})
+    best = None
+    for start in (np.full(n, cw[n] / n), w[np.argsort(np.argsort(-x))].astype(np.float64)):
+        res = optimize.minimize(obj, start, jac=grad, constraints=cons, method="SLSQP",
+                                options={"ftol": 1e-15, "maxiter": 1000})
+        if best is None or res.fun < best.fun:
+            best = res
+    return best.x
+
+
+# phi = x^2/2 (Prop. 2, second line): u* = argmin_u R*(x - u) + f_phi(u, w) with
+# f_phi(u, w) = max over permutations pi of sum_i w_pi(i) u_i^2 / 2; y* = grad R*(x - u*).
+def general_mag_by_definition(x, w, p, lam):
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    n = x.size
+    q = q_of(p)
+
+    def rstar(t):
+        return (np.abs(t) ** q).sum() / (q * lam ** (q - 1))
+
+    def grad_rstar(t):
+        return np.sign(t) * np.abs(t) ** (q - 1) / lam ** (q - 1)
+
+    def obj(z):
+        return rstar(x - z[:n]) + z[n]
+
+    def obj_grad(z):
+        g = np.zeros(n + 1)
+        g[:n] = -grad_rstar(x - z[:n])
+        g[n] = 1.0
+        return g
+
+    cons = []
+    for perm in itertools.permutations(range(n)):
+        wp = w[list(perm)]
+        cons.append({"type": "ineq", "fun": lambda z, wp=wp: z[n] - 0.5 * (wp * z[:n] ** 2).sum(),
+                     "jac": lambda z, wp=wp: np.concatenate([-wp * z[:n], [1.0]])})
+
+    def f_phi(u):
+        return 0.5 * (w * np.sort(u ** 2)[::-1]).sum()
+
+    best = None
+    for start in (x.copy(), x / (1.0 + lam * w.max()), 0.5 * x):
+        z0 = np.concatenate([start, [f_phi(start) + 1e-3]])
+        res = optimize.minimize(obj, z0, jac=obj_grad, constraints=cons, method="SLSQP",
+                                options={"ftol": 1e-15, "maxiter": 1000})
+        if best is None or res.fun < best.fun:
+            best = res
+    return grad_rstar(x - best.x[:n])

@@ -661,3 +661,72 @@ def test_dykstra_iterations(oracle):
             v = ind.dykstra_mask_p2(s, w, lam, iters=it)
             got = oracle.topk_mask_dykstra(s.astype(np.float32), k, lam, it)
             assert np.abs(got - (s - v) / lam).max() < 1e-13
+
+
+# ----------------------------------------------------------------------------------------------
+# General non-increasing weights (soft rank / soft sort / partial ranks).  phi = identity: the
+# regularised LP over the permutahedron P(w) solved as a constrained program; phi = x^2/2: the
+# definition of Prop. 2 with f_phi(u, w) as a maximum over permutations; w = 1_k reproduces the
+# top-k operators bit for bit; p = 2 is the Euclidean projection of x / lambda onto P(w) computed
+# from the library isotonic regression; the JVP by central differences.
+@pytest.mark.parametrize("p", [P2, P43])
+def test_general_weights_vs_definitions(oracle, p):
+    r = rng(41)
+    for trial in range(20):
+        n = int(r.integers(2, 6))
+        lam = float(r.choice([0.2, 1.0, 3.0]))
+        x = r.normal(size=n).astype(np.float32) * 2
+        w = np.sort(r.choice([0.0, 0.5, 1.0, 2.0, 3.0], size=n))[::-1].astype(np.float32)
+        y = oracle.topk_general(x, w, p, lam, "id")["out"]
+        ref = ind.general_mask_by_definition(x.astype(np.float64), w, p, lam)
+        assert np.abs(y - ref).max() < 1e-4, ("id", x, w, lam, y, ref)
+        if n <= 4:
+            y = oracle.topk_general(x, w, p, lam, "half_sq")["out"]
+            ref = ind.general_mag_by_definition(x.astype(np.float64), w, p, lam)
+            assert np.abs(y - ref).max() < 1e-4, ("half_sq", x, w, lam, y, ref)
+
+
+def test_general_weights_special_cases_and_jvp(oracle):
+    from sklearn.isotonic import isotonic_regression
+    r = rng(42)
+    for _ in range(30):
+        n = int(r.integers(1, 50))
+        k = int(r.integers(0, n + 1))
+        lam = float(r.choice([0.1, 1.0]))
+        x = r.normal(size=(3, n)).astype(np.float32)
+        t = r.normal(size=(3, n)).astype(np.float32)
+        ones_k = (np.arange(n) < k).astype(np.float32)
+        for p in (P2, P43):
+            for phi, fn in (("id", oracle.topk_mask), ("half_sq", oracle.topkmag)):
+                a = oracle.topk_general(x, ones_k, p, lam, phi, tangent=t)
+                b = fn(x, k, p, lam, tangent=t)
+                assert np.array_equal(a["out"], b["out"]) and np.array_equal(a["jvp"], b["jvp"])
+        # soft rank weights: projection onto the permutahedron through isotonic regression
+        rho = np.arange(n, 0, -1).astype(np.float32)
+        y = oracle.topk_general(x[0], rho, P2, lam, "id")["out"]
+        order = np.argsort(-x[0], kind="stable")
+        s = x[0].astype(np.float64)[order]
+        v = isotonic_regression(s - lam * rho.astype(np.float64), increasing=False)
+        ref = np.empty(n)
+        ref[order] = (s - v) / lam
+        assert np.abs(y - ref).max() < 1e-9
+        assert abs(y.sum() - rho.sum()) < 1e-8 * max(1.0, rho.sum())
+    checked = 0
+    for _ in range(300):
+        p = P2 if r.random() < 0.5 else P43
+        phi = "id" if r.random() < 0.5 else "half_sq"
+        n = int(r.integers(2, 16))
+        lam = float(r.choice([0.3, 1.0, 2.0]))
+        x, t = r.normal(size=n) * 2, r.normal(size=n)
+        w = np.sort(r.choice([0.0, 0.5, 1.0, 2.0, 3.0], size=n))[::-1].astype(np.float32)
+        f = lambda z: oracle.topk_general(z, w, p, lam, phi, f64=True)["out"]
+        h = 1e-6
+        # same piece: second differences vanish when no block changes between x - 4ht and x + 4ht
+        a, b, c = f(x - 4 * h * t), f(x), f(x + 4 * h * t)
+        if np.abs(a - 2 * b + c).max() > 1e-9:
+            continue
+        jvp = oracle.topk_general(x, w, p, lam, phi, tangent=t, f64=True)["jvp"]
+        fd = ind.central_diff_jvp(f, x, t, h)
+        assert np.abs(jvp - fd).max() < 3e-6 * max(1.0, np.abs(jvp).max()) / min(1.0, lam)
+        checked += 1
+    assert checked > 100
