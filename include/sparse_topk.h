@@ -66,6 +66,12 @@ enum {
   TOPK_OP_MASKED_VALUE = 6   /* topk_masked_value_fwd and _jvp */
 };
 
+/* phi of topk_general_*: phi(x) = x (mask-like operators) or phi(x) = x^2 / 2 (in magnitude). */
+enum {
+  TOPK_PHI_IDENTITY = 0,
+  TOPK_PHI_HALF_SQUARE = 1
+};
+
 /* Rows up to this length are handled by one wavefront in registers (no workspace needed). */
 #define TOPK_SHORT_ROW_MAX 1024
 
@@ -118,6 +124,26 @@ int topk_mask_vjp(const float* theta, const float* cotangent, int64_t rows, int6
                   double p, double lambda, float* out, float* vjp_out, void* stream);
 int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n, int64_t k,
                 double p, double lambda, float* out, float* vjp_out, void* stream);
+
+/*
+ * The relaxed operators for a general weight vector (Sec. 4: y_{phi,R}(x, w) = grad_1
+ * f_{phi,R}(x, w), Prop. 2; reductions of Prop. 5 / Prop. 6; full PAV partition of App. "PAV
+ * algorithm"; JVP in x by Prop. 7).  With the LP forms of Sec. 3 this gives relaxed ranks
+ * (input -theta, w = (n, .., 1)), relaxed sorts (input (n, .., 1), w = sort(theta), one weight
+ * row per row) and partial ranks; w = 1_k reproduces topk_mask_* / topkmag_*.
+ *   x [rows][n] in.  w: weights by SORTED position, non-increasing (w_1 >= ... >= w_n >= 0; not
+ *   checked, the result is unspecified otherwise): [n] shared by all rows when w_stride == 0,
+ *   [rows][n] when w_stride == n (anything else: TOPK_ERR_INVALID).  phi: a TOPK_PHI_* code.
+ *   out, jvp_out [rows][n] out (out may be NULL in the *_jvp call).
+ *   Rows up to TOPK_SHORT_ROW_MAX elements only (TOPK_ERR_INVALID beyond); no workspace.
+ *   One lane per row walks the block stack, so this entry point is far slower per element than
+ *   the top-k ones.  Other arguments and errors as topk_mask_fwd / topk_mask_jvp.
+ */
+int topk_general_fwd(const float* x, const float* w, int64_t w_stride, int64_t rows, int64_t n,
+                     int phi, double p, double lambda, float* out, void* stream);
+int topk_general_jvp(const float* x, const float* w, int64_t w_stride, const float* tangent,
+                     int64_t rows, int64_t n, int phi, double p, double lambda, float* out,
+                     float* jvp_out, void* stream);
 
 /*
  * Relaxed top-k mask for p = 2 by Dykstra's alternating projection algorithm (Sec. 5, Alg. 1)

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
 
 EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
-    "topk_mask_dykstra_fwd", "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
+    "topk_general_fwd", "topk_general_jvp", "topk_mask_dykstra_fwd", "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
     "topk_mask_loss", "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace",
     "topk_strerror",
 )
@@ -52,6 +52,10 @@ def load() -> ctypes.CDLL:
     for name in ("topk_signed_mask_jvp", "topk_masked_value_jvp"):
         getattr(L, name).argtypes = L.topk_mask_jvp.argtypes
         getattr(L, name).restype = ci
+    L.topk_general_fwd.argtypes = [vp, vp, i64, i64, i64, ci, dbl, dbl, vp, vp]
+    L.topk_general_fwd.restype = ci
+    L.topk_general_jvp.argtypes = [vp, vp, i64, vp, i64, i64, ci, dbl, dbl, vp, vp, vp]
+    L.topk_general_jvp.restype = ci
     L.topk_mask_dykstra_fwd.argtypes = [vp, i64, i64, i64, dbl, ci, vp, vp]
     L.topk_mask_dykstra_fwd.restype = ci
     L.topk_mask_vjp.argtypes = L.topk_mask_jvp.argtypes
@@ -186,6 +190,42 @@ def _abs_variant(name, op, x, tangent, k, p, lam, out, jvp_out, stream):
     _check(getattr(load(), name + "_jvp")(x.data_ptr(), tangent.data_ptr(), rows, n, int(k),
                                           float(p), float(lam), out.data_ptr(), jvp_out.data_ptr(),
                                           _stream(stream)), name + "_jvp")
+    return out, jvp_out
+
+
+TOPK_PHI_IDENTITY, TOPK_PHI_HALF_SQUARE = 0, 1
+
+
+def _weights(w, rows, n):
+    if not isinstance(w, torch.Tensor) or not w.is_cuda or w.dtype != torch.float32 or \
+            not w.is_contiguous() or tuple(w.shape) not in ((n,), (rows, n)):
+        raise TopkError("w must be a contiguous float32 GPU tensor of shape [n] or [rows, n]")
+    return w, (0 if w.dim() == 1 else n)
+
+
+def topk_general_fwd(x, w, phi, p, lam, out=None, stream=None):
+    x = _dev_f32(x, "x")
+    rows, n = x.shape
+    w, stride = _weights(w, rows, n)
+    out = torch.empty_like(x) if out is None else _dev_f32(out, "out")
+    _check(load().topk_general_fwd(x.data_ptr(), w.data_ptr(), stride, rows, n, int(phi), float(p),
+                                   float(lam), out.data_ptr(), _stream(stream)), "topk_general_fwd")
+    return out
+
+
+def topk_general_jvp(x, w, tangent, phi, p, lam, out=None, jvp_out=None, want_out=True, stream=None):
+    """Returns (out, jvp_out); out is None when want_out is False and no out tensor was given."""
+    x = _dev_f32(x, "x")
+    tangent = _dev_f32(tangent, "tangent")
+    rows, n = x.shape
+    w, stride = _weights(w, rows, n)
+    if out is None and want_out:
+        out = torch.empty_like(x)
+    jvp_out = torch.empty_like(x) if jvp_out is None else _dev_f32(jvp_out, "jvp_out")
+    _check(load().topk_general_jvp(x.data_ptr(), w.data_ptr(), stride, tangent.data_ptr(), rows, n,
+                                   int(phi), float(p), float(lam),
+                                   None if out is None else out.data_ptr(), jvp_out.data_ptr(),
+                                   _stream(stream)), "topk_general_jvp")
     return out, jvp_out
 
 

@@ -198,6 +198,37 @@ int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int
 
 extern "C" {
 
+static int run_general(int phi, const float* x, const float* w, int64_t w_stride,
+                       const float* tangent, int64_t rows, int64_t n, double p, double lambda,
+                       float* out, float* jvp, bool need_jvp, void* stream) {
+  const int rc = check_shape(rows, n, 0, lambda);
+  if (rc != TOPK_OK) return rc;
+  if (n > TOPK_SHORT_ROW_MAX || (w_stride != 0 && w_stride != n)) return TOPK_ERR_INVALID;
+  if (phi != TOPK_PHI_IDENTITY && phi != TOPK_PHI_HALF_SQUARE) return TOPK_ERR_INVALID;
+  const int pc = p_code(p);
+  if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
+  if (rows == 0) return TOPK_OK;
+  if (x == nullptr || w == nullptr) return TOPK_ERR_NULL;
+  if (!need_jvp && out == nullptr) return TOPK_ERR_NULL;
+  if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
+  if (topk::launch_general_rows(phi == TOPK_PHI_HALF_SQUARE, pc, x, w, w_stride,
+                                need_jvp ? tangent : nullptr, out, need_jvp ? jvp : nullptr, rows,
+                                int(n), make_reg(lambda), static_cast<hipStream_t>(stream)) != 0)
+    return TOPK_ERR_INVALID;
+  return finish();
+}
+
+int topk_general_fwd(const float* x, const float* w, int64_t w_stride, int64_t rows, int64_t n,
+                     int phi, double p, double lambda, float* out, void* stream) {
+  return run_general(phi, x, w, w_stride, nullptr, rows, n, p, lambda, out, nullptr, false, stream);
+}
+
+int topk_general_jvp(const float* x, const float* w, int64_t w_stride, const float* tangent,
+                     int64_t rows, int64_t n, int phi, double p, double lambda, float* out,
+                     float* jvp_out, void* stream) {
+  return run_general(phi, x, w, w_stride, tangent, rows, n, p, lambda, out, jvp_out, true, stream);
+}
+
 int topk_mask_dykstra_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double lambda,
                           int iters, float* out, void* stream) {
   const int rc = check_shape(rows, n, k, lambda);

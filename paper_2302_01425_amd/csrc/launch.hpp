@@ -118,6 +118,12 @@ int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& 
 int launch_mask_loss(int pc, const float* x, const float* target, float* grad, float* loss,
                      int64_t rows, int64_t n, double lambda, double p, hipStream_t st);
 
+// Relaxed operator for general non-increasing weights w ([n] with w_stride = 0, or one row of
+// weights per row with w_stride = n), n <= 1024; tangent / jvp / out may be null.
+int launch_general_rows(bool mag, int pc, const float* x, const float* w, int64_t w_stride,
+                        const float* tangent, float* out, float* jvp, int64_t rows, int n,
+                        const Reg& R, hipStream_t st);
+
 // Relaxed top-k mask, p = 2, by `iters` iterations of Dykstra's alternating projections (Alg. 1)
 // on the sorted row instead of the exact block search; n <= 1024.
 int launch_short_dykstra(const float* x, float* out, int64_t rows, int n, int k, double lambda,

@@ -224,6 +224,59 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
+# ---- general non-increasing weights (soft rank / soft sort / partial ranks) -------------------------
+@pytest.mark.parametrize("n", [1, 2, 5, 16, 33, 64, 100, 400, 1024])
+def test_general_weights(gpu, oracle, n):
+    r = np.random.default_rng(500 + n)
+    for rows in (1, 37):
+        x = (r.normal(size=(rows, n)) * 2).astype(np.float32)
+        if n >= 4:
+            x[:, 1] = x[:, 0]
+            x[-1] = np.round(x[-1])                       # many ties
+        t = r.normal(size=(rows, n)).astype(np.float32)
+        rho = np.arange(n, 0, -1).astype(np.float32)
+        k = max(1, n // 3)
+        weights = {
+            "ones_k": (np.arange(n) < k).astype(np.float32),
+            "rank": rho,
+            "steps": np.sort(r.choice([0.0, 0.5, 1.0, 2.0, 3.0], size=n))[::-1].astype(np.float32),
+            "partial_rank": np.maximum(rho - (n - k), 0.0).astype(np.float32),
+            "per_row": -np.sort(-(r.normal(size=(rows, n)) ** 2).astype(np.float32), axis=1),
+        }
+        xd, td = dev(x), dev(t)
+        for wname, w in weights.items():
+            wd = dev(w)
+            for phi, phic in (("id", gpu.TOPK_PHI_IDENTITY), ("half_sq", gpu.TOPK_PHI_HALF_SQUARE)):
+                for p in (P2, P43):
+                    lam = float(r.choice([0.1, 1.0, 4.0]))
+                    print(f"case shape={x.shape} w={wname} phi={phi} p={p:.4f} lam={lam}", flush=True)
+                    xin = -x if wname == "rank" else x            # rank = y(-theta, rho), Sec. 3
+                    xin_d = dev(xin)
+                    ref = oracle.topk_general(xin, w, p, lam, phi, tangent=t)
+                    out1 = host(gpu.topk_general_fwd(xin_d, wd, phic, p, lam))
+                    out2, jv = (host(a) for a in gpu.topk_general_jvp(xin_d, wd, td, phic, p, lam))
+                    _, jv_only = gpu.topk_general_jvp(xin_d, wd, td, phic, p, lam, want_out=False)
+                    assert np.array_equal(out1, out2) and np.array_equal(jv, host(jv_only))
+                    close(out1, ref["out"], "general fwd")
+                    close(jv, ref["jvp"], "general jvp")
+        # w = 1_k through the general path agrees with the top-k kernels
+        for phic, fn in ((gpu.TOPK_PHI_IDENTITY, gpu.topk_mask_jvp), (gpu.TOPK_PHI_HALF_SQUARE, gpu.topkmag_jvp)):
+            for p in (P2, P43):
+                a, b = (host(v) for v in gpu.topk_general_jvp(xd, dev(weights["ones_k"]), td, phic, p, 0.5))
+                c, d = (host(v) for v in fn(xd, td, k, p, 0.5))
+                close(a, c, "general vs top-k fwd")
+                close(b, d, "general vs top-k jvp")
+    # soft sort (Sec. 3): input (n, .., 1), weights = the row sorted in descending order
+    theta = r.normal(size=(5, n)).astype(np.float32)
+    ws = -np.sort(-theta, axis=1)
+    if n > 1 and ws.min() < 0:
+        ws = ws - ws.min()                                   # keep the weights non-negative
+    rho_rows = np.tile(np.arange(n, 0, -1).astype(np.float32), (5, 1))
+    ref = oracle.topk_general(rho_rows, ws, P2, 0.3, "id")["out"]
+    got = host(gpu.topk_general_fwd(dev(rho_rows), dev(ws), gpu.TOPK_PHI_IDENTITY, P2, 0.3))
+    close(got, ref, "soft sort")
+
+
 # ---- Dykstra's algorithm with a fixed number of iterations ----------------------------------------
 @pytest.mark.parametrize("n", [1, 2, 3, 16, 63, 64, 100, 400, 1024])
 def test_dykstra_iterations(gpu, oracle, n):
