@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void long_dense_kernel(
   for (int i = 0; i < 8; ++i) {
     const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
     if (e >= n) continue;
-    emit_dense_element<MAG, PC>(ri, x_all[base + e], e, tangent, out, jvp, R);
+    emit_dense_element<MAG, PC>(ri, load_stream(x_all + base + e), e, tangent, out, jvp, R);
   }
 }
 

@@ -436,23 +436,24 @@ __device__ __forceinline__ bool emit_dense_element(const RowInfo& ri, float xv, 
   const bool above = v > ri.hi_incl;
   const bool below = v < ri.lo_incl;
   if (!empty && !above && !below) return false;
+  // dense outputs are written once and the tangent is read once: streaming accesses
   if constexpr (MAG && PC == kP43) {
     float y = 0.0f, d = 0.0f;
     if (above && xv != 0.0f) {
       double g, slope;
       P::above_both(double(v), R, 0.0, &g, &slope);
       y = float(xv < 0.0f ? -g : g);
-      if (jvp != nullptr) d = float(slope * double(tangent[e]));
+      if (jvp != nullptr) d = float(slope * double(load_stream(tangent + e)));
     }
-    if (out != nullptr) out[e] = y;
-    if (jvp != nullptr) jvp[e] = d;
+    if (out != nullptr) store_stream(out + e, y);
+    if (jvp != nullptr) store_stream(jvp + e, d);
   } else {
     const float inv_1pl = float(R.inv_1pl);
-    if (out != nullptr) out[e] = above ? (MAG ? xv * inv_1pl : 1.0f) : 0.0f;
+    if (out != nullptr) store_stream(out + e, above ? (MAG ? xv * inv_1pl : 1.0f) : 0.0f);
     if (jvp != nullptr) {
       float d = 0.0f;
-      if (MAG && above && xv != 0.0f) d = tangent[e] * inv_1pl;
-      jvp[e] = d;
+      if (MAG && above && xv != 0.0f) d = load_stream(tangent + e) * inv_1pl;
+      store_stream(jvp + e, d);
     }
   }
   return true;

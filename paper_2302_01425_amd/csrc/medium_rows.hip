@@ -369,7 +369,7 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
   for (int e0 = threadIdx.x; e0 < n; e0 += 8 * kMT) {
     float v[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = (e0 + i * kMT < n) ? x[e0 + i * kMT] : 0.0f;
+    for (int i = 0; i < 8; ++i) v[i] = (e0 + i * kMT < n) ? load_stream(x + e0 + i * kMT) : 0.0f;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       if (e0 + i * kMT < n)

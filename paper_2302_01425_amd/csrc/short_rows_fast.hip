@@ -267,13 +267,13 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   if (FULL) {
 #pragma unroll
     for (int q = 0; q < E / 4; ++q) {
-      const float4 v = *reinterpret_cast<const float4*>(x + base + e0 + 4 * q);
+      const float4 v = load4_stream(x + base + e0 + 4 * q);
       xin[4 * q] = v.x; xin[4 * q + 1] = v.y; xin[4 * q + 2] = v.z; xin[4 * q + 3] = v.w;
     }
     if (want_jvp) {
 #pragma unroll
       for (int q = 0; q < E / 4; ++q) {
-        const float4 v = *reinterpret_cast<const float4*>(tangent + base + e0 + 4 * q);
+        const float4 v = load4_stream(tangent + base + e0 + 4 * q);
         tin[4 * q] = v.x; tin[4 * q + 1] = v.y; tin[4 * q + 2] = v.z; tin[4 * q + 3] = v.w;
       }
     }
@@ -537,8 +537,8 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
     if (FULL) {
 #pragma unroll
       for (int q = 0; q < E / 4; ++q)
-        *reinterpret_cast<float4*>(out + base + e0 + 4 * q) =
-            make_float4(yv[4 * q], yv[4 * q + 1], yv[4 * q + 2], yv[4 * q + 3]);
+        store4_stream(out + base + e0 + 4 * q,
+                 make_float4(yv[4 * q], yv[4 * q + 1], yv[4 * q + 2], yv[4 * q + 3]));
     } else {
       store_elems<E, VEC>(out, base, e0, n, yv);
     }
@@ -549,8 +549,8 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
     if (FULL) {
 #pragma unroll
       for (int q = 0; q < E / 4; ++q)
-        *reinterpret_cast<float4*>(jvp + base + e0 + 4 * q) =
-            make_float4(jv[4 * q], jv[4 * q + 1], jv[4 * q + 2], jv[4 * q + 3]);
+        store4_stream(jvp + base + e0 + 4 * q,
+                 make_float4(jv[4 * q], jv[4 * q + 1], jv[4 * q + 2], jv[4 * q + 3]));
     } else {
       store_elems<E, VEC>(jvp, base, e0, n, jv);
     }
