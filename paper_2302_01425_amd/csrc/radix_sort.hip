@@ -553,13 +553,24 @@ __global__ __launch_bounds__(kThreads) void select_offsets_kernel(const uint32_t
   __shared__ uint32_t wave_tot[kWaves];
   const int64_t row = blockIdx.x;
   uint32_t carry = 0, above = 0;
-  for (int c = 0; c < tiles; c += kThreads) {
-    const int t = c + threadIdx.x;
-    const uint32_t v = (t < tiles) ? tcnt[row * tiles + t] : 0u;
-    above += (t < tiles) ? tabove[row * tiles + t] : 0u;
+  constexpr int kPer = 16;               // consecutive tiles per thread: all loads in flight at once
+  for (int c = 0; c < tiles; c += kThreads * kPer) {
+    const int t0 = c + threadIdx.x * kPer;
+    uint32_t v[kPer], mine = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      v[i] = (t0 + i < tiles) ? tcnt[row * tiles + t0 + i] : 0u;
+      above += (t0 + i < tiles) ? tabove[row * tiles + t0 + i] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) mine += v[i];
     uint32_t total;
-    const uint32_t ex = block_exclusive_scan(v, wave_tot, &total);
-    if (t < tiles) toff[row * tiles + t] = carry + ex;
+    uint32_t run = carry + block_exclusive_scan(mine, wave_tot, &total);
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      if (t0 + i < tiles) toff[row * tiles + t0 + i] = run;
+      run += v[i];
+    }
     carry += total;
   }
   uint32_t above_all;
