@@ -227,6 +227,11 @@ __device__ __forceinline__ void half_scan(double& v, int t) {
   if constexpr (H >= 8) { const double o = row_shr_f64<4>(v); v = (t >= 4) ? v + o : v; }
 }
 
+// Element offset of the q-th float4 of a lane in a full row: the lanes of a row take consecutive
+// float4s, so every load / store instruction of a row group covers one contiguous span of the row
+// (which elements a lane holds is immaterial to the sort: the index travels in the word).
+#define TOPK_FULL_OFF(q) ((((q) * GL) + lr) * 4)
+
 // VEC: rows are 16-byte aligned and n % 4 == 0 (float4 loads and stores).
 // FULL: additionally n == NP, so there is no padding and no bounds test anywhere.
 // MODE: 0 forward only, 1 JVP only, 2 forward + JVP (compile-time, so no output is tested for at
@@ -267,13 +272,13 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   if (FULL) {
 #pragma unroll
     for (int q = 0; q < E / 4; ++q) {
-      const float4 v = load4_stream(x + base + e0 + 4 * q);
+      const float4 v = load4_stream(x + base + TOPK_FULL_OFF(q));
       xin[4 * q] = v.x; xin[4 * q + 1] = v.y; xin[4 * q + 2] = v.z; xin[4 * q + 3] = v.w;
     }
     if (want_jvp) {
 #pragma unroll
       for (int q = 0; q < E / 4; ++q) {
-        const float4 v = load4_stream(tangent + base + e0 + 4 * q);
+        const float4 v = load4_stream(tangent + base + TOPK_FULL_OFF(q));
         tin[4 * q] = v.x; tin[4 * q + 1] = v.y; tin[4 * q + 2] = v.z; tin[4 * q + 3] = v.w;
       }
     }
@@ -285,21 +290,37 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   if (FULL) {
 #pragma unroll
     for (int r = 0; r < E; ++r)
-      c[r] = (desc_key(MAG ? fabsf(xin[r]) : xin[r]) & ~IM) | uint32_t(e0 + r);
+      c[r] = (desc_key(MAG ? fabsf(xin[r]) : xin[r]) & ~IM) | uint32_t(TOPK_FULL_OFF(r / 4) + (r & 3));
   } else {
     make_words<E, MAG>(xin, e0, n, IM, c);
     // padding reads as NaN so that it never looks out of order next to a real value
 #pragma unroll
     for (int r = 0; r < E; ++r) xin[r] = (e0 + r < n) ? xin[r] : __uint_as_float(0x7fc00000u);
   }
-  lds_store<E>(lx + e0, xin);
+  if (FULL) {
+#pragma unroll
+    for (int q = 0; q < E / 4; ++q)
+      *reinterpret_cast<float4*>(lx + TOPK_FULL_OFF(q)) =
+          make_float4(xin[4 * q], xin[4 * q + 1], xin[4 * q + 2], xin[4 * q + 3]);
+  } else {
+    lds_store<E>(lx + e0, xin);
+  }
   if (want_out) lds_zero<E>(ly + e0);
   if (want_jvp) lds_zero<E>(ld + e0);
   __builtin_amdgcn_wave_barrier();
   TOPK_MARK(1);
   float s[E];
   sort_words<GL, E, MAG>(c, s, lr, lx);
-  if (want_jvp) lds_store<E>(lt + e0, tin);     // staged after the sort: the sort need not wait for it
+  if (want_jvp) {                               // staged after the sort: the sort need not wait for it
+    if (FULL) {
+#pragma unroll
+      for (int q = 0; q < E / 4; ++q)
+        *reinterpret_cast<float4*>(lt + TOPK_FULL_OFF(q)) =
+            make_float4(tin[4 * q], tin[4 * q + 1], tin[4 * q + 2], tin[4 * q + 3]);
+    } else {
+      lds_store<E>(lt + e0, tin);
+    }
+  }
   lds_store<E>(ls + e0, s);
   __builtin_amdgcn_wave_barrier();
   TOPK_MARK(2);
@@ -533,25 +554,23 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   // ---- coalesced stores of the un-sorted rows ---------------------------------------------------
   if (want_out) {
     float yv[E];
-    lds_load<E>(ly + e0, yv);
     if (FULL) {
 #pragma unroll
       for (int q = 0; q < E / 4; ++q)
-        store4_stream(out + base + e0 + 4 * q,
-                 make_float4(yv[4 * q], yv[4 * q + 1], yv[4 * q + 2], yv[4 * q + 3]));
+        store4_stream(out + base + TOPK_FULL_OFF(q), *reinterpret_cast<const float4*>(ly + TOPK_FULL_OFF(q)));
     } else {
+      lds_load<E>(ly + e0, yv);
       store_elems<E, VEC>(out, base, e0, n, yv);
     }
   }
   if (want_jvp) {
     float jv[E];
-    lds_load<E>(ld + e0, jv);
     if (FULL) {
 #pragma unroll
       for (int q = 0; q < E / 4; ++q)
-        store4_stream(jvp + base + e0 + 4 * q,
-                 make_float4(jv[4 * q], jv[4 * q + 1], jv[4 * q + 2], jv[4 * q + 3]));
+        store4_stream(jvp + base + TOPK_FULL_OFF(q), *reinterpret_cast<const float4*>(ld + TOPK_FULL_OFF(q)));
     } else {
+      lds_load<E>(ld + e0, jv);
       store_elems<E, VEC>(jvp, base, e0, n, jv);
     }
   }

@@ -137,7 +137,10 @@ __device__ __forceinline__ double group_exclusive_scan_f64(double tot, int lr) {
 
 // 16-byte loads and stores with the non-temporal hint, for data that is touched once (inputs
 // read once, final outputs): they do not displace cache lines that will be used again, and
-// measured 17 % faster than plain accesses on the 16384 x 64 router workload.
+// measured 17 % faster than plain accesses on the 16384 x 64 router workload (8 elements per
+// lane).  Not for lanes that own 16 consecutive elements: there one cache line is shared by the
+// four accesses of a lane, and the hinted accesses each go to the L2 again (measured twice as
+// slow on 65536 x 256).
 typedef float float4_raw __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 load4_stream(const float* p) {
   const float4_raw v = __builtin_nontemporal_load(reinterpret_cast<const float4_raw*>(p));
@@ -157,7 +160,7 @@ __device__ __forceinline__ void load_elems(const float* __restrict__ p, int64_t 
 #pragma unroll
     for (int c = 0; c < E / 4; ++c) {
       float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (e0 + 4 * c < n) q = load4_stream(p + base + e0 + 4 * c);
+      if (e0 + 4 * c < n) q = *reinterpret_cast<const float4*>(p + base + e0 + 4 * c);
       v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
     }
   } else {
@@ -173,8 +176,8 @@ __device__ __forceinline__ void store_elems(float* __restrict__ p, int64_t base,
 #pragma unroll
     for (int c = 0; c < E / 4; ++c)
       if (e0 + 4 * c < n)
-        store4_stream(p + base + e0 + 4 * c,
-                      make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]));
+        *reinterpret_cast<float4*>(p + base + e0 + 4 * c) =
+            make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
   } else {
 #pragma unroll
     for (int r = 0; r < E; ++r)
