@@ -136,9 +136,17 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
 
   // ---- pool adjacent violators, one lane per row ---------------------------------------------
   if (lr == 0) {
-    int top = 0;
+    // The block on top of the stack is kept in registers (t*), so the first test of every
+    // position needs no LDS read; its copy in LDS is written when the next block is pushed
+    // above it.  The next position's value and weight are read one iteration ahead.
+    int top = 0;                           // blocks in LDS below the register-held top
+    bool have = false;
+    int tlo = 0;
+    double tS1 = 0.0, tW = 0.0, tS2 = 0.0, tS3 = 0.0, tg = 0.0;
+    float s_next = ss[0], w_next = lw[0];
     for (int i = 0; i < n; ++i) {
-      const double si = double(ss[i]), wi = double(lw[i]);
+      const double si = double(s_next), wi = double(w_next);
+      if (i + 1 < n) { s_next = ss[i + 1]; w_next = lw[i + 1]; }
       int lo = i;
       double S1 = si, W = wi, S2 = 0.0, S3 = 0.0, g;
       if (CUBIC) { S2 = si * si; S3 = S2 * si; }
@@ -147,27 +155,31 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
                           : __dsub_rn(S1, __dmul_rn(R.lambda, W));
       else if (!MAG) g = si - R.lambda * cbrt(W);
       else g = (W == 0.0) ? si : block_root<true>(1.0, W, S1, S2, S3, R, 0.0, si);
-      while (top > 0) {
-        const int plo = st_lo[top - 1];
-        const double pg = st_g[top - 1], pS1 = st_s1[top - 1], pW = st_w[top - 1];
+      while (have) {
         bool viol;
         if (!CUBIC) {
-          viol = pg < g;
+          viol = tg < g;
         } else {
-          const double pcnt = double(lo - plo), cnt = double(i + 1 - lo);
-          const bool p_closed = (lo - plo == 1) && (!MAG || pW == 0.0);
+          const double pcnt = double(lo - tlo), cnt = double(i + 1 - lo);
+          const bool p_closed = (lo - tlo == 1) && (!MAG || tW == 0.0);
           const bool t_closed = (i + 1 - lo == 1) && (!MAG || W == 0.0);
-          if (p_closed == t_closed) viol = pg < g;
-          else if (p_closed) viol = block_cubic<MAG>(pg, cnt, W, S1, S2, S3, R) < 0.0;
-          else viol = block_cubic<MAG>(g, pcnt, pW, pS1, st_s2[top - 1], st_s3[top - 1], R) > 0.0;
+          if (p_closed == t_closed) viol = tg < g;
+          else if (p_closed) viol = block_cubic<MAG>(tg, cnt, W, S1, S2, S3, R) < 0.0;
+          else viol = block_cubic<MAG>(g, pcnt, tW, tS1, tS2, tS3, R) > 0.0;
         }
         if (!viol) break;
         // merge the previous block into the current one
-        S1 = __dadd_rn(S1, pS1);
-        W = __dadd_rn(W, pW);
-        if (CUBIC) { S2 += st_s2[top - 1]; S3 += st_s3[top - 1]; }
-        lo = plo;
-        --top;
+        S1 = __dadd_rn(S1, tS1);
+        W = __dadd_rn(W, tW);
+        if (CUBIC) { S2 += tS2; S3 += tS3; }
+        lo = tlo;
+        // the block below becomes the top
+        have = top > 0;
+        if (have) {
+          --top;
+          tlo = st_lo[top]; tS1 = st_s1[top]; tW = st_w[top]; tg = st_g[top];
+          if (CUBIC) { tS2 = st_s2[top]; tS3 = st_s3[top]; }
+        }
         const double cnt = double(i + 1 - lo);
         if (!CUBIC) {
           g = MAG ? __ddiv_rn(S1, __dadd_rn(__dmul_rn(R.lambda, W), cnt))
@@ -178,11 +190,17 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
                   : block_root<false>(cnt, W, S1, S2, S3, R, smin - R.lambda * cbrt(W) - 1e-300, smax);
         }
       }
-      st_lo[top] = lo;
-      st_s1[top] = S1;
-      st_w[top] = W;
-      st_g[top] = g;
-      if (CUBIC) { st_s2[top] = S2; st_s3[top] = S3; }
+      if (have) {                          // spill the old top below the new one
+        st_lo[top] = tlo; st_s1[top] = tS1; st_w[top] = tW; st_g[top] = tg;
+        if (CUBIC) { st_s2[top] = tS2; st_s3[top] = tS3; }
+        ++top;
+      }
+      have = true;
+      tlo = lo; tS1 = S1; tW = W; tS2 = S2; tS3 = S3; tg = g;
+    }
+    if (have) {
+      st_lo[top] = tlo; st_s1[top] = tS1; st_w[top] = tW; st_g[top] = tg;
+      if (CUBIC) { st_s2[top] = tS2; st_s3[top] = tS3; }
       ++top;
     }
     st_lo[top] = n;
