@@ -126,6 +126,21 @@ int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n,
                 double p, double lambda, float* out, float* vjp_out, void* stream);
 
 /*
+ * Relaxed top-k mask in compact form, e.g. for dispatching tokens to the selected experts (Sec. 6,
+ * sparse mixture of experts): the operator's output is exactly zero below the pooled block, so a
+ * row is described by its non-zeros.  Per row, in descending order of theta (ties by ascending
+ * index): idx_out[r][j] = index of the j-th largest entry, val_out[r][j] = its mask value, for
+ * j < min(nnz_out[r], max_nnz); the remaining slots hold -1 / 0.0f.  nnz_out[r] is the number of
+ * non-zeros (k <= nnz <= n for k >= 1); if it exceeds max_nnz the list was cut off.
+ *   theta [rows][n] in; idx_out (int32) and val_out (float) [rows][max_nnz], nnz_out (int32) [rows]
+ *   out.  1 <= max_nnz <= n.  Rows up to TOPK_SHORT_ROW_MAX elements only (TOPK_ERR_INVALID
+ *   beyond); no workspace.  Other arguments and errors as topk_mask_fwd.
+ */
+int topk_mask_sparse_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double p,
+                         double lambda, int64_t max_nnz, int32_t* idx_out, float* val_out,
+                         int32_t* nnz_out, void* stream);
+
+/*
  * The relaxed operators for a general weight vector (Sec. 4: y_{phi,R}(x, w) = grad_1
  * f_{phi,R}(x, w), Prop. 2; reductions of Prop. 5 / Prop. 6; full PAV partition of App. "PAV
  * algorithm"; JVP in x by Prop. 7).  With the LP forms of Sec. 3 this gives relaxed ranks

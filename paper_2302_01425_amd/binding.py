@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
 
 EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
-    "topk_general_fwd", "topk_general_jvp", "topk_mask_dykstra_fwd", "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
+    "topk_mask_sparse_fwd", "topk_general_fwd", "topk_general_jvp", "topk_mask_dykstra_fwd", "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
     "topk_mask_loss", "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace",
     "topk_strerror",
 )
@@ -52,6 +52,8 @@ def load() -> ctypes.CDLL:
     for name in ("topk_signed_mask_jvp", "topk_masked_value_jvp"):
         getattr(L, name).argtypes = L.topk_mask_jvp.argtypes
         getattr(L, name).restype = ci
+    L.topk_mask_sparse_fwd.argtypes = [vp, i64, i64, i64, dbl, dbl, i64, vp, vp, vp, vp]
+    L.topk_mask_sparse_fwd.restype = ci
     L.topk_general_fwd.argtypes = [vp, vp, i64, i64, i64, ci, dbl, dbl, vp, vp]
     L.topk_general_fwd.restype = ci
     L.topk_general_jvp.argtypes = [vp, vp, i64, vp, i64, i64, ci, dbl, dbl, vp, vp, vp]
@@ -191,6 +193,19 @@ def _abs_variant(name, op, x, tangent, k, p, lam, out, jvp_out, stream):
                                           float(p), float(lam), out.data_ptr(), jvp_out.data_ptr(),
                                           _stream(stream)), name + "_jvp")
     return out, jvp_out
+
+
+def topk_mask_sparse_fwd(theta, k, p, lam, max_nnz, stream=None):
+    """Returns (idx [rows, max_nnz] int32, val [rows, max_nnz] float32, nnz [rows] int32)."""
+    theta = _dev_f32(theta, "theta")
+    rows, n = theta.shape
+    idx = torch.empty((rows, int(max_nnz)), dtype=torch.int32, device=theta.device)
+    val = torch.empty((rows, int(max_nnz)), dtype=torch.float32, device=theta.device)
+    nnz = torch.empty((rows,), dtype=torch.int32, device=theta.device)
+    _check(load().topk_mask_sparse_fwd(theta.data_ptr(), rows, n, int(k), float(p), float(lam),
+                                       int(max_nnz), idx.data_ptr(), val.data_ptr(), nnz.data_ptr(),
+                                       _stream(stream)), "topk_mask_sparse_fwd")
+    return idx, val, nnz
 
 
 TOPK_PHI_IDENTITY, TOPK_PHI_HALF_SQUARE = 0, 1

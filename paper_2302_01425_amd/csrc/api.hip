@@ -229,6 +229,24 @@ int topk_general_jvp(const float* x, const float* w, int64_t w_stride, const flo
   return run_general(phi, x, w, w_stride, tangent, rows, n, p, lambda, out, jvp_out, true, stream);
 }
 
+int topk_mask_sparse_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double p,
+                         double lambda, int64_t max_nnz, int32_t* idx_out, float* val_out,
+                         int32_t* nnz_out, void* stream) {
+  const int rc = check_shape(rows, n, k, lambda);
+  if (rc != TOPK_OK) return rc;
+  if (n > TOPK_SHORT_ROW_MAX || max_nnz < 1 || max_nnz > n) return TOPK_ERR_INVALID;
+  const int pc = p_code(p);
+  if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
+  if (rows == 0) return TOPK_OK;
+  if (theta == nullptr || idx_out == nullptr || val_out == nullptr || nnz_out == nullptr)
+    return TOPK_ERR_NULL;
+  const topk::SparseOut sp{idx_out, val_out, nnz_out, int(max_nnz)};
+  if (topk::launch_short_rows_sparse(pc, theta, rows, int(n), int(k), make_reg(lambda), sp,
+                                     static_cast<hipStream_t>(stream)) != 0)
+    return TOPK_ERR_INVALID;
+  return finish();
+}
+
 int topk_mask_dykstra_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double lambda,
                           int iters, float* out, void* stream) {
   const int rc = check_shape(rows, n, k, lambda);

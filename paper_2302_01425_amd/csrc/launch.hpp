@@ -118,6 +118,18 @@ int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& 
 int launch_mask_loss(int pc, const float* x, const float* target, float* grad, float* loss,
                      int64_t rows, int64_t n, double lambda, double p, hipStream_t st);
 
+// Compact output of the relaxed top-k mask of short rows (n <= 1024): per row the non-zeros in
+// descending order of theta, idx / val [rows][max_nnz] (unused slots -1 / 0), nnz [rows] = their
+// number (may exceed max_nnz: the list is then cut off).
+struct SparseOut {
+  int32_t* idx;
+  float* val;
+  int32_t* nnz;
+  int max_nnz;
+};
+int launch_short_rows_sparse(int pc, const float* x, int64_t rows, int n, int k, const Reg& R,
+                             const SparseOut& sp, hipStream_t st);
+
 // Relaxed operator for general non-increasing weights w ([n] with w_stride = 0, or one row of
 // weights per row with w_stride = n), n <= 1024; tangent / jvp / out may be null.
 int launch_general_rows(bool mag, int pc, const float* x, const float* w, int64_t w_stride,

@@ -72,7 +72,7 @@ struct ShortCfg {
 template <int GL, int E, bool MAG, int PC, bool VEC>
 __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_kernel(
     const float* __restrict__ x, const float* __restrict__ tangent, float* __restrict__ out,
-    float* __restrict__ jvp, int64_t rows, int n, int k, Reg R) {
+    float* __restrict__ jvp, int64_t rows, int n, int k, Reg R, SparseOut sp) {
   using P = Pool<MAG, PC>;
   using C = ShortCfg<GL, E>;
   constexpr int NP = C::NP, RPW = C::RPW, RS = C::RS, IDXB = C::IDXB;
@@ -168,7 +168,7 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
   // Positions before the block keep their singleton solution (mask: exactly 1; magnitude:
   // s/(1+lambda) for p = 2, the root of the one-element cubic for p = 4/3); positions after it
   // are exactly 0.
-  if (out != nullptr) {
+  if (out != nullptr || sp.idx != nullptr) {
 #pragma unroll
     for (int r = 0; r < E; ++r) {
       const int pos1 = e0 + r + 1;
@@ -179,8 +179,16 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
       y = (pos1 > b) ? 0.0 : y;
       float yf = float(y);
       if (MAG) yf = (yf == 0.0f) ? 0.0f : ((field[r] & 1u) ? -yf : yf);
-      if (pos1 <= n) ly[MAG ? (field[r] >> 1) : field[r]] = yf;
+      if (out != nullptr && pos1 <= n) ly[MAG ? (field[r] >> 1) : field[r]] = yf;
+      // compact output: the non-zeros are the sorted positions 1..b, in that order
+      if (sp.idx != nullptr && valid && pos1 <= sp.max_nnz) {
+        const bool nz = pos1 <= b;
+        const int64_t o = row * sp.max_nnz + pos1 - 1;
+        sp.idx[o] = nz ? int32_t(MAG ? (field[r] >> 1) : field[r]) : -1;
+        sp.val[o] = nz ? yf : 0.0f;
+      }
     }
+    if (sp.idx != nullptr && valid && lr == 0) sp.nnz[row] = b;
   }
 
   // ---- JVP (Prop. 7): d gamma = weighted block average of the sorted tangent ------------------
@@ -349,20 +357,21 @@ int launch_dykstra_shape(const float* x, float* out, int64_t rows, int n, int k,
 // ---------------------------------------------------------------------------------------------
 template <int GL, int E, bool VEC>
 int launch_shape(bool mag, int pc, const float* x, const float* t, float* out, float* jvp,
-                 int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
+                 int64_t rows, int n, int k, const Reg& R, hipStream_t st,
+                 const SparseOut& sp = SparseOut{nullptr, nullptr, nullptr, 0}) {
   using C = ShortCfg<GL, E>;
   const int64_t waves = (rows + C::RPW - 1) / C::RPW;
   const int64_t blocks = (waves + C::WPB - 1) / C::WPB;
   if (blocks > 0x7fffffffLL) return -1;
   dim3 grid((unsigned)blocks), block(C::WPB * kWave);
   if (!mag && pc == kP2)
-    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP2, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP2, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R, sp);
   else if (!mag && pc == kP43)
-    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP43, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, false, kP43, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R, sp);
   else if (mag && pc == kP2)
-    hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP2, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP2, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R, sp);
   else if (mag && pc == kP43)
-    hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP43, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R);
+    hipLaunchKernelGGL((short_rows_kernel<GL, E, true, kP43, VEC>), grid, block, 0, st, x, t, out, jvp, rows, n, k, R, sp);
   else
     return -1;
   return 0;
@@ -445,6 +454,20 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
     const int rc = launch_short_rows_fast(np, lg, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
     if (rc != -2) return rc;
   }
+  TOPK_SHAPE_TABLE
+#undef CALL
+  return -1;
+}
+
+int launch_short_rows_sparse(int pc, const float* x, int64_t rows, int n, int k, const Reg& R,
+                             const SparseOut& sp, hipStream_t st) {
+  const bool vec = (n % 4 == 0) && aligned16(x);
+  int np = 2;
+  while (np < n) np <<= 1;
+#define CALL(GL, E, V) \
+  launch_shape<GL, E, V>(false, pc, x, nullptr, nullptr, nullptr, rows, n, k, R, st, sp)
+  if (np == 2) return CALL(1, 2, false);
+  const int lg = pick_log_gl(np, rows);
   TOPK_SHAPE_TABLE
 #undef CALL
   return -1;

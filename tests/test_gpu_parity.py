@@ -224,6 +224,33 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
+# ---- compact (index, value) output of the mask ----------------------------------------------------------
+@pytest.mark.parametrize("n", [1, 2, 7, 64, 100, 400, 1024])
+def test_mask_sparse_output(gpu, oracle, n):
+    r = np.random.default_rng(600 + n)
+    for rows in (1, 41):
+        x = r.normal(size=(rows, n)).astype(np.float32)
+        if n >= 4:
+            x[:, 1] = x[:, 0]
+            x[-1] = np.round(x[-1] * 2) / 2
+        xd = dev(x)
+        for p in (P2, P43):
+            for k in sorted({0, 1, max(1, n // 8), n // 2, n}):
+                for lam, cap in ((0.05, n), (1.0, n), (1.0, max(1, min(n, k + 2)))):
+                    print(f"case shape={x.shape} k={k} p={p:.4f} lam={lam} max_nnz={cap}", flush=True)
+                    ref = oracle.topk_mask(x, k, p, lam, want_perm=True)
+                    idx, val, nnz = (host(a) for a in gpu.topk_mask_sparse_fwd(xd, k, p, lam, cap))
+                    dense = host(gpu.topk_mask_fwd(xd, k, p, lam))
+                    for row in range(rows):
+                        b = int((ref["out"][row] != 0.0).sum())
+                        assert nnz[row] == b
+                        m = min(b, cap)
+                        assert np.array_equal(idx[row, :m], ref["perm"][row, :m])
+                        close(val[row, :m], ref["out"][row, ref["perm"][row, :m]], "sparse values")
+                        close(val[row, :m], dense[row, idx[row, :m]], "sparse vs dense")
+                        assert np.all(idx[row, m:] == -1) and np.all(val[row, m:] == 0.0)
+
+
 # ---- general non-increasing weights (soft rank / soft sort / partial ranks) -------------------------
 @pytest.mark.parametrize("n", [1, 2, 5, 16, 33, 64, 100, 400, 1024])
 def test_general_weights(gpu, oracle, n):
