@@ -25,6 +25,10 @@
 namespace topk {
 namespace {
 
+// rows are read once and written once: streaming accesses (each instruction of a row group
+// covers a contiguous span, see load_row)
+constexpr bool kStreamRows = true;
+
 
 // E consecutive floats of a row starting at element e0; VEC: rows are 16-byte aligned and n % 4 == 0
 // ---- argsort only ------------------------------------------------------------------------------
@@ -39,9 +43,9 @@ __global__ __launch_bounds__(256) void short_argsort_kernel(const float* __restr
   const bool valid = row < rows;
   if (!valid) row = rows - 1;
   float v[E];
-  load_elems<E, VEC>(x, row * n, lr * E, n, v);
+  load_row<GL, E, VEC, kStreamRows>(x, row * n, lr, n, v);
   double K[E];
-  make_keys<E, false, IDXB>(v, lr * E, n, K);
+  make_keys_row<GL, E, VEC, false, IDXB>(v, lr, n, K);
   SortRuns<GL, E, NP>::run(K, lr);
   if (!valid) return;
 #pragma unroll
@@ -94,14 +98,14 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
 
   // ---- load, sort ----------------------------------------------------------------------------
   float xin[E];
-  load_elems<E, VEC>(x, base, e0, n, xin);
+  load_row<GL, E, VEC, kStreamRows>(x, base, lr, n, xin);
   if (jvp != nullptr) {
     float tin[E];
-    load_elems<E, VEC>(tangent, base, e0, n, tin);
-    lds_store<E>(lt + e0, tin);
+    load_row<GL, E, VEC, kStreamRows>(tangent, base, lr, n, tin);
+    lds_store_row<GL, E, VEC>(lt, lr, tin);
   }
   double K[E];
-  make_keys<E, MAG, IDXB>(xin, e0, n, K);
+  make_keys_row<GL, E, VEC, MAG, IDXB>(xin, lr, n, K);
   SortRuns<GL, E, NP>::run(K, lr);
 
   float s32[E];
@@ -243,13 +247,13 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void short_rows_ker
   // ---- coalesced stores of the un-sorted rows ---------------------------------------------------
   if (out != nullptr) {
     float yv[E];
-    lds_load<E>(ly + e0, yv);
-    store_elems<E, VEC>(out, base, e0, n, yv);
+    lds_load_row<GL, E, VEC>(ly, lr, yv);
+    store_row<GL, E, VEC, kStreamRows>(out, base, lr, n, yv);
   }
   if (jvp != nullptr) {
     float jv[E];
-    lds_load<E>(lt + e0, jv);
-    store_elems<E, VEC>(jvp, base, e0, n, jv);
+    lds_load_row<GL, E, VEC>(lt, lr, jv);
+    store_row<GL, E, VEC, kStreamRows>(jvp, base, lr, n, jv);
   }
 }
 
@@ -282,9 +286,9 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void dykstra_rows_k
   float* ly = &lds[wv][(lane / GL) * RS];
 
   float xin[E];
-  load_elems<E, VEC>(x, base, e0, n, xin);
+  load_row<GL, E, VEC, kStreamRows>(x, base, lr, n, xin);
   double K[E];
-  make_keys<E, false, IDXB>(xin, e0, n, K);
+  make_keys_row<GL, E, VEC, false, IDXB>(xin, lr, n, K);
   SortRuns<GL, E, NP>::run(K, lr);
 
   double s[E], v[E], pc[E], qc[E];
@@ -338,8 +342,8 @@ __global__ __launch_bounds__((ShortCfg<GL, E>::WPB * kWave)) void dykstra_rows_k
   __builtin_amdgcn_wave_barrier();
   if (!valid) return;
   float yv[E];
-  lds_load<E>(ly + e0, yv);
-  store_elems<E, VEC>(out, base, e0, n, yv);
+  lds_load_row<GL, E, VEC>(ly, lr, yv);
+  store_row<GL, E, VEC, kStreamRows>(out, base, lr, n, yv);
 }
 
 template <int GL, int E, bool VEC>

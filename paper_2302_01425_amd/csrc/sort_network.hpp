@@ -80,6 +80,26 @@ __device__ __forceinline__ void unpack(double c, uint32_t& key, uint32_t& field)
   field = lo & ((1u << IDXB) - 1u);
 }
 
+// the same for a row dealt to the lanes by elem_of<GL, E, VEC>
+template <int GL, int E, bool VEC, bool MAG, int IDXB>
+__device__ __forceinline__ void make_keys_row(const float (&v)[E], int lr, int n, double (&K)[E]) {
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int e = elem_of<GL, E, VEC>(lr, r);
+    uint32_t key = kSentinelKey, field = (1u << IDXB) - 1u;
+    if (e < n) {
+      if (MAG) {
+        field = (uint32_t(e) << 1) | (__float_as_uint(v[r]) >> 31);
+        key = desc_key(fabsf(v[r]));
+      } else {
+        field = uint32_t(e);
+        key = desc_key(v[r]);
+      }
+    }
+    K[r] = pack<IDXB>(key, field);
+  }
+}
+
 template <int E, bool MAG, int IDXB>
 __device__ __forceinline__ void make_keys(const float (&v)[E], int e0, int n, double (&K)[E]) {
 #pragma unroll

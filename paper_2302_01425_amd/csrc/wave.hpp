@@ -138,9 +138,9 @@ __device__ __forceinline__ double group_exclusive_scan_f64(double tot, int lr) {
 // 16-byte loads and stores with the non-temporal hint, for data that is touched once (inputs
 // read once, final outputs): they do not displace cache lines that will be used again, and
 // measured 17 % faster than plain accesses on the 16384 x 64 router workload (8 elements per
-// lane).  Not for lanes that own 16 consecutive elements: there one cache line is shared by the
-// four accesses of a lane, and the hinted accesses each go to the L2 again (measured twice as
-// slow on 65536 x 256).
+// lane).  Not for lanes that own 16 CONSECUTIVE elements (load_elems / store_elems): there one
+// cache line is shared by the four accesses of a lane, and the hinted accesses each go to the L2
+// again (measured twice as slow on 65536 x 256); rows dealt float4 by float4 (load_row) are fine.
 typedef float float4_raw __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 load4_stream(const float* p) {
   const float4_raw v = __builtin_nontemporal_load(reinterpret_cast<const float4_raw*>(p));
@@ -182,6 +182,75 @@ __device__ __forceinline__ void store_elems(float* __restrict__ p, int64_t base,
 #pragma unroll
     for (int r = 0; r < E; ++r)
       if (e0 + r < n) p[base + e0 + r] = v[r];
+  }
+}
+
+// ---- rows dealt to the lanes float4 by float4 ---------------------------------------------------
+// For vectorisable rows (VEC) register r of lane lr holds element ((r/4) * GL + lr) * 4 + r % 4
+// instead of lr * E + r: every load / store instruction of a row group then covers one
+// contiguous span of the row.  Which elements a lane holds is immaterial to the sort, the index
+// travels with the key.  STREAM adds the non-temporal hint.
+template <int GL, int E, bool VEC>
+__device__ __forceinline__ int elem_of(int lr, int r) {
+  if constexpr (VEC) return (((r >> 2) * GL + lr) << 2) + (r & 3);
+  else return lr * E + r;
+}
+template <int GL, int E, bool VEC, bool STREAM>
+__device__ __forceinline__ void load_row(const float* __restrict__ p, int64_t base, int lr, int n,
+                                         float (&v)[E]) {
+  if constexpr (VEC) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c) {
+      const int off = (c * GL + lr) * 4;
+      float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (off < n) q = STREAM ? load4_stream(p + base + off) : *reinterpret_cast<const float4*>(p + base + off);
+      v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
+    }
+  } else {
+    load_elems<E, false>(p, base, lr * E, n, v);
+  }
+}
+template <int GL, int E, bool VEC, bool STREAM>
+__device__ __forceinline__ void store_row(float* __restrict__ p, int64_t base, int lr, int n,
+                                          const float (&v)[E]) {
+  if constexpr (VEC) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c) {
+      const int off = (c * GL + lr) * 4;
+      const float4 q = make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
+      if (off < n) {
+        if (STREAM) store4_stream(p + base + off, q);
+        else *reinterpret_cast<float4*>(p + base + off) = q;
+      }
+    }
+  } else {
+    store_elems<E, false>(p, base, lr * E, n, v);
+  }
+}
+// the same registers to / from a row staged in LDS in original element order
+template <int GL, int E, bool VEC>
+__device__ __forceinline__ void lds_store_row(float* row, int lr, const float (&v)[E]) {
+  if constexpr (VEC) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c)
+      *reinterpret_cast<float4*>(row + (c * GL + lr) * 4) =
+          make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < E; ++r) row[lr * E + r] = v[r];
+  }
+}
+template <int GL, int E, bool VEC>
+__device__ __forceinline__ void lds_load_row(const float* row, int lr, float (&v)[E]) {
+  if constexpr (VEC) {
+#pragma unroll
+    for (int c = 0; c < E / 4; ++c) {
+      const float4 q = *reinterpret_cast<const float4*>(row + (c * GL + lr) * 4);
+      v[4 * c] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < E; ++r) v[r] = row[lr * E + r];
   }
 }
 
