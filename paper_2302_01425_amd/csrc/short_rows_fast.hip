@@ -41,6 +41,12 @@ extern "C" int topk_debug_read_trace(unsigned long long* host_out) {
 namespace topk {
 namespace {
 
+__device__ __forceinline__ uint32_t median3_u32(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // ---- 32-bit sorting network (same mirror-bitonic schedule as the float64 one) ----------------
 template <int GL, int E, int M>
 __device__ __forceinline__ void sort_stage32(uint32_t (&K)[E], int lr) {
@@ -58,15 +64,15 @@ __device__ __forceinline__ void sort_stage32(uint32_t (&K)[E], int lr) {
       }
     }
   } else {
-    const bool low = (lr & top_bit(LM)) == 0;
+    // the lower lane keeps the minimum, the upper one the maximum: both are the median of
+    // (own, other, bound) with bound = 0 resp. 0xffffffff, one instruction instead of min, max
+    // and a select
+    const uint32_t bound = (lr & top_bit(LM)) == 0 ? 0u : 0xffffffffu;
     uint32_t O[E];
 #pragma unroll
     for (int r = 0; r < E; ++r) O[r] = lane_xor<LM>(K[r ^ RM]);
 #pragma unroll
-    for (int r = 0; r < E; ++r) {
-      const uint32_t mn = min(K[r], O[r]), mx = max(K[r], O[r]);
-      K[r] = low ? mn : mx;
-    }
+    for (int r = 0; r < E; ++r) K[r] = median3_u32(K[r], O[r], bound);
   }
 }
 
