@@ -224,6 +224,31 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
+# ---- finite but extreme inputs: huge and tiny magnitudes, denormals, both signs of zero -----------------
+@pytest.mark.parametrize("n", [64, 100, 1000, 5000, 200000])
+def test_extreme_finite_values(gpu, oracle, n):
+    r = np.random.default_rng(700 + n)
+    rows = 3 if n <= 5000 else 1
+    # magnitudes up to 1e12: beyond about 2^52 lambda the oracle's float64 subtraction s - v of a
+    # top-k singleton (v = s - lambda) returns 0 instead of lambda, while the library writes the
+    # exact 1 there
+    expo = r.integers(-40, 12, size=(rows, n)).astype(np.float64)
+    x = (r.normal(size=(rows, n)) * 10.0 ** expo).astype(np.float32)      # includes denormals and zeros
+    x[:, ::7] = 0.0
+    x[:, 1::7] = -0.0
+    x[0, :8] = [3e12, -3e12, 1e-45, -1e-45, 1.0, -1.0, 1e10, 1e-30]
+    t = r.normal(size=(rows, n)).astype(np.float32)
+    for k in (1, max(2, n // 10), n - 1):
+        for p in (P2, P43):
+            # lambda is large against most magnitudes: a long pooled block for the middle k; the
+            # oracle's p = 4/3 pooling is quadratic in the block length, so on the long row p = 4/3
+            # runs only for k = 1 (mask: a short block at the top)
+            if p == P2 or n <= 5000 or k == 1:
+                run_case(gpu, oracle, "mask", x, t, k, p, 0.5, check_perm=(k == 1 and p == P2))
+            if p == P2 or n <= 5000:
+                run_case(gpu, oracle, "mag", x, t, k, p, 0.5, check_perm=False)
+
+
 # ---- compact (index, value) output of the mask ----------------------------------------------------------
 @pytest.mark.parametrize("n", [1, 2, 7, 64, 100, 400, 1024])
 def test_mask_sparse_output(gpu, oracle, n):
