@@ -224,6 +224,55 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
+# ---- the row lengths at which the kernel family changes ---------------------------------------------
+@pytest.mark.parametrize("n", [128, 129, 1024, 1025, 8192, 8193, 131072, 131073])
+def test_kernel_family_boundaries(gpu, oracle, n):
+    r = np.random.default_rng(800 + n)
+    x = r.normal(size=(2, n)).astype(np.float32)
+    x[1, :] = np.round(x[1, :] * 8) / 8
+    t = r.normal(size=(2, n)).astype(np.float32)
+    k = max(1, n // 10)
+    run_case(gpu, oracle, "mask", x, t, k, P2, 0.3, check_perm=(n <= 8193))
+    run_case(gpu, oracle, "mask", x, t, k, P43, 0.05, check_perm=False)
+    run_case(gpu, oracle, "mag", x, t, k, P2, 0.1, check_perm=False)
+    run_case(gpu, oracle, "mag", x[:1], t[:1], k, P43, 0.02, check_perm=False)
+
+
+# ---- arrays that are not 16-byte aligned (no vector loads) -----------------------------------------------
+@pytest.mark.parametrize("rows,n", [(9, 64), (5, 128), (3, 400), (2, 1024), (2, 5000), (1, 150000)])
+def test_unaligned_arrays(gpu, oracle, rows, n):
+    import torch
+    r = np.random.default_rng(900 + n)
+    x = r.normal(size=(rows, n)).astype(np.float32)
+    t = r.normal(size=(rows, n)).astype(np.float32)
+
+    def shifted(a):                     # the same values, 4 bytes past a 16-byte boundary
+        flat = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+        flat[1:] = torch.from_numpy(a.reshape(-1)).cuda()
+        v = flat[1:].view(a.shape)
+        assert v.data_ptr() % 16 == 4 and v.is_contiguous()
+        return v
+
+    xd, td = shifted(x), shifted(t)
+    k = max(1, n // 7)
+    for op, fn, ofn in (("mask", gpu.topk_mask_jvp, oracle.topk_mask), ("mag", gpu.topkmag_jvp, oracle.topkmag)):
+        for p, lam in ((P2, 0.4), (P43, 0.05)):
+            out_buf = shifted(np.zeros_like(x))
+            jvp_buf = shifted(np.zeros_like(x))
+            ref = ofn(x, k, p, lam, tangent=t)
+            out, jv = fn(xd, td, k, p, lam, out=out_buf, jvp_out=jvp_buf)
+            close(host(out), ref["out"], op + " fwd, unaligned")
+            close(host(jv), ref["jvp"], op + " jvp, unaligned")
+    for name, ofn in (("topk_signed_mask", oracle.topk_signed_mask), ("topk_masked_value", oracle.topk_masked_value)):
+        ref = ofn(x, k, P2, 0.4, tangent=t)
+        out, jv = getattr(gpu, name + "_jvp")(xd, td, k, P2, 0.4, out=shifted(np.zeros_like(x)),
+                                              jvp_out=shifted(np.zeros_like(x)))
+        close(host(out), ref["out"], name + " fwd, unaligned")
+        close(host(jv), ref["jvp"], name + " jvp, unaligned")
+    perm = host(gpu.topk_argsort_desc(xd))
+    assert np.array_equal(perm, oracle.argsort_desc(x))
+
+
 # ---- finite but extreme inputs: huge and tiny magnitudes, denormals, both signs of zero -----------------
 @pytest.mark.parametrize("n", [64, 100, 1000, 5000, 200000])
 def test_extreme_finite_values(gpu, oracle, n):
