@@ -547,6 +547,39 @@ def test_determinism_and_streams(gpu):
     assert torch.equal(o1, o2) and torch.equal(j1, j2)
 
 
+@pytest.mark.parametrize("rows,n,op", [(1000, 64, "mask"), (4, 5000, "mask"), (1, 300000, "mag")])
+def test_hip_graph_replays(gpu, rows, n, op):
+    """The calls only enqueue kernels, so they can be captured; every replay, with other work and
+    new input contents in between, must give what the eager call gives on the same contents."""
+    import torch
+    r = np.random.default_rng(1000 + n)
+    k, lam = max(1, n // 10), 0.2
+    fn = gpu.topk_mask_jvp if op == "mask" else gpu.topkmag_jvp
+    xd = torch.empty((rows, n), dtype=torch.float32, device="cuda")
+    td = torch.empty_like(xd)
+    out, jv = torch.empty_like(xd), torch.empty_like(xd)
+    xd.copy_(dev(r.normal(size=(rows, n)).astype(np.float32)))
+    td.copy_(dev(r.normal(size=(rows, n)).astype(np.float32)))
+    fn(xd, td, k, P2, lam)                                  # registers the workspace before the capture
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(graph, stream=st):
+            fn(xd, td, k, P2, lam, out=out, jvp_out=jv, stream=st)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        xd.copy_(dev(r.normal(size=(rows, n)).astype(np.float32)))
+        td.copy_(dev(r.normal(size=(rows, n)).astype(np.float32)))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_o, got_j = out.clone(), jv.clone()
+        ref_o, ref_j = fn(xd, td, k, P2, lam)               # eager, between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(got_o, ref_o) and torch.equal(got_j, ref_j), rep
+
+
 def test_rows_zero_and_errors(gpu):
     import torch
     x = torch.zeros((0, 8), device="cuda")
