@@ -238,6 +238,16 @@ def test_kernel_family_boundaries(gpu, oracle, n):
     run_case(gpu, oracle, "mag", x[:1], t[:1], k, P43, 0.02, check_perm=False)
 
 
+# ---- many rows: grids of 10^4 .. 10^5 workgroups --------------------------------------------------------
+@pytest.mark.parametrize("rows,n,k", [(1 << 21, 8, 2), (300000, 300, 30), (30000, 2048, 200)])
+def test_many_rows(gpu, oracle, rows, n, k):
+    r = np.random.default_rng(1100 + n)
+    x = r.normal(size=(rows, n)).astype(np.float32)
+    t = r.normal(size=(rows, n)).astype(np.float32)
+    run_case(gpu, oracle, "mask", x, t, k, P2, 0.3, check_perm=False)
+    run_case(gpu, oracle, "mag", x, t, k, P43, 0.05, check_perm=False)
+
+
 # ---- arrays that are not 16-byte aligned (no vector loads) -----------------------------------------------
 @pytest.mark.parametrize("rows,n", [(9, 64), (5, 128), (3, 400), (2, 1024), (2, 5000), (1, 150000)])
 def test_unaligned_arrays(gpu, oracle, rows, n):
