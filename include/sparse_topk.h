@@ -133,8 +133,11 @@ int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n,
  * j < min(nnz_out[r], max_nnz); the remaining slots hold -1 / 0.0f.  nnz_out[r] is the number of
  * non-zeros (k <= nnz <= n for k >= 1); if it exceeds max_nnz the list was cut off.
  *   theta [rows][n] in; idx_out (int32) and val_out (float) [rows][max_nnz], nnz_out (int32) [rows]
- *   out.  1 <= max_nnz <= n.  Rows up to TOPK_SHORT_ROW_MAX elements only (TOPK_ERR_INVALID
- *   beyond); no workspace.  Other arguments and errors as topk_mask_fwd.
+ *   out.  1 <= max_nnz <= n.  Rows up to 131072 elements (TOPK_ERR_INVALID beyond).  Rows above
+ *   TOPK_SHORT_ROW_MAX need the workspace of TOPK_OP_MASK_FWD, and their lists are ordered
+ *   differently: first the entries that lie above everything that can pool (value exactly 1), in
+ *   ascending index order, then the remaining non-zeros in descending order of theta.
+ *   Other arguments and errors as topk_mask_fwd.
  */
 int topk_mask_sparse_fwd(const float* theta, int64_t rows, int64_t n, int64_t k, double p,
                          double lambda, int64_t max_nnz, int32_t* idx_out, float* val_out,

@@ -202,6 +202,7 @@ def topk_mask_sparse_fwd(theta, k, p, lam, max_nnz, stream=None):
     idx = torch.empty((rows, int(max_nnz)), dtype=torch.int32, device=theta.device)
     val = torch.empty((rows, int(max_nnz)), dtype=torch.float32, device=theta.device)
     nnz = torch.empty((rows,), dtype=torch.int32, device=theta.device)
+    ensure_workspace(TOPK_OP_MASK_FWD, rows, n, k, p, theta.device)
     _check(load().topk_mask_sparse_fwd(theta.data_ptr(), rows, n, int(k), float(p), float(lam),
                                        int(max_nnz), idx.data_ptr(), val.data_ptr(), nnz.data_ptr(),
                                        _stream(stream)), "topk_mask_sparse_fwd")

@@ -234,13 +234,22 @@ int topk_mask_sparse_fwd(const float* theta, int64_t rows, int64_t n, int64_t k,
                          int32_t* nnz_out, void* stream) {
   const int rc = check_shape(rows, n, k, lambda);
   if (rc != TOPK_OK) return rc;
-  if (n > TOPK_SHORT_ROW_MAX || max_nnz < 1 || max_nnz > n) return TOPK_ERR_INVALID;
+  if (n > topk::kMediumRowMax || max_nnz < 1 || max_nnz > n) return TOPK_ERR_INVALID;
   const int pc = p_code(p);
   if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
   if (rows == 0) return TOPK_OK;
   if (theta == nullptr || idx_out == nullptr || val_out == nullptr || nnz_out == nullptr)
     return TOPK_ERR_NULL;
   const topk::SparseOut sp{idx_out, val_out, nnz_out, int(max_nnz)};
+  if (is_long(n)) {
+    SortBuffers B;
+    const int wrc = carve(rows, n, &B);
+    if (wrc != TOPK_OK) return wrc;
+    if (topk::launch_medium_rows_sparse(pc, B, theta, rows, n, k, make_reg(lambda), sp,
+                                        static_cast<hipStream_t>(stream)) != 0)
+      return TOPK_ERR_INVALID;
+    return finish();
+  }
   if (topk::launch_short_rows_sparse(pc, theta, rows, int(n), int(k), make_reg(lambda), sp,
                                      static_cast<hipStream_t>(stream)) != 0)
     return TOPK_ERR_INVALID;

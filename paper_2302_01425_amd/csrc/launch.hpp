@@ -129,6 +129,10 @@ struct SparseOut {
 };
 int launch_short_rows_sparse(int pc, const float* x, int64_t rows, int n, int k, const Reg& R,
                              const SparseOut& sp, hipStream_t st);
+// the same for rows of 1025 .. kMediumRowMax elements (one-launch kernel; needs the workspace);
+// there the entries above the key window (value 1) come first, in ascending index order
+int launch_medium_rows_sparse(int pc, const SortBuffers& B, const float* x, int64_t rows, int64_t n,
+                              int64_t k, const Reg& R, const SparseOut& sp, hipStream_t st);
 
 // Relaxed operator for general non-increasing weights w ([n] with w_stride = 0, or one row of
 // weights per row with w_stride = n), n <= 1024; tangent / jvp / out may be null.

@@ -236,11 +236,14 @@ __device__ __forceinline__ SortedList sort_candidates(uint32_t* ka, uint32_t* ia
   return SortedList{kin, iin, even ? 0 : 1, false};    // even: an even number of passes was made
 }
 
-template <bool MAG, int PC, int NT>
+// SPARSE (mask only): instead of the dense outputs the row's non-zeros are written as (index,
+// value) lists: first the elements above the key window (value exactly 1) in ascending index
+// order, then the candidates' non-zeros in descending order of theta.
+template <bool MAG, int PC, int NT, bool SPARSE = false>
 __global__ __launch_bounds__(NT) void medium_rows_kernel(
     const float* __restrict__ x_all, const float* __restrict__ tangent_all,
     float* __restrict__ out_all, float* __restrict__ jvp_all, uint32_t* keys_a, uint32_t* idx_a,
-    uint32_t* keys_b, uint32_t* idx_b, int n, int k_row, Reg R) {
+    uint32_t* keys_b, uint32_t* idx_b, int n, int k_row, Reg R, SparseOut sp) {
   constexpr int kMT = NT, kMW = NT / kWave, kCTile = MedCfg<NT>::kCTile;
   __shared__ MedShared<NT> sm;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
@@ -256,6 +259,7 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
 
   TOPK_MED_MARK(0);
   uint32_t cn = 0;
+  uint32_t above_total = 0;              // elements of the row above the key window
   int k = k_row;
   const uint32_t* skeys = ka;
   const uint32_t* sidx = ia;
@@ -303,10 +307,15 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
     // beyond the infinities are clamped, they would decode to NaN)
     const float v_top = float(bound_value(klo)), v_bot = float(bound_value(khi));
     uint32_t above = 0;                    // per wavefront, summed at the end
+    uint32_t above_done = 0;               // SPARSE: elements above the window in earlier tiles
+    int32_t* sp_idx = SPARSE ? sp.idx + int64_t(blockIdx.x) * sp.max_nnz : nullptr;
+    float* sp_val = SPARSE ? sp.val + int64_t(blockIdx.x) * sp.max_nnz : nullptr;
     for (int tile_first = 0; tile_first < n; tile_first += kCTile) {
       uint32_t pos[kCItems];
       float xv[kCItems];
       uint32_t ncand = 0;
+      uint32_t apos[SPARSE ? kCItems : 1];
+      uint32_t nabove = 0;                 // SPARSE: this wavefront's above-elements of the tile
 #pragma unroll
       for (int i = 0; i < kCItems; ++i) {
         const int e = tile_first + w * (kCItems * kWave) + i * kWave + lane;
@@ -319,12 +328,20 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
         const float v = MAG ? fabsf(xv[i]) : xv[i];
         const bool cand = valid && v <= v_top && v >= v_bot;
         const unsigned long long cm = __ballot(cand);
-        above += __popcll(__ballot(valid && v > v_top));
+        const unsigned long long am = __ballot(valid && v > v_top);
+        above += __popcll(am);
+        if (SPARSE) {
+          apos[i] = (valid && v > v_top) ? nabove + __popcll(am & lanemask_lt()) : 0xffffffffu;
+          nabove += __popcll(am);
+        }
         pos[i] = cand ? ncand + __popcll(cm & lanemask_lt()) : 0xffffffffu;
         ncand += __popcll(cm);
       }
       __syncthreads();                     // wave_a of the previous tile has been read
-      if (lane == 0) sm.wave_a[w] = ncand;
+      if (lane == 0) {
+        sm.wave_a[w] = ncand;
+        if (SPARSE) sm.wave_b[w] = nabove;
+      }
       __syncthreads();
       uint32_t before = 0, total = 0;
 #pragma unroll
@@ -332,6 +349,24 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
         const uint32_t t = sm.wave_a[q];
         if (q < w) before += t;
         total += t;
+      }
+      if (SPARSE) {
+        uint32_t abefore = 0, atotal = 0;
+#pragma unroll
+        for (int q = 0; q < kMW; ++q) {
+          const uint32_t t = sm.wave_b[q];
+          if (q < w) abefore += t;
+          atotal += t;
+        }
+#pragma unroll
+        for (int i = 0; i < kCItems; ++i) {
+          const uint32_t o = above_done + abefore + apos[i];
+          if (apos[i] != 0xffffffffu && o < uint32_t(sp.max_nnz)) {
+            sp_idx[o] = tile_first + w * (kCItems * kWave) + i * kWave + lane;
+            sp_val[o] = 1.0f;
+          }
+        }
+        above_done += atotal;
       }
 #pragma unroll
       for (int i = 0; i < kCItems; ++i) {
@@ -344,12 +379,14 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
       }
       cn += total;
     }
+    if (SPARSE) __syncthreads();           // the last tile's wave_b has been read
     if (lane == 0) sm.wave_b[w] = above;
     __syncthreads();
     uint32_t above_all = 0;
 #pragma unroll
     for (int q = 0; q < kMW; ++q) above_all += sm.wave_b[q];
     k = k_row - int(above_all);
+    above_total = above_all;
 
     TOPK_MED_MARK(3);
     // ---- 4. sort the candidates -------------------------------------------------------------------
@@ -366,6 +403,35 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
 
   TOPK_MED_MARK(5);
   // ---- 6. outputs ----------------------------------------------------------------------------------
+  if constexpr (SPARSE) {
+    int32_t* sp_idx = sp.idx + int64_t(blockIdx.x) * sp.max_nnz;
+    float* sp_val = sp.val + int64_t(blockIdx.x) * sp.max_nnz;
+    int64_t nnz;
+    if (k_row >= 1 && k_row < n) {
+      // the candidates' sorted positions 1 .. b follow the elements above the window
+      nnz = int64_t(above_total) + ri.b;
+      for (int64_t pos1 = 1 + threadIdx.x; pos1 <= ri.b; pos1 += kMT) {
+        const int64_t o = int64_t(above_total) + pos1 - 1;
+        if (o >= sp.max_nnz) break;
+        const double v = double(key_to_float(skeys[pos1 - 1])) - ri.center;
+        const double y = pos1 < ri.a ? 1.0 : Pool<false, PC>::y_in_block(v, ri.gamma, R);
+        sp_idx[o] = int32_t(sidx[pos1 - 1]);
+        sp_val[o] = float(y);
+      }
+    } else {
+      nnz = k_row == 0 ? 0 : n;            // k = n: every entry is 1
+      for (int64_t o = threadIdx.x; o < nnz && o < sp.max_nnz; o += kMT) {
+        sp_idx[o] = int32_t(o);
+        sp_val[o] = 1.0f;
+      }
+    }
+    for (int64_t o = nnz + threadIdx.x; o < sp.max_nnz; o += kMT) {
+      sp_idx[o] = -1;
+      sp_val[o] = 0.0f;
+    }
+    if (threadIdx.x == 0) sp.nnz[blockIdx.x] = int32_t(nnz);
+    return;
+  }
   for (int e0 = threadIdx.x; e0 < n; e0 += 8 * kMT) {
     float v[8];
 #pragma unroll
@@ -436,12 +502,26 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(uint32_t* keys_a
 template <bool MAG, int PC>
 void launch(const SortBuffers& B, const float* x, const float* tangent, float* out, float* jvp,
             int64_t rows, int n, int k, const Reg& R, hipStream_t st) {
+  const SparseOut none{nullptr, nullptr, nullptr, 0};
   if (n <= kSmallRowMax)
     hipLaunchKernelGGL((medium_rows_kernel<MAG, PC, 256>), dim3(unsigned(rows)), dim3(256), 0, st, x,
-                       tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R);
+                       tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R, none);
   else
     hipLaunchKernelGGL((medium_rows_kernel<MAG, PC, 1024>), dim3(unsigned(rows)), dim3(1024), 0, st,
-                       x, tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R);
+                       x, tangent, out, jvp, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k, R, none);
+}
+
+template <int PC>
+void launch_sparse(const SortBuffers& B, const float* x, int64_t rows, int n, int k, const Reg& R,
+                   const SparseOut& sp, hipStream_t st) {
+  if (n <= kSmallRowMax)
+    hipLaunchKernelGGL((medium_rows_kernel<false, PC, 256, true>), dim3(unsigned(rows)), dim3(256), 0,
+                       st, x, nullptr, nullptr, nullptr, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n, k,
+                       R, sp);
+  else
+    hipLaunchKernelGGL((medium_rows_kernel<false, PC, 1024, true>), dim3(unsigned(rows)), dim3(1024),
+                       0, st, x, nullptr, nullptr, nullptr, B.keys_a, B.idx_a, B.keys_b, B.idx_b, n,
+                       k, R, sp);
 }
 
 }  // namespace
@@ -454,6 +534,15 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
   else if (!mag && pc == kP43) launch<false, kP43>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
   else if (mag && pc == kP2) launch<true, kP2>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
   else if (mag && pc == kP43) launch<true, kP43>(B, x, tangent, out, jvp, rows, int(n), int(k), R, st);
+  else return -1;
+  return 0;
+}
+
+int launch_medium_rows_sparse(int pc, const SortBuffers& B, const float* x, int64_t rows, int64_t n,
+                              int64_t k, const Reg& R, const SparseOut& sp, hipStream_t st) {
+  if (n > kMediumRowMax || rows > 0x7fffffffLL) return -1;
+  if (pc == kP2) launch_sparse<kP2>(B, x, rows, int(n), int(k), R, sp, st);
+  else if (pc == kP43) launch_sparse<kP43>(B, x, rows, int(n), int(k), R, sp, st);
   else return -1;
   return 0;
 }

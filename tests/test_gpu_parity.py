@@ -335,6 +335,40 @@ def test_mask_sparse_output(gpu, oracle, n):
                         assert np.all(idx[row, m:] == -1) and np.all(val[row, m:] == 0.0)
 
 
+@pytest.mark.parametrize("rows,n", [(3, 1025), (5, 5000), (2, 8193), (64, 32768), (1, 131072)])
+def test_mask_sparse_output_of_longer_rows(gpu, oracle, rows, n):
+    """Rows above 1024 elements: the list holds the same (index, value) pairs as the dense output
+    has non-zeros; entries of value 1 above the key window come first in index order, the rest
+    follows in descending order of theta."""
+    r = np.random.default_rng(650 + n)
+    x = r.normal(size=(rows, n)).astype(np.float32)
+    x[-1] = np.round(x[-1] * 4) / 4
+    xd = dev(x)
+    for p, lam in ((P2, 0.1), (P43, 0.05)):
+        for k in sorted({0, 1, n // 32, n // 3, n}):
+            cap = min(n, max(1, 2 * k + 64))
+            print(f"case shape={x.shape} k={k} p={p:.4f} lam={lam} max_nnz={cap}", flush=True)
+            ref = oracle.topk_mask(x, k, p, lam, want_perm=True)
+            idx, val, nnz = (host(a) for a in gpu.topk_mask_sparse_fwd(xd, k, p, lam, cap))
+            dense = host(gpu.topk_mask_fwd(xd, k, p, lam))
+            for row in range(rows):
+                b = int((ref["out"][row] != 0.0).sum())
+                assert nnz[row] == b, (row, nnz[row], b)
+                m = min(b, cap)
+                got_i, got_v = idx[row, :m], val[row, :m]
+                assert np.all(idx[row, m:] == -1) and np.all(val[row, m:] == 0.0)
+                assert len(np.unique(got_i)) == m and got_i.min(initial=0) >= 0
+                assert np.array_equal(got_v, dense[row, got_i])          # the same values as the dense call
+                close(got_v, ref["out"][row, got_i], "sparse values")
+                ones = int(np.argmax(got_v != 1.0)) if (got_v != 1.0).any() else m
+                if m == b:      # the whole list: exactly the oracle's non-zero set
+                    assert np.array_equal(np.sort(got_i), np.sort(ref["perm"][row, :b]))
+                # after the leading run in index order, descending order of theta
+                tail = got_i[ones:]
+                tv = x[row, tail]
+                assert np.all(tv[:-1] >= tv[1:])
+
+
 # ---- general non-increasing weights (soft rank / soft sort / partial ranks) -------------------------
 @pytest.mark.parametrize("n", [1, 2, 5, 16, 33, 64, 100, 400, 1024])
 def test_general_weights(gpu, oracle, n):
