@@ -195,13 +195,20 @@ def _abs_variant(name, op, x, tangent, k, p, lam, out, jvp_out, stream):
     return out, jvp_out
 
 
-def topk_mask_sparse_fwd(theta, k, p, lam, max_nnz, stream=None):
-    """Returns (idx [rows, max_nnz] int32, val [rows, max_nnz] float32, nnz [rows] int32)."""
+def topk_mask_sparse_fwd(theta, k, p, lam, max_nnz, idx_out=None, val_out=None, nnz_out=None,
+                         stream=None):
+    """Returns (idx [rows, max_nnz] int32, val [rows, max_nnz] float32, nnz [rows] int32); the three
+    tensors may be passed in (contiguous, on the GPU, of those shapes and types)."""
     theta = _dev_f32(theta, "theta")
     rows, n = theta.shape
-    idx = torch.empty((rows, int(max_nnz)), dtype=torch.int32, device=theta.device)
-    val = torch.empty((rows, int(max_nnz)), dtype=torch.float32, device=theta.device)
-    nnz = torch.empty((rows,), dtype=torch.int32, device=theta.device)
+    shape = (rows, int(max_nnz))
+    idx = torch.empty(shape, dtype=torch.int32, device=theta.device) if idx_out is None else idx_out
+    val = torch.empty(shape, dtype=torch.float32, device=theta.device) if val_out is None else val_out
+    nnz = torch.empty((rows,), dtype=torch.int32, device=theta.device) if nnz_out is None else nnz_out
+    for t, dt, sh, name in ((idx, torch.int32, shape, "idx_out"), (val, torch.float32, shape, "val_out"),
+                            (nnz, torch.int32, (rows,), "nnz_out")):
+        if not t.is_cuda or t.dtype != dt or tuple(t.shape) != sh or not t.is_contiguous():
+            raise TopkError(f"{name} must be a contiguous {dt} GPU tensor of shape {sh}")
     ensure_workspace(TOPK_OP_MASK_FWD, rows, n, k, p, theta.device)
     _check(load().topk_mask_sparse_fwd(theta.data_ptr(), rows, n, int(k), float(p), float(lam),
                                        int(max_nnz), idx.data_ptr(), val.data_ptr(), nnz.data_ptr(),

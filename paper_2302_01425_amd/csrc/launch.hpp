@@ -69,6 +69,15 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
                       float* jvp, int64_t rows, int n, int k, const Reg& R, hipStream_t st);
 int launch_short_argsort(const float* x, int32_t* perm, int64_t rows, int n, hipStream_t st);
 
+// Compact output of the relaxed top-k mask: per row the non-zeros, idx / val [rows][max_nnz]
+// (unused slots -1 / 0), nnz [rows] = their number (may exceed max_nnz: the list is then cut off).
+struct SparseOut {
+  int32_t* idx;
+  float* val;
+  int32_t* nnz;
+  int max_nnz;
+};
+
 // Fast variants for padded row lengths np <= 128 with 2^lg lanes per row; return -2 when the
 // (np, lg) shape is not instantiated (the caller then uses the general kernels above).
 int launch_short_rows_fast(int np, int lg, bool vec, bool mag, int pc, const float* x,
@@ -76,6 +85,8 @@ int launch_short_rows_fast(int np, int lg, bool vec, bool mag, int pc, const flo
                            int k, const Reg& R, hipStream_t st);
 int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t* perm,
                               int64_t rows, int n, hipStream_t st);
+int launch_short_rows_fast_sparse(int np, int lg, bool vec, int pc, const float* x, int64_t rows,
+                                  int n, int k, const Reg& R, const SparseOut& sp, hipStream_t st);
 
 // Long rows: segmented radix sort (result in B.keys_a / B.idx_a), then solve + scatter.
 int radix_tiles(int64_t n);
@@ -121,12 +132,6 @@ int launch_mask_loss(int pc, const float* x, const float* target, float* grad, f
 // Compact output of the relaxed top-k mask of short rows (n <= 1024): per row the non-zeros in
 // descending order of theta, idx / val [rows][max_nnz] (unused slots -1 / 0), nnz [rows] = their
 // number (may exceed max_nnz: the list is then cut off).
-struct SparseOut {
-  int32_t* idx;
-  float* val;
-  int32_t* nnz;
-  int max_nnz;
-};
 int launch_short_rows_sparse(int pc, const float* x, int64_t rows, int n, int k, const Reg& R,
                              const SparseOut& sp, hipStream_t st);
 // the same for rows of 1025 .. kMediumRowMax elements (one-launch kernel; needs the workspace);

@@ -472,6 +472,10 @@ int launch_short_rows_sparse(int pc, const float* x, int64_t rows, int n, int k,
   launch_shape<GL, E, V>(false, pc, x, nullptr, nullptr, nullptr, rows, n, k, R, st, sp)
   if (np == 2) return CALL(1, 2, false);
   const int lg = pick_log_gl(np, rows);
+  if (np <= 128 && fast_enabled()) {
+    const int rc = launch_short_rows_fast_sparse(np, lg, vec, pc, x, rows, n, k, R, sp, st);
+    if (rc != -2) return rc;
+  }
   TOPK_SHAPE_TABLE
 #undef CALL
   return -1;

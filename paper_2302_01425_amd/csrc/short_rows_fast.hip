@@ -240,13 +240,13 @@ __device__ __forceinline__ void half_scan(double& v, int t) {
 
 // VEC: rows are 16-byte aligned and n % 4 == 0 (float4 loads and stores).
 // FULL: additionally n == NP, so there is no padding and no bounds test anywhere.
-// MODE: 0 forward only, 1 JVP only, 2 forward + JVP (compile-time, so no output is tested for at
-// run time).
+// MODE: 0 forward only, 1 JVP only, 2 forward + JVP, 3 forward only in compact form (compile-time,
+// so no output is tested for at run time).
 template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE>
 __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast_kernel(
     const float* __restrict__ x, const float* __restrict__ tangent, float* __restrict__ out,
     float* __restrict__ jvp, int64_t rows, int n, int k, Reg R, float inv_lambda32,
-    float inv_1pl32) {
+    float inv_1pl32, SparseOut sp) {
   using P = Pool<MAG, PC>;
   using C = FastCfg<GL, E>;
   constexpr int NP = C::NP, RS = C::RS;
@@ -270,7 +270,8 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   float* ly = &lds[wv][3][roff];         // y, original order, zero-filled
   float* ld = &lds[wv][4][roff];         // dy, original order, zero-filled
   const int nn = FULL ? NP : n;
-  constexpr bool want_out = (MODE != 1), want_jvp = (MODE != 0);
+  constexpr bool kSparse = (MODE == 3);  // forward only, the non-zeros as (index, value) lists
+  constexpr bool want_out = (MODE == 0 || MODE == 2), want_jvp = (MODE == 1 || MODE == 2);
 
   // ---- load, stage, sort ---------------------------------------------------------------------
   TOPK_MARK(0);
@@ -510,11 +511,11 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
     dgamma = (a <= b) ? num * recip(den) : 0.0;
   }
   // outputs of one sorted position; rows that have nothing there write to the padding slot
-  auto emit = [&](bool have, bool in_block, uint32_t w, float sv, float tv) {
+  auto emit = [&](int q, bool have, bool in_block, uint32_t w, float sv, float tv) {
     const uint32_t e = have ? (w & IM) : uint32_t(NP);
     const bool neg = MAG && (w >> 31);
     const float t = ((sv - c32) - g32) * inv_lambda32;       // (s - gamma) / lambda
-    if (want_out) {
+    if (want_out || kSparse) {
       float y;
       if (MAG) {
         const double yd = in_block ? P::y_in_block(double(sv), gamma, R) : double(sv) * R.inv_1pl;
@@ -523,7 +524,13 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
       } else {
         y = in_block ? (CUBIC ? t * t * t : t) : 1.0f;
       }
-      ly[e] = y;
+      if (want_out) ly[e] = y;
+      // compact form: sorted position q of the row is entry q of its list
+      if (kSparse && valid && q < sp.max_nnz) {
+        const int64_t o = row * sp.max_nnz + q;
+        sp.idx[o] = have ? int32_t(w & IM) : -1;
+        sp.val[o] = have ? y : 0.0f;
+      }
     }
     if (want_jvp) {
       const double diff = double(tv) - dgamma;
@@ -535,7 +542,7 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
       ld[e] = dy;
     }
   };
-  emit(have0, blk0, w0, s0, t0);
+  emit(lr, have0, blk0, w0, s0, t0);
   if (more) {
     for (int q = lr + GL; __any(q < b); q += GL) {
       const bool have = q < b;
@@ -550,8 +557,18 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
           tv = (sv == 0.0f) ? 0.0f : tv;
         }
       }
-      emit(have, have & (q + 1 >= a), w, sv, tv);
+      emit(q, have, have & (q + 1 >= a), w, sv, tv);
     }
+  }
+  if (kSparse && valid) {
+    // slots after the non-zeros that no pass reached, and the count
+    for (int q = lr + GL; q < sp.max_nnz; q += GL) {
+      if (q >= b) {
+        sp.idx[row * sp.max_nnz + q] = -1;
+        sp.val[row * sp.max_nnz + q] = 0.0f;
+      }
+    }
+    if (lr == 0) sp.nnz[row] = b;
   }
   __builtin_amdgcn_wave_barrier();
   TOPK_MARK(4);
@@ -585,7 +602,8 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
 
 template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE>
 int launch_fast_mode(const float* x, const float* t, float* out, float* jvp, int64_t rows, int n,
-                     int k, const Reg& R, hipStream_t st) {
+                     int k, const Reg& R, hipStream_t st,
+                     const SparseOut& sp = SparseOut{nullptr, nullptr, nullptr, 0}) {
   using C = FastCfg<GL, E>;
   const int64_t waves = (rows + C::RPW - 1) / C::RPW;
   const int64_t blocks = (waves + C::WPB - 1) / C::WPB;
@@ -593,7 +611,7 @@ int launch_fast_mode(const float* x, const float* t, float* out, float* jvp, int
   dim3 grid((unsigned)blocks), block(C::WPB * kWave);
   const float il = float(R.inv_lambda), i1 = float(R.inv_1pl);
   hipLaunchKernelGGL((short_rows_fast_kernel<GL, E, MAG, PC, VEC, FULL, MODE>), grid, block, 0, st,
-                     x, t, out, jvp, rows, n, k, R, il, i1);
+                     x, t, out, jvp, rows, n, k, R, il, i1, sp);
   return 0;
 }
 
@@ -657,6 +675,27 @@ int launch_short_rows_fast(int np, int lg, bool vec, bool mag, int pc, const flo
                            const float* tangent, float* out, float* jvp, int64_t rows, int n,
                            int k, const Reg& R, hipStream_t st) {
 #define CALL(GL, E, V) launch_fast_shape<GL, E, V>(mag, pc, x, tangent, out, jvp, rows, n, k, R, st)
+  TOPK_FAST_TABLE
+#undef CALL
+  return -2;
+}
+
+// compact output of the mask (mode 3)
+template <int GL, int E, bool VEC>
+int launch_fast_sparse_shape(int pc, const float* x, int64_t rows, int n, int k, const Reg& R,
+                             const SparseOut& sp, hipStream_t st) {
+  if (VEC && n == GL * E) {
+    if (pc == kP2) return launch_fast_mode<GL, E, false, kP2, true, true, 3>(x, nullptr, nullptr, nullptr, rows, n, k, R, st, sp);
+    return launch_fast_mode<GL, E, false, kP43, true, true, 3>(x, nullptr, nullptr, nullptr, rows, n, k, R, st, sp);
+  }
+  if (pc == kP2) return launch_fast_mode<GL, E, false, kP2, VEC, false, 3>(x, nullptr, nullptr, nullptr, rows, n, k, R, st, sp);
+  return launch_fast_mode<GL, E, false, kP43, VEC, false, 3>(x, nullptr, nullptr, nullptr, rows, n, k, R, st, sp);
+}
+
+int launch_short_rows_fast_sparse(int np, int lg, bool vec, int pc, const float* x, int64_t rows,
+                                  int n, int k, const Reg& R, const SparseOut& sp, hipStream_t st) {
+  if (pc != kP2 && pc != kP43) return -2;
+#define CALL(GL, E, V) launch_fast_sparse_shape<GL, E, V>(pc, x, rows, n, k, R, sp, st)
   TOPK_FAST_TABLE
 #undef CALL
   return -2;
