@@ -31,8 +31,8 @@ METRIC = "rows/s and GB/s (% HBM peak) for topkmask fwd+JVP, 16384x64 k=2 p=2"
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="moe_router")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph",
                     help="graph: the K launches are captured once in a HIP graph and replayed; "
@@ -50,6 +50,8 @@ def parse():
                     help="instead of the one JSON line: time the mask forward + JVP over row lengths "
                          "64 .. 2^24 at a constant 2^24 elements, k = ceil(n/10) (the paper's timing "
                          "sweep uses k = ceil(n/10)), lambda = 0.1, one JSON line per row length")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the timing of the other four workloads (key `workloads`)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=4.0)
     return ap.parse_args()
@@ -99,8 +101,12 @@ class Runner:
         if rc != 0:
             raise RuntimeError(f"library call failed: {rc}")
 
-    def timed(self, steps, warmup, mode, rotate):
-        """Returns milliseconds for exactly `steps` steps (HIP events on the launch stream)."""
+    def timed(self, steps, warmup, mode, rotate, min_ms=20.0):
+        """Times `steps` steps with HIP events on the launch stream and returns (milliseconds per
+        step, repeats).  The K steps (one captured graph, or K plain launches) are repeated R times
+        between the two events, R chosen from one untimed pass so that the timed region lasts at
+        least `min_ms`: the one-off cost of starting a graph or a launch burst is then spread over
+        R * K steps and the figure does not depend on K."""
         torch = self.torch
         nsets = len(self.args) if rotate else 1
         stream = torch.cuda.Stream()
@@ -118,17 +124,27 @@ class Runner:
                         self.launch(i % nsets, sp)
                 graph.replay()                      # one untimed replay (upload, page-in)
                 stream.synchronize()
+
+            def one_pass():
+                if graph is not None:
+                    graph.replay()
+                else:
+                    for i in range(steps):
+                        self.launch(i % nsets, sp)
+
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record(stream)
-            if graph is not None:
-                graph.replay()
-            else:
-                for i in range(steps):
-                    self.launch(i % nsets, sp)
+            one_pass()
             e1.record(stream)
             torch.cuda.synchronize()
-        return e0.elapsed_time(e1)
+            repeats = max(1, min(2000, int(-(-min_ms // max(e0.elapsed_time(e1), 1e-3)))))
+            e0.record(stream)
+            for _ in range(repeats):
+                one_pass()
+            e1.record(stream)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (repeats * steps), repeats
 
 
 def cpu_baseline(w, seconds):
@@ -177,7 +193,7 @@ def sweep(a):
             sets = max(2, -(-a.cold_mib * (1 << 20) // set_bytes))
             r = Runner(w, sets, "cuda:0")
             steps = max(10, min(200, int(2e5 / max(50.0, 1e-6 * total))))
-            ms = r.timed(steps, 5, a.mode, rotate=True) / steps
+            ms, _ = r.timed(steps, 5, a.mode, rotate=True)
             print(json.dumps({"sweep": "mask fwd+JVP, 2^24 elements, k = ceil(n/10), lambda = 0.1",
                               "p": round(p, 4), "n": n, "rows": rows, "us_per_step": ms * 1e3,
                               "gbps": BYTES_PER_ELEMENT * total / (ms * 1e-3) / 1e9,
@@ -241,6 +257,38 @@ def sweep_solvers(a):
         torch.cuda.empty_cache()
 
 
+def other_workloads(a, traffic_table):
+    """The other four configurations, each timed like the headline one (cold, same launch mode):
+    per workload the time of a step, the rate of algorithmic bytes (16 B per element) and its
+    fraction of the HBM peak; for the two long-row workloads also the fraction against a byte model
+    that includes a whole-row 4-pass LSD radix sort through HBM (16 + 4 + 4 x 16 B per element),
+    which is what sorting the rows completely would move."""
+    import torch
+    from paper_2302_01425_amd.workloads import WORKLOADS
+    res = {}
+    for name in ("tiny", "moe_router_smooth", "expert_choice", "magnitude_pruning"):
+        w = WORKLOADS[name]
+        elems = w.rows * w.n
+        set_bytes = 4 * 4 * elems
+        sets = max(2, -(-a.cold_mib * (1 << 20) // set_bytes))
+        sets = min(sets, 64)                              # tiny: 64 sets are plenty of launches
+        r = Runner(w, sets, "cuda:0")
+        steps = max(2, min(a.steps, int(2e8 // elems) or 2))
+        ms, reps = r.timed(steps, min(a.warmup, 5), a.mode, rotate=True)
+        del r
+        torch.cuda.empty_cache()
+        gbps = BYTES_PER_ELEMENT * elems / (ms * 1e-3) / 1e9
+        e = {"ms_per_step": ms, "steps": steps, "repeats": reps, "rows_per_s": w.rows / (ms * 1e-3),
+             "gbps": gbps, "frac": gbps / HBM_PEAK_GBPS}
+        if w.n > 1024:
+            e["frac_sort_inclusive_model"] = (16 + 4 + 4 * 16) * elems / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
+        t = traffic_table.get(name)
+        if t:
+            e["traffic"] = t["total_bytes"]
+        res[name] = e
+    return res
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -266,26 +314,27 @@ def main():
     r = Runner(w, sets, "cuda:0")
     if a.copy_calibration:
         r.enable_copy_mode()
-        ms = r.timed(a.steps, a.warmup, a.mode, rotate=True)
+        ms, reps = r.timed(a.steps, a.warmup, a.mode, rotate=True)
         print(json.dumps({"calibration": "plain copy", "bytes_read_per_step": algo_bytes // 2,
                           "bytes_written_per_step": algo_bytes // 2, "steps": a.steps,
-                          "ms_per_step": ms / a.steps,
-                          "gbps": algo_bytes / (ms / a.steps * 1e-3) / 1e9}))
+                          "repeats": reps, "ms_per_step": ms,
+                          "gbps": algo_bytes / (ms * 1e-3) / 1e9}))
         return
 
-    ms_cold = r.timed(a.steps, a.warmup, a.mode, rotate=True)
-    ms_warm = r.timed(a.steps, a.warmup, a.mode, rotate=False) if a.regime == "both" else ms_cold
+    per_cold, reps = r.timed(a.steps, a.warmup, a.mode, rotate=True)
+    per_warm = r.timed(a.steps, a.warmup, a.mode, rotate=False)[0] if a.regime == "both" else per_cold
+    del r
+    torch.cuda.empty_cache()
 
-    per_cold = ms_cold / a.steps
-    per_warm = ms_warm / a.steps
     gbps_cold = algo_bytes / (per_cold * 1e-3) / 1e9
     gbps_warm = algo_bytes / (per_warm * 1e-3) / 1e9
-    traffic = None
+    traffic_table = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            entry = json.load(f).get(a.workload)
-            traffic = entry["total_bytes"] if entry else None    # HBM bytes per launch (rocprofv3)
+            traffic_table = json.load(f)
+    entry = traffic_table.get(a.workload)
+    traffic = entry["total_bytes"] if entry else None    # HBM bytes per launch (rocprofv3)
 
     line = {
         "metric": METRIC if a.workload == "moe_router" else f"rows/s for {w.op} fwd+JVP, {a.workload}",
@@ -294,6 +343,7 @@ def main():
         "n_gpus": 1,
         "steps": a.steps,
         "warmup": a.warmup,
+        "repeats": reps,
         "ms_per_step": per_cold,
         "higher_is_better": True,
         "scaling": "weak",
@@ -305,6 +355,7 @@ def main():
                         f"lambda={w.lam}, {w.op} forward + JVP fused, fp32 in/out",
             "regime": f"cold: {sets} rotating buffer sets, {sets * set_bytes >> 20} MiB",
             "launch": a.mode,
+            "timed_region": f"{reps} x {a.steps} steps between one pair of HIP events",
             "solve_arithmetic": "f64",
         },
         "elements_per_s": w.rows * w.n / (per_cold * 1e-3),
@@ -318,6 +369,8 @@ def main():
             "algorithmic_bytes_per_launch": algo_bytes,
         },
     }
+    if a.workload == "moe_router" and not a.headline_only:
+        line["workloads"] = other_workloads(a, traffic_table)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds)
     print(json.dumps(line))

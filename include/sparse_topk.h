@@ -219,7 +219,12 @@ int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_
 
 /*
  * The sorting permutation itself (Sec. 3, argsort): perm_out[r][i] = original index of the i-th
- * largest value of row r (0-based).  This is the permutation the operators above use.
+ * largest value of row r (0-based), ties by ascending index, -0 equal to +0.  For rows of up to
+ * TOPK_SHORT_ROW_MAX elements this is the permutation the operators above build in registers.
+ * Longer rows are sorted completely here (segmented radix sort through the workspace of
+ * TOPK_OP_ARGSORT), whereas the operators only order the part of such a row that can pool (the
+ * elements inside a value window around positions k and k+1, in this same order); their outputs
+ * do not depend on the order of the rest.
  */
 int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm_out, void* stream);
 
@@ -236,6 +241,29 @@ size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p
  * TOPK_ERR_INVALID (misaligned pointer, or NULL with bytes != 0).
  */
 int topk_set_workspace(void* dev_ptr, size_t bytes);
+
+/*
+ * Test and tuning control: chooses among code paths that compute the same results (the GPU tests
+ * compare them bit for bit).  Process-wide, takes effect for later calls; not meant for production
+ * callers, whose default is always TOPK_*_AUTO.
+ *   TOPK_ROUTE_LONG_ROWS        how rows above TOPK_SHORT_ROW_MAX elements are handled:
+ *                               TOPK_LONG_ROWS_AUTO (by shape), _SELECT (the multi-launch candidate
+ *                               selection for every such row), _SORT (rows sorted completely)
+ *   TOPK_ROUTE_SHORT_ROW_LANES  lanes of a wavefront that share a short row: 0 (by shape) or a
+ *                               power of two up to 64 (clamped to what the row length allows)
+ *   TOPK_ROUTE_SHORT_ROW_KERNEL TOPK_SHORT_ROW_KERNEL_AUTO, or _GENERAL: the general short-row
+ *                               kernel also for rows of up to 128 elements
+ * Returns TOPK_OK or TOPK_ERR_INVALID (unknown control or value).
+ */
+#define TOPK_ROUTE_LONG_ROWS 0
+#define TOPK_ROUTE_SHORT_ROW_LANES 1
+#define TOPK_ROUTE_SHORT_ROW_KERNEL 2
+#define TOPK_LONG_ROWS_AUTO 0
+#define TOPK_LONG_ROWS_SELECT 1
+#define TOPK_LONG_ROWS_SORT 2
+#define TOPK_SHORT_ROW_KERNEL_AUTO 0
+#define TOPK_SHORT_ROW_KERNEL_GENERAL 2
+int topk_set_route(int which, int value);
 
 /* Static, human-readable text for a return code. */
 const char* topk_strerror(int code);

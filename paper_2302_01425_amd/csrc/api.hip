@@ -46,16 +46,12 @@ Reg make_reg(double lambda) {
 bool is_long(int64_t n) { return n > TOPK_SHORT_ROW_MAX; }
 
 // How rows above TOPK_SHORT_ROW_MAX are handled.  Default: one fused launch up to
-// topk::kMediumRowMax elements, candidate selection + sort of the candidates above.
-// TOPK_LONG_ROWS=select uses the multi-launch selection path for every such row, =sort sorts
-// the rows completely (same results; for tests and comparisons).
-enum LongMode { kAuto, kSelect, kFullSort };
-LongMode long_mode() {
-  const char* e = std::getenv("TOPK_LONG_ROWS");
-  if (e != nullptr && std::strcmp(e, "sort") == 0) return kFullSort;
-  if (e != nullptr && std::strcmp(e, "select") == 0) return kSelect;
-  return kAuto;
-}
+// topk::kMediumRowMax elements, candidate selection + sort of the candidates above.  Through
+// topk_set_route the multi-launch selection path can be chosen for every such row, or a complete
+// sort of the rows (same results; for tests and comparisons).
+enum LongMode { kAuto = TOPK_LONG_ROWS_AUTO, kSelect = TOPK_LONG_ROWS_SELECT,
+                kFullSort = TOPK_LONG_ROWS_SORT };
+LongMode long_mode() { return static_cast<LongMode>(topk::routes().long_rows); }
 
 struct Layout {
   size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, hpart, bins, tile_hist2, bins2, tcnt, tabove, toff, sel, total;
@@ -109,11 +105,16 @@ int carve(int64_t rows, int64_t n, SortBuffers* B, size_t skip = 0) {
 }
 
 int check_shape(int64_t rows, int64_t n, int64_t k, double lambda) {
-  if (rows < 0 || n < 1 || n >= (int64_t(1) << 30) || k < 0 || k > n) return TOPK_ERR_INVALID;
+  if (rows < 0 || rows >= (int64_t(1) << 31) || n < 1 || n >= (int64_t(1) << 30) || k < 0 || k > n)
+    return TOPK_ERR_INVALID;
   if (!(lambda > 0.0) || !std::isfinite(lambda)) return TOPK_ERR_INVALID;
   return TOPK_OK;
 }
 
+// Launch errors are read from the runtime's last-error slot: begin() empties it after the
+// arguments have been validated and before the first launch (an error left there by an earlier,
+// unrelated call would otherwise be reported as this call's), finish() reads it after the last.
+void begin() { (void)hipGetLastError(); }
 int finish() { return hipGetLastError() == hipSuccess ? TOPK_OK : TOPK_ERR_LAUNCH; }
 
 // shared body of the four operator entry points
@@ -130,15 +131,18 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const Reg R = make_reg(lambda);
+  SortBuffers B;
+  if (is_long(n)) {
+    rc = carve(rows, n, &B, ws_skip);
+    if (rc != TOPK_OK) return rc;
+  }
+  begin();
   if (!is_long(n)) {
     if (topk::launch_short_rows(mag, pc, x, need_jvp ? tangent : nullptr, out,
                                 need_jvp ? jvp : nullptr, rows, int(n), int(k), R, st) != 0)
       return TOPK_ERR_INVALID;
     return finish();
   }
-  SortBuffers B;
-  rc = carve(rows, n, &B, ws_skip);
-  if (rc != TOPK_OK) return rc;
   const LongMode mode = long_mode();
   if (mode == kAuto && n <= topk::kMediumRowMax) {
     if (topk::launch_medium_rows(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
@@ -177,14 +181,18 @@ int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int
   if (rows == 0) return TOPK_OK;
   if (x == nullptr || out == nullptr) return TOPK_ERR_NULL;
   if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
+  // the whole workspace is checked before the first launch: two arrays here, then the mask's own
   const size_t skip = abs_scratch_bytes(rows, n);
-  if (g_ws.ptr == nullptr || g_ws.bytes < skip) return TOPK_ERR_WORKSPACE;
+  const size_t need = skip + (is_long(n) ? layout_for(rows, n).total : 0);
+  if (g_ws.ptr == nullptr || g_ws.bytes < need) return TOPK_ERR_WORKSPACE;
+  begin();
   float* ax = static_cast<float*>(g_ws.ptr);
   float* st = reinterpret_cast<float*>(static_cast<char*>(g_ws.ptr) + skip / 2);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t count = rows * n;
   if (topk::launch_abs_prepare(x, need_jvp ? tangent : nullptr, ax, st, count, s) != 0)
     return TOPK_ERR_INVALID;
+  if (hipGetLastError() != hipSuccess) return TOPK_ERR_LAUNCH;
   rc = run_operator(false, ax, need_jvp ? st : nullptr, rows, n, k, p, lambda, out,
                     need_jvp ? jvp : nullptr, true, need_jvp, stream, skip);
   if (rc != TOPK_OK) return rc;
@@ -196,7 +204,35 @@ int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int
 
 }  // namespace
 
+namespace topk {
+Routes& routes() {
+  static Routes r;
+  return r;
+}
+}  // namespace topk
+
 extern "C" {
+
+int topk_set_route(int which, int value) {
+  topk::Routes& r = topk::routes();
+  switch (which) {
+    case TOPK_ROUTE_LONG_ROWS:
+      if (value < TOPK_LONG_ROWS_AUTO || value > TOPK_LONG_ROWS_SORT) return TOPK_ERR_INVALID;
+      r.long_rows = value;
+      return TOPK_OK;
+    case TOPK_ROUTE_SHORT_ROW_LANES:
+      if (value < 0 || value > 64 || (value & (value - 1)) != 0) return TOPK_ERR_INVALID;
+      r.short_lanes = value;
+      return TOPK_OK;
+    case TOPK_ROUTE_SHORT_ROW_KERNEL:
+      if (value < TOPK_SHORT_ROW_KERNEL_AUTO || value > TOPK_SHORT_ROW_KERNEL_GENERAL)
+        return TOPK_ERR_INVALID;
+      r.short_kernel = value;
+      return TOPK_OK;
+    default:
+      return TOPK_ERR_INVALID;
+  }
+}
 
 static int run_general(int phi, const float* x, const float* w, int64_t w_stride,
                        const float* tangent, int64_t rows, int64_t n, double p, double lambda,
@@ -211,6 +247,7 @@ static int run_general(int phi, const float* x, const float* w, int64_t w_stride
   if (x == nullptr || w == nullptr) return TOPK_ERR_NULL;
   if (!need_jvp && out == nullptr) return TOPK_ERR_NULL;
   if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
+  begin();
   if (topk::launch_general_rows(phi == TOPK_PHI_HALF_SQUARE, pc, x, w, w_stride,
                                 need_jvp ? tangent : nullptr, out, need_jvp ? jvp : nullptr, rows,
                                 int(n), make_reg(lambda), static_cast<hipStream_t>(stream)) != 0)
@@ -245,11 +282,13 @@ int topk_mask_sparse_fwd(const float* theta, int64_t rows, int64_t n, int64_t k,
     SortBuffers B;
     const int wrc = carve(rows, n, &B);
     if (wrc != TOPK_OK) return wrc;
+    begin();
     if (topk::launch_medium_rows_sparse(pc, B, theta, rows, n, k, make_reg(lambda), sp,
                                         static_cast<hipStream_t>(stream)) != 0)
       return TOPK_ERR_INVALID;
     return finish();
   }
+  begin();
   if (topk::launch_short_rows_sparse(pc, theta, rows, int(n), int(k), make_reg(lambda), sp,
                                      static_cast<hipStream_t>(stream)) != 0)
     return TOPK_ERR_INVALID;
@@ -263,6 +302,7 @@ int topk_mask_dykstra_fwd(const float* theta, int64_t rows, int64_t n, int64_t k
   if (iters < 0 || n > TOPK_SHORT_ROW_MAX) return TOPK_ERR_INVALID;
   if (rows == 0) return TOPK_OK;
   if (theta == nullptr || out == nullptr) return TOPK_ERR_NULL;
+  begin();
   if (topk::launch_short_dykstra(theta, out, rows, int(n), int(k), lambda, iters,
                                  static_cast<hipStream_t>(stream)) != 0)
     return TOPK_ERR_INVALID;
@@ -346,12 +386,14 @@ int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm
   if (theta == nullptr || perm_out == nullptr) return TOPK_ERR_NULL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (!is_long(n)) {
+    begin();
     if (topk::launch_short_argsort(theta, perm_out, rows, int(n), st) != 0) return TOPK_ERR_INVALID;
     return finish();
   }
   SortBuffers B;
   int rc = carve(rows, n, &B);
   if (rc != TOPK_OK) return rc;
+  begin();
   if (topk::launch_segmented_sort(false, theta, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
   if (hipMemcpyAsync(perm_out, B.idx_a, size_t(rows) * size_t(n) * 4, hipMemcpyDeviceToDevice,
                      st) != hipSuccess)

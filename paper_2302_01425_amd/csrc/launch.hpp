@@ -8,6 +8,15 @@
 
 namespace topk {
 
+// Choice among equivalent code paths (identical results), set through topk_set_route: for tests
+// that compare the routes and for tuning runs.  Values as in sparse_topk.h.
+struct Routes {
+  int long_rows = 0;      // TOPK_LONG_ROWS_*
+  int short_lanes = 0;    // lanes per row of the short-row kernels, 0 = chosen from the shape
+  int short_kernel = 0;   // TOPK_SHORT_ROW_KERNEL_*
+};
+Routes& routes();
+
 // Per-row result of the long-row solve: the pooled block [a, b] (1-based, inclusive; a = k+1,
 // b = k when nothing pools), its pooled value (relative to `center`), and d gamma of the JVP.
 // [wa, wb] is the block widened over values tied with its two end values: every sorted position

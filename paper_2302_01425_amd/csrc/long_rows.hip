@@ -9,18 +9,6 @@
 //            scattered through sigma.
 #include <hip/hip_runtime.h>
 
-#ifdef TOPK_PHASE_TRACE
-// Development aid (not compiled into the library): wall-clock stamps of the steps of the solve.
-__device__ unsigned long long g_long_trace[64][16];
-#define TOPK_SOLVE_MARK(i)                                                              \
-  do {                                                                                  \
-    if (blockIdx.x < 64 && threadIdx.x == 0) g_long_trace[blockIdx.x][i] = wall_clock64(); \
-  } while (0)
-extern "C" int topk_debug_read_long_trace(unsigned long long* host_out) {
-  return int(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_long_trace), sizeof(g_long_trace)));
-}
-#endif
-
 #include "common.hpp"
 #include "pooling.hpp"
 #include "launch.hpp"
@@ -49,12 +37,10 @@ __global__ __launch_bounds__(kSolveThreads) void long_solve_kernel(
     k = k_row - sel[row].above;
     if (n <= kFinishMax) return;          // solved together with the sort of its short list
   }
-  TOPK_SOLVE_MARK(0);
   const RowInfo ri = Solver::solve<MAG, PC>(
       skeys_all + row * row_len, sidx_all + row * row_len,
       tangent_all != nullptr ? tangent_all + row * row_len : nullptr, n, k, R, sm);
   if (threadIdx.x == 0) info[row] = ri;
-  TOPK_SOLVE_MARK(6);
 }
 
 // Dense pass in original order: everything whose value lies outside the block's value window.

@@ -14,10 +14,6 @@
 #include "pooling.hpp"
 #include "wave.hpp"
 
-#ifndef TOPK_SOLVE_MARK
-#define TOPK_SOLVE_MARK(i) do { } while (0)
-#endif
-
 namespace topk {
 
 struct Acc {
@@ -291,7 +287,6 @@ struct RowSolver {
       if (P::kCentered) center = sk;
       const double dk = sk - center, dk1 = sk1 - center;
       grow = P::seed_violates(dk, dk1, R, center);
-      TOPK_SOLVE_MARK(7);
       if (grow) {
         a = k;
         b = k + 1;
@@ -309,12 +304,10 @@ struct RowSolver {
           }
         }
         __syncthreads();
-        TOPK_SOLVE_MARK(11);
         a = sm.hand.a;
         b = sm.hand.b;
         S = sm.hand.S;
         if (sm.hand.done == 0) grow_block<NT, MAG, PC>(skeys, n, k, center, R, a, b, S, 0, sm.grow);
-        TOPK_SOLVE_MARK(8);
         const double da = double(key_to_float(skeys[a - 1])) - center;
         const double db = double(key_to_float(skeys[b - 1])) - center;
         // bracket of the pooled value: above the singleton minimiser of position a (mask:
@@ -323,7 +316,6 @@ struct RowSolver {
                           MAG ? da : db, center);
       }
     }
-    TOPK_SOLVE_MARK(9);
     if (grow && tangent != nullptr) {
       // Prop. 7: d gamma = sum_B c_j tau_j / (sum_B c_j [+ lambda m]),  c_j = |gamma - s_j|^(q-2)
       Acc acc{0.0, 0.0, 0.0, 0};
@@ -355,7 +347,6 @@ struct RowSolver {
       const Acc got = sum_acc(acc, sm.acc);
       dgamma = got.s1 / P::jac_denominator(got.s2, double(k - a + 1), R);
     }
-    TOPK_SOLVE_MARK(10);
     // ---- value window of the block, widened over ties at both ends -----------------------------
     RowInfo ri;
     ri.src = 0;

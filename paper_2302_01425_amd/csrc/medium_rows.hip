@@ -17,21 +17,6 @@
 // sizes); the row itself is read three times, the second and third time from L2.
 #include <hip/hip_runtime.h>
 
-#ifdef TOPK_PHASE_TRACE
-// Development aid (not compiled into the library): wall-clock stamps of the steps of a workgroup.
-__device__ unsigned long long g_med_trace[256][16];
-#define TOPK_MED_MARK(i)                                                               \
-  do {                                                                                 \
-    if (blockIdx.x < 256 && threadIdx.x == 0) g_med_trace[blockIdx.x][i] = wall_clock64(); \
-  } while (0)
-#define TOPK_SOLVE_MARK(i) TOPK_MED_MARK(i)
-extern "C" int topk_debug_read_med_trace(unsigned long long* host_out) {
-  return int(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_med_trace), sizeof(g_med_trace)));
-}
-#else
-#define TOPK_MED_MARK(i) do { } while (0)
-#endif
-
 #include "common.hpp"
 #include "launch.hpp"
 #include "long_solve.hpp"
@@ -257,7 +242,6 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
   uint32_t* kb = keys_b + base;
   uint32_t* ib = idx_b + base;
 
-  TOPK_MED_MARK(0);
   uint32_t cn = 0;
   uint32_t above_total = 0;              // elements of the row above the key window
   int k = k_row;
@@ -278,7 +262,6 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
       }
     }
     __syncthreads();
-    TOPK_MED_MARK(1);
     // ---- 2. bins of positions k and k+1, key window ---------------------------------------------
     constexpr int kPerThread = kSelBins / kMT;
     uint32_t c[kPerThread], mine = 0;
@@ -301,7 +284,6 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
     key_window<MAG>(sm.found[0], sm.found[1], R, PC == kP43, &klo, &khi);
     __syncthreads();                       // the histogram's memory is reused below
 
-    TOPK_MED_MARK(2);
     // ---- 3. ordered compaction of the candidates into (ka, ia) ----------------------------------
     // the window in value space (key order is reversed value order, -0 == +0 either way; keys
     // beyond the infinities are clamped, they would decode to NaN)
@@ -388,20 +370,17 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
     k = k_row - int(above_all);
     above_total = above_all;
 
-    TOPK_MED_MARK(3);
     // ---- 4. sort the candidates -------------------------------------------------------------------
     const SortedList sorted = sort_candidates<NT, kMItems>(ka, ia, kb, ib, cn, klo, khi, sm);
     skeys = sorted.keys;
     sidx = sorted.idx;
   }
 
-  TOPK_MED_MARK(4);
   // ---- 5. solve ---------------------------------------------------------------------------------------
   const int64_t n_sorted = (k_row >= 1 && k_row < n) ? int64_t(cn) : int64_t(n);
   const RowInfo ri = RowSolver<NT>::template solve<MAG, PC>(skeys, sidx, tangent, n_sorted, int64_t(k), R,
                                                     sm.solve);
 
-  TOPK_MED_MARK(5);
   // ---- 6. outputs ----------------------------------------------------------------------------------
   if constexpr (SPARSE) {
     int32_t* sp_idx = sp.idx + int64_t(blockIdx.x) * sp.max_nnz;
@@ -444,7 +423,6 @@ __global__ __launch_bounds__(NT) void medium_rows_kernel(
   for (int64_t pos1 = ri.wa + threadIdx.x; pos1 <= ri.wb; pos1 += kMT)
     emit_window_position<MAG, PC>(ri, pos1, key_to_float(skeys[pos1 - 1]), sidx[pos1 - 1], tangent,
                                   out, jvp, R);
-  TOPK_MED_MARK(6);
 }
 
 // Long rows: sort and solve of a candidate list of up to kFinishMax elements (the dense list in
@@ -467,14 +445,12 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(uint32_t* keys_a
   const int64_t base = row * n;
   uint32_t* ka = keys_a + base;
   uint32_t* ia = idx_a + base;
-  TOPK_MED_MARK(0);
   uint32_t* kb = keys_b + base;
   uint32_t* ib = idx_b + base;
   const SortedList sorted = sort_candidates<kFinishThreads, 16>(ka, ia, kb, ib, rs.cn, rs.klo, rs.khi, sm);
   const uint32_t* skeys = sorted.keys;
   const uint32_t* sidx = sorted.idx;
   int src = sorted.global_src;
-  TOPK_MED_MARK(3);
   if (src < 0) {
     // sorted in LDS only; the window pass reads the list from global memory
     for (uint32_t j = threadIdx.x; j < rs.cn; j += kMT) {
@@ -490,13 +466,11 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(uint32_t* keys_a
     skeys = lds_keys;
     __syncthreads();
   }
-  TOPK_MED_MARK(4);
   RowInfo ri = RowSolver<kMT>::solve<MAG, PC>(
       skeys, sidx, tangent_all != nullptr ? tangent_all + base : nullptr, int64_t(rs.cn),
       k_row - rs.above, R, sm.solve);
   ri.src = src;
   if (threadIdx.x == 0) info[row] = ri;
-  TOPK_MED_MARK(5);
 }
 
 template <bool MAG, int PC>

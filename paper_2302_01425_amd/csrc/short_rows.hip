@@ -399,10 +399,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // the solve, but also fewer wavefronts; with few rows the rows are spread over more lanes so
 // that every SIMD of the chip (1024 of them) still gets wavefronts.
 int pick_log_gl(int np, int64_t rows) {
-  static const int forced = [] {
-    const char* e = getenv("TOPK_SHORT_ROW_LANES");      // tuning override: lanes per row
-    return e ? atoi(e) : 0;
-  }();
+  const int forced = routes().short_lanes;             // tuning override: lanes per row
   // smallest allowed log2(GL): at most 8 elements per lane up to 128 padded elements (measured:
   // 16 per lane lose to 8 on both router workloads), at most 16 beyond
   const int emax = np <= 128 ? 8 : 16;
@@ -422,14 +419,8 @@ int pick_log_gl(int np, int64_t rows) {
   return lg;
 }
 
-// tuning / A-B switch: TOPK_SHORT_ROW_FAST=0 keeps the general float64-key kernels for all shapes
-bool fast_enabled() {
-  static const bool on = [] {
-    const char* e = getenv("TOPK_SHORT_ROW_FAST");
-    return !(e && e[0] == '0');
-  }();
-  return on;
-}
+// A/B switch (topk_set_route): the general float64-key kernels for all shapes
+bool fast_enabled() { return routes().short_kernel != 2; }
 
 }  // namespace
 

@@ -21,23 +21,6 @@
 #include "launch.hpp"
 #include "wave.hpp"
 
-#ifdef TOPK_PHASE_TRACE
-// Development aid (not compiled into the library): per-phase timestamps of one wavefront.
-__device__ unsigned long long g_phase_trace[4096][16];
-#define TOPK_MARK(i)                                                                   \
-  do {                                                                                 \
-    if (blockIdx.x < 4096 && threadIdx.x == 0) {                                         \
-      g_phase_trace[blockIdx.x][i] = __builtin_readcyclecounter();                     \
-      g_phase_trace[blockIdx.x][8 + i] = wall_clock64();                               \
-    }                                                                                  \
-  } while (0)
-extern "C" int topk_debug_read_trace(unsigned long long* host_out) {
-  return int(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_phase_trace), sizeof(g_phase_trace)));
-}
-#else
-#define TOPK_MARK(i) do { } while (0)
-#endif
-
 namespace topk {
 namespace {
 
@@ -274,7 +257,6 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   constexpr bool want_out = (MODE == 0 || MODE == 2), want_jvp = (MODE == 1 || MODE == 2);
 
   // ---- load, stage, sort ---------------------------------------------------------------------
-  TOPK_MARK(0);
   float xin[E], tin[E];
   if (FULL) {
 #pragma unroll
@@ -315,7 +297,6 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   if (want_out) lds_zero<E>(ly + e0);
   if (want_jvp) lds_zero<E>(ld + e0);
   __builtin_amdgcn_wave_barrier();
-  TOPK_MARK(1);
   float s[E];
   sort_words<GL, E, MAG>(c, s, lr, lx);
   if (want_jvp) {                               // staged after the sort: the sort need not wait for it
@@ -330,7 +311,6 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
   }
   lds_store<E>(ls + e0, s);
   __builtin_amdgcn_wave_barrier();
-  TOPK_MARK(2);
 
   // ---- isotonic solve: grow the one pooled block outwards from (k, k+1) ----------------------
   // All lanes of a row carry the same (a, b, sums).  A step tests the two neighbours of the block
@@ -440,7 +420,6 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
       gamma = grew ? gamma : 0.0;
     }
   }
-  TOPK_MARK(3);
 
   // ---- epilogue over the sorted positions 1..b (everything else stays zero) --------------------
   // pass j handles sorted position j*GL + lr + 1 of every row of the wavefront.  The original
@@ -571,7 +550,6 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
     if (lr == 0) sp.nnz[row] = b;
   }
   __builtin_amdgcn_wave_barrier();
-  TOPK_MARK(4);
   if (!valid) return;
 
   // ---- coalesced stores of the un-sorted rows ---------------------------------------------------
@@ -597,7 +575,6 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
       store_elems<E, VEC>(jvp, base, e0, n, jv);
     }
   }
-  TOPK_MARK(5);
 }
 
 template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE>

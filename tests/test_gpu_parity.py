@@ -21,6 +21,21 @@ def gpu():
     return binding
 
 
+import contextlib
+
+
+@contextlib.contextmanager
+def long_rows_route(gpu, mode):
+    """Run the body with rows above 1024 elements on the named route ("auto", "select", "sort")."""
+    code = {"auto": gpu.TOPK_LONG_ROWS_AUTO, "select": gpu.TOPK_LONG_ROWS_SELECT,
+            "sort": gpu.TOPK_LONG_ROWS_SORT}[mode]
+    gpu.set_route(gpu.TOPK_ROUTE_LONG_ROWS, code)
+    try:
+        yield
+    finally:
+        gpu.set_route(gpu.TOPK_ROUTE_LONG_ROWS, gpu.TOPK_LONG_ROWS_AUTO)
+
+
 def dev(a):
     import torch
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -129,7 +144,7 @@ def test_long_rows(gpu, oracle, rows, n):
     run_case(gpu, oracle, "mask", x, t, n // 3, P43, 50.0, check_perm=False)
 
 
-def test_long_rows_kinks_ties_and_full_sort_agreement(gpu, oracle, monkeypatch):
+def test_long_rows_kinks_ties_and_full_sort_agreement(gpu, oracle):
     """Long rows whose block boundary falls inside runs of equal values (the position of each tied
     index decides its JVP), and agreement of the candidate-selection path with the full sort."""
     r = np.random.default_rng(5)
@@ -155,18 +170,15 @@ def test_long_rows_kinks_ties_and_full_sort_agreement(gpu, oracle, monkeypatch):
         jvpf = gpu.topk_mask_jvp if op == "mask" else gpu.topkmag_jvp
         o_def, j_def = (host(a) for a in jvpf(xd, td, k, p, lam))
         for mode in ("select", "sort"):
-            monkeypatch.setenv("TOPK_LONG_ROWS", mode)
-            o_alt, j_alt = (host(a) for a in jvpf(xd, td, k, p, lam))
-            monkeypatch.delenv("TOPK_LONG_ROWS")
+            with long_rows_route(gpu, mode):
+                o_alt, j_alt = (host(a) for a in jvpf(xd, td, k, p, lam))
             assert np.array_equal(o_def, o_alt) and np.array_equal(j_def, j_alt), (mode, op, p, k, lam)
 
 
 @pytest.mark.parametrize("mode", ["auto", "select"])
-def test_degenerate_windows(gpu, oracle, monkeypatch, mode):
+def test_degenerate_windows(gpu, oracle, mode):
     """Rows whose candidate window degenerates: constant rows (one key), two values, windows that
     touch +0 / -0, rows of mostly zeros where s_k itself is zero."""
-    if mode != "auto":
-        monkeypatch.setenv("TOPK_LONG_ROWS", mode)
     r = np.random.default_rng(31)
     n = 6000
     t = r.normal(size=(6, n)).astype(np.float32)
@@ -178,27 +190,28 @@ def test_degenerate_windows(gpu, oracle, monkeypatch, mode):
     x[3, ::7] = -0.0
     x[4] = np.round(r.normal(size=n) * 2) * np.float32(1e-38)   # tiny values around zero (denormals)
     x[5] = -np.abs(r.normal(size=n))                          # all negative
-    for k in (1, 100, n // 2, n - 1):
-        for p, lam in ((P2, 0.5), (P43, 0.5), (P2, 1e-3)):
-            run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
-        run_case(gpu, oracle, "mag", x, t, k, P2, 0.1, check_perm=False)
+    with long_rows_route(gpu, mode):
+        for k in (1, 100, n // 2, n - 1):
+            for p, lam in ((P2, 0.5), (P43, 0.5), (P2, 1e-3)):
+                run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
+            run_case(gpu, oracle, "mag", x, t, k, P2, 0.1, check_perm=False)
 
 
 @pytest.mark.parametrize("mode", ["select", "sort"])
-def test_long_rows_multi_launch_paths(gpu, oracle, monkeypatch, mode):
+def test_long_rows_multi_launch_paths(gpu, oracle, mode):
     """The multi-launch paths (candidate selection + sort of the candidates; full sort), which by
     default only rows above 131072 elements take, on sizes the oracle finishes quickly."""
-    monkeypatch.setenv("TOPK_LONG_ROWS", mode)
     r = np.random.default_rng(11)
-    for rows, n in [(3, 3000), (2, 4097), (1, 70001)]:
-        x = r.normal(size=(rows, n)).astype(np.float32)
-        x[-1, :] = np.round(x[-1, :] * 4) / 4
-        t = r.normal(size=(rows, n)).astype(np.float32)
-        for p, k, lam in [(P2, 1, 0.1), (P2, n // 10, 0.01), (P43, n // 2, 1.0), (P2, n - 1, 0.1),
-                          (P43, n // 3, 50.0)]:
-            run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
-        for k in (0, n // 10, n):
-            run_case(gpu, oracle, "mag", x * np.float32(0.02), t, k, P2, 0.05, check_perm=False)
+    with long_rows_route(gpu, mode):
+        for rows, n in [(3, 3000), (2, 4097), (1, 70001)]:
+            x = r.normal(size=(rows, n)).astype(np.float32)
+            x[-1, :] = np.round(x[-1, :] * 4) / 4
+            t = r.normal(size=(rows, n)).astype(np.float32)
+            for p, k, lam in [(P2, 1, 0.1), (P2, n // 10, 0.01), (P43, n // 2, 1.0), (P2, n - 1, 0.1),
+                              (P43, n // 3, 50.0)]:
+                run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
+            for k in (0, n // 10, n):
+                run_case(gpu, oracle, "mag", x * np.float32(0.02), t, k, P2, 0.05, check_perm=False)
 
 
 def test_rows_above_the_fused_kernel_limit(gpu, oracle):
