@@ -50,6 +50,8 @@ def parse():
                     help="instead of the one JSON line: time the mask forward + JVP over row lengths "
                          "64 .. 2^24 at a constant 2^24 elements, k = ceil(n/10) (the paper's timing "
                          "sweep uses k = ceil(n/10)), lambda = 0.1, one JSON line per row length")
+    ap.add_argument("--route", action="append", default=[], metavar="WHICH=VALUE",
+                    help="tuning run: set a route control of the library (topk_set_route), e.g. 2=1")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip the timing of the other four workloads (key `workloads`)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -301,6 +303,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if a.route:
+        from paper_2302_01425_amd import binding
+        for item in a.route:
+            which, value = item.split("=")
+            binding.set_route(int(which), int(value))
     if a.sweep:
         sweep(a)
         return

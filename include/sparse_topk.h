@@ -251,8 +251,11 @@ int topk_set_workspace(void* dev_ptr, size_t bytes);
  *                               selection for every such row), _SORT (rows sorted completely)
  *   TOPK_ROUTE_SHORT_ROW_LANES  lanes of a wavefront that share a short row: 0 (by shape) or a
  *                               power of two up to 64 (clamped to what the row length allows)
- *   TOPK_ROUTE_SHORT_ROW_KERNEL TOPK_SHORT_ROW_KERNEL_AUTO, or _GENERAL: the general short-row
- *                               kernel also for rows of up to 128 elements
+ *   TOPK_ROUTE_SHORT_ROW_KERNEL for rows of up to 128 elements: TOPK_SHORT_ROW_KERNEL_AUTO (dense
+ *                               outputs from the kernel that orders values only), _INDEXED (the
+ *                               kernel that builds the permutation, as the compact output and
+ *                               topk_argsort_desc always do), _GENERAL (the general short-row
+ *                               kernel of rows up to TOPK_SHORT_ROW_MAX elements)
  * Returns TOPK_OK or TOPK_ERR_INVALID (unknown control or value).
  */
 #define TOPK_ROUTE_LONG_ROWS 0
@@ -262,6 +265,7 @@ int topk_set_workspace(void* dev_ptr, size_t bytes);
 #define TOPK_LONG_ROWS_SELECT 1
 #define TOPK_LONG_ROWS_SORT 2
 #define TOPK_SHORT_ROW_KERNEL_AUTO 0
+#define TOPK_SHORT_ROW_KERNEL_INDEXED 1
 #define TOPK_SHORT_ROW_KERNEL_GENERAL 2
 int topk_set_route(int which, int value);
 

@@ -92,6 +92,10 @@ struct SparseOut {
 int launch_short_rows_fast(int np, int lg, bool vec, bool mag, int pc, const float* x,
                            const float* tangent, float* out, float* jvp, int64_t rows, int n,
                            int k, const Reg& R, hipStream_t st);
+// Dense outputs of the same shapes without building the permutation (short_rows_select.hip).
+int launch_short_rows_value(int np, int lg, bool vec, bool mag, int pc, const float* x,
+                            const float* tangent, float* out, float* jvp, int64_t rows, int n,
+                            int k, const Reg& R, hipStream_t st);
 int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t* perm,
                               int64_t rows, int n, hipStream_t st);
 int launch_short_rows_fast_sparse(int np, int lg, bool vec, int pc, const float* x, int64_t rows,

@@ -419,8 +419,11 @@ int pick_log_gl(int np, int64_t rows) {
   return lg;
 }
 
-// A/B switch (topk_set_route): the general float64-key kernels for all shapes
+// A/B switches (topk_set_route): TOPK_SHORT_ROW_KERNEL_GENERAL keeps the general float64-key
+// kernels for all shapes, _INDEXED the 32-bit-word kernels that build the permutation also for the
+// dense outputs (by default those come from the value-ordering kernel).
 bool fast_enabled() { return routes().short_kernel != 2; }
+bool value_enabled() { return routes().short_kernel == 0; }
 
 }  // namespace
 
@@ -445,6 +448,10 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
 #define CALL(GL, E, V) launch_shape<GL, E, V>(mag, pc, x, tangent, out, jvp, rows, n, k, R, st)
   if (np == 2) return CALL(1, 2, false);
   const int lg = pick_log_gl(np, rows);
+  if (np <= 128 && value_enabled()) {
+    const int rc = launch_short_rows_value(np, lg, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
+    if (rc != -2) return rc;
+  }
   if (np <= 128 && fast_enabled()) {
     const int rc = launch_short_rows_fast(np, lg, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
     if (rc != -2) return rc;
