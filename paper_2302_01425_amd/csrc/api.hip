@@ -82,10 +82,10 @@ Layout layout_for(int64_t rows, int64_t n) {
 }
 
 // `skip`: bytes at the start of the workspace that the caller keeps for itself
-int carve(int64_t rows, int64_t n, SortBuffers* B, size_t skip = 0) {
+int carve(int64_t rows, int64_t n, SortBuffers* B, size_t skip = 0, const Workspace& ws = g_ws) {
   const Layout L = layout_for(rows, n);
-  if (g_ws.ptr == nullptr || g_ws.bytes < skip + L.total) return TOPK_ERR_WORKSPACE;
-  char* base = static_cast<char*>(g_ws.ptr) + skip;
+  if (ws.ptr == nullptr || ws.bytes < skip + L.total) return TOPK_ERR_WORKSPACE;
+  char* base = static_cast<char*>(ws.ptr) + skip;
   B->keys_a = reinterpret_cast<uint32_t*>(base + L.keys_a);
   B->keys_b = reinterpret_cast<uint32_t*>(base + L.keys_b);
   B->idx_a = reinterpret_cast<uint32_t*>(base + L.idx_a);
@@ -120,7 +120,7 @@ int finish() { return hipGetLastError() == hipSuccess ? TOPK_OK : TOPK_ERR_LAUNC
 // shared body of the four operator entry points
 int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, int64_t n,
                  int64_t k, double p, double lambda, float* out, float* jvp, bool need_out,
-                 bool need_jvp, void* stream, size_t ws_skip = 0) {
+                 bool need_jvp, void* stream, size_t ws_skip = 0, const Workspace& ws = g_ws) {
   int rc = check_shape(rows, n, k, lambda);
   if (rc != TOPK_OK) return rc;
   const int pc = p_code(p);
@@ -133,7 +133,7 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   const Reg R = make_reg(lambda);
   SortBuffers B;
   if (is_long(n)) {
-    rc = carve(rows, n, &B, ws_skip);
+    rc = carve(rows, n, &B, ws_skip, ws);
     if (rc != TOPK_OK) return rc;
   }
   begin();

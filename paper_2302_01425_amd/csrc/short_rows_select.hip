@@ -29,6 +29,14 @@
 #include "launch.hpp"
 #include "wave.hpp"
 
+// wavefronts per workgroup, and single-neighbour growth steps before the chunked growth (p = 2)
+#ifndef TOPK_VALUE_WPB
+#define TOPK_VALUE_WPB 4
+#endif
+#ifndef TOPK_VALUE_SINGLE_STEPS
+#define TOPK_VALUE_SINGLE_STEPS 3
+#endif
+
 namespace topk {
 namespace {
 
@@ -252,7 +260,7 @@ __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
       cnt = 2.0;
       m = 1.0;
       // (1) a few single-neighbour steps: the usual p = 2 block has 2-5 positions
-      constexpr int kSingleSteps = CUBIC ? 0 : 3;
+      constexpr int kSingleSteps = CUBIC ? 0 : TOPK_VALUE_SINGLE_STEPS;
       bool pending = true;               // some row of the wavefront may still grow
       for (int step = 0; step < kSingleSteps || !CHUNKED; ++step) {
         const double dj = double(nr) - center, di = double(nl) - center;
@@ -424,7 +432,7 @@ int launch_value_wpb(const float* x, const float* t, float* out, float* jvp, int
 template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE>
 int launch_value_mode(const float* x, const float* t, float* out, float* jvp, int64_t rows, int n,
                       int k, const Reg& R, hipStream_t st) {
-  constexpr int WPB = 4;
+  constexpr int WPB = TOPK_VALUE_WPB;
   if (k >= 1 && k <= GL && k < n)
     return launch_value_wpb<GL, E, MAG, PC, VEC, FULL, MODE, true, WPB>(x, t, out, jvp, rows, n, k, R, st);
   return launch_value_wpb<GL, E, MAG, PC, VEC, FULL, MODE, false, WPB>(x, t, out, jvp, rows, n, k, R, st);
