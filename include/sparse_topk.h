@@ -52,7 +52,9 @@ enum {
   TOPK_ERR_NULL = -2,           /* a required pointer is NULL */
   TOPK_ERR_UNSUPPORTED_P = -3,  /* p is neither 2 nor 4/3 */
   TOPK_ERR_WORKSPACE = -4,      /* long rows and the registered workspace is missing or too small */
-  TOPK_ERR_LAUNCH = -5          /* the HIP runtime refused a launch (see hipGetLastError) */
+  TOPK_ERR_LAUNCH = -5,         /* the HIP runtime refused a launch (see hipGetLastError) */
+  TOPK_ERR_STATIC_SCRATCH = -6  /* topk_mask_jvp_static: the shape needs more scratch than
+                                   TOPK_STATIC_SCRATCH_BYTES */
 };
 
 /* Operator codes for topk_workspace_bytes(). */
@@ -105,6 +107,28 @@ int topk_mask_jvp(const float* theta, const float* tangent, int64_t rows, int64_
  */
 int topkmag_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p, double lambda,
                 float* out, void* stream);
+
+/*
+ * topk_mask_jvp for callers that cannot allocate or register device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for
+ * bit) and errors as topk_mask_jvp, but rows above TOPK_SHORT_ROW_MAX elements use a scratch
+ * array that is part of the library's device image instead of the registered workspace; the
+ * call allocates nothing, frees nothing and ignores topk_set_workspace.
+ *   - Limit: topk_workspace_bytes(TOPK_OP_MASK_JVP, rows, n, k, p) <= TOPK_STATIC_SCRATCH_BYTES
+ *     (about rows * n <= 3.6 million elements); larger shapes return TOPK_ERR_STATIC_SCRATCH
+ *     with nothing enqueued.  Rows up to TOPK_SHORT_ROW_MAX elements need no scratch and have no
+ *     such limit.
+ *   - Every GPU the library is used on holds its own copy of the array (TOPK_STATIC_SCRATCH_BYTES
+ *     of device memory, for the life of the process); the first call on a device looks its
+ *     address up (make that call outside a stream capture).
+ *   - All calls on one GPU share that GPU's array and nothing in it needs to start at zero, but
+ *     two calls that overlap in time on one GPU (different streams, or threads) race on it:
+ *     serialise them on one stream.
+ */
+#define TOPK_STATIC_SCRATCH_BYTES (64u << 20)
+int topk_mask_jvp_static(const float* theta, const float* tangent, int64_t rows, int64_t n,
+                         int64_t k, double p, double lambda, float* out, float* jvp_out,
+                         void* stream);
 
 /* JVP of the relaxed top-k in magnitude (Prop. 7, case phi = x^2/2), fused with the forward pass;
  * `out` may be NULL. */

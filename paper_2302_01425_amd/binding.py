@@ -21,7 +21,7 @@ EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
     "topk_mask_sparse_fwd", "topk_general_fwd", "topk_general_jvp", "topk_mask_dykstra_fwd", "topk_signed_mask_fwd", "topk_signed_mask_jvp", "topk_masked_value_fwd", "topk_masked_value_jvp",
     "topk_mask_loss", "topk_argsort_desc", "topk_workspace_bytes", "topk_set_workspace",
-    "topk_set_route", "topk_strerror",
+    "topk_set_route", "topk_strerror", "topk_mask_jvp_static",
 )
 
 _lib = None
@@ -44,6 +44,8 @@ def load() -> ctypes.CDLL:
     vp, i64, dbl, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_int
     L.topk_mask_fwd.argtypes = [vp, i64, i64, i64, dbl, dbl, vp, vp]
     L.topk_mask_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
+    L.topk_mask_jvp_static.argtypes = L.topk_mask_jvp.argtypes
+    L.topk_mask_jvp_static.restype = ci
     L.topkmag_fwd.argtypes = [vp, i64, i64, i64, dbl, dbl, vp, vp]
     L.topkmag_jvp.argtypes = [vp, vp, i64, i64, i64, dbl, dbl, vp, vp, vp]
     for name in ("topk_signed_mask_fwd", "topk_masked_value_fwd"):
@@ -207,6 +209,25 @@ def topk_mask_jvp(theta, tangent, k, p, lam, out=None, jvp_out=None, want_out=Tr
     _check(load().topk_mask_jvp(theta.data_ptr(), tangent.data_ptr(), rows, n, int(k), float(p),
                                 float(lam), None if out is None else out.data_ptr(),
                                 jvp_out.data_ptr(), _stream(stream)), "topk_mask_jvp")
+    return out, jvp_out
+
+
+def topk_mask_jvp_static(theta, tangent, k, p, lam, out, jvp_out, stream=None):
+    """topk_mask_jvp on the library's static scratch: nothing is allocated here either, so every
+    tensor (out may be None) comes from the caller.  Returns (out, jvp_out)."""
+    theta = _dev_f32(theta, "theta")
+    tangent = _like(tangent, theta, "tangent")
+    rows, n = theta.shape
+    if out is not None:
+        out = _like(out, theta, "out", (theta, tangent))
+    jvp_out = _like(jvp_out, theta, "jvp_out", (theta, tangent))
+    if out is not None and _overlap(out, jvp_out):
+        raise TopkError("out and jvp_out overlap")
+    _check(load().topk_mask_jvp_static(theta.data_ptr(), tangent.data_ptr(), rows, n, int(k),
+                                       float(p), float(lam),
+                                       None if out is None else out.data_ptr(),
+                                       jvp_out.data_ptr(), _stream(stream)),
+           "topk_mask_jvp_static")
     return out, jvp_out
 
 

@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/sparse_topk.h"
 #include "launch.hpp"
@@ -202,6 +203,35 @@ int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int
   return finish();
 }
 
+// ---- the library's own scratch, for the one entry point that must not allocate ------------------
+// One copy of this array lives on every GPU the library is loaded on, for the life of the process.
+// In host code its name is only a handle for hipGetSymbolAddress: the device address is looked up
+// once per device (with that device current) and kept; kernels and carve() only ever see that
+// address.
+__device__ __align__(256) unsigned char scratch[TOPK_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int static_scratch(Workspace* ws) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return TOPK_ERR_LAUNCH;
+  if (dev < 0 || dev >= kMaxDevices) return TOPK_ERR_INVALID;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      return TOPK_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  ws->ptr = g_scratch_ptr[dev];
+  ws->bytes = TOPK_STATIC_SCRATCH_BYTES;
+  return TOPK_OK;
+}
+
 }  // namespace
 
 namespace topk {
@@ -341,6 +371,23 @@ int topk_mask_jvp(const float* theta, const float* tangent, int64_t rows, int64_
                       stream);
 }
 
+int topk_mask_jvp_static(const float* theta, const float* tangent, int64_t rows, int64_t n,
+                         int64_t k, double p, double lambda, float* out, float* jvp_out,
+                         void* stream) {
+  // shapes whose scratch does not fit the static array are refused before anything else happens
+  const int rc = check_shape(rows, n, k, lambda);
+  if (rc != TOPK_OK) return rc;
+  if (is_long(n) && layout_for(rows, n).total > size_t(TOPK_STATIC_SCRATCH_BYTES))
+    return TOPK_ERR_STATIC_SCRATCH;
+  Workspace ws;
+  if (is_long(n)) {
+    const int src = static_scratch(&ws);
+    if (src != TOPK_OK) return src;
+  }
+  return run_operator(false, theta, tangent, rows, n, k, p, lambda, out, jvp_out, false, true,
+                      stream, 0, ws);
+}
+
 int topkmag_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p, double lambda,
                 float* out, void* stream) {
   return run_operator(true, x, nullptr, rows, n, k, p, lambda, out, nullptr, true, false, stream);
@@ -432,6 +479,9 @@ const char* topk_strerror(int code) {
     case TOPK_ERR_UNSUPPORTED_P: return "unsupported p (only 2 and 4/3)";
     case TOPK_ERR_WORKSPACE: return "workspace missing or too small (see topk_workspace_bytes)";
     case TOPK_ERR_LAUNCH: return "HIP launch failed";
+    case TOPK_ERR_STATIC_SCRATCH:
+      return "shape needs more scratch than the library's static buffer of "
+             "TOPK_STATIC_SCRATCH_BYTES (use topk_mask_jvp with a registered workspace)";
     default: return "unknown error code";
   }
 }
