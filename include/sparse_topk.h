@@ -271,8 +271,11 @@ int topk_set_workspace(void* dev_ptr, size_t bytes);
  * compare them bit for bit).  Process-wide, takes effect for later calls; not meant for production
  * callers, whose default is always TOPK_*_AUTO.
  *   TOPK_ROUTE_LONG_ROWS        how rows above TOPK_SHORT_ROW_MAX elements are handled:
- *                               TOPK_LONG_ROWS_AUTO (by shape), _SELECT (the multi-launch candidate
- *                               selection for every such row), _SORT (rows sorted completely)
+ *                               TOPK_LONG_ROWS_AUTO (by shape), _SELECT (multi-launch candidate
+ *                               selection, sorted (key, index) lists and scatter, for every such
+ *                               row), _SORT (rows sorted completely), _WIDE (multi-launch
+ *                               selection, key-only sort and outputs by value: what AUTO takes
+ *                               for few or very long rows)
  *   TOPK_ROUTE_SHORT_ROW_LANES  lanes of a wavefront that share a short row: 0 (by shape) or a
  *                               power of two up to 64 (clamped to what the row length allows)
  *   TOPK_ROUTE_SHORT_ROW_KERNEL for rows of up to 128 elements: TOPK_SHORT_ROW_KERNEL_AUTO (dense
@@ -288,6 +291,7 @@ int topk_set_workspace(void* dev_ptr, size_t bytes);
 #define TOPK_LONG_ROWS_AUTO 0
 #define TOPK_LONG_ROWS_SELECT 1
 #define TOPK_LONG_ROWS_SORT 2
+#define TOPK_LONG_ROWS_WIDE 3
 #define TOPK_SHORT_ROW_KERNEL_AUTO 0
 #define TOPK_SHORT_ROW_KERNEL_INDEXED 1
 #define TOPK_SHORT_ROW_KERNEL_GENERAL 2

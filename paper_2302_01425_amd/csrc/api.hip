@@ -51,7 +51,7 @@ bool is_long(int64_t n) { return n > TOPK_SHORT_ROW_MAX; }
 // topk_set_route the multi-launch selection path can be chosen for every such row, or a complete
 // sort of the rows (same results; for tests and comparisons).
 enum LongMode { kAuto = TOPK_LONG_ROWS_AUTO, kSelect = TOPK_LONG_ROWS_SELECT,
-                kFullSort = TOPK_LONG_ROWS_SORT };
+                kFullSort = TOPK_LONG_ROWS_SORT, kWide = TOPK_LONG_ROWS_WIDE };
 LongMode long_mode() { return static_cast<LongMode>(topk::routes().long_rows); }
 
 struct Layout {
@@ -145,14 +145,28 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
     return finish();
   }
   const LongMode mode = long_mode();
+  // k = 0 and k = n pool nothing and read no sorted value: no sort at all
+  const bool trivial = (k == 0 || k == n);
+  // Few long rows: one workgroup per row would leave most of the chip idle, so the streaming steps
+  // of a row are spread over many workgroups (separate launches) and only the sort + solve of its
+  // candidates is left to one.  Also every row above kMediumRowMax elements.
+  const bool few_long_rows = rows <= 96 && n >= 16384;
+  if (!trivial && (mode == kWide || (mode == kAuto && (n > topk::kMediumRowMax || few_long_rows)))) {
+    const bool refine = n > (int64_t(1) << 18);
+    if (topk::launch_wide_select(mag, pc, refine, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
+    if (topk::launch_wide_finish(mag, pc, B, need_jvp ? tangent : nullptr, rows, n, k, R, st) != 0)
+      return TOPK_ERR_INVALID;
+    if (topk::launch_wide_dense(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
+                                need_jvp ? jvp : nullptr, rows, n, R, st) != 0)
+      return TOPK_ERR_INVALID;
+    return finish();
+  }
   if (mode == kAuto && n <= topk::kMediumRowMax) {
     if (topk::launch_medium_rows(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
                                  need_jvp ? jvp : nullptr, rows, n, k, R, st) != 0)
       return TOPK_ERR_INVALID;
     return finish();
   }
-  // k = 0 and k = n pool nothing and read no sorted value: no sort at all
-  const bool trivial = (k == 0 || k == n);
   const bool selected = !trivial && mode != kFullSort;
   if (selected) {
     if (topk::launch_candidate_lists(mag, pc, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
@@ -247,7 +261,7 @@ int topk_set_route(int which, int value) {
   topk::Routes& r = topk::routes();
   switch (which) {
     case TOPK_ROUTE_LONG_ROWS:
-      if (value < TOPK_LONG_ROWS_AUTO || value > TOPK_LONG_ROWS_SORT) return TOPK_ERR_INVALID;
+      if (value < TOPK_LONG_ROWS_AUTO || value > TOPK_LONG_ROWS_WIDE) return TOPK_ERR_INVALID;
       r.long_rows = value;
       return TOPK_OK;
     case TOPK_ROUTE_SHORT_ROW_LANES:

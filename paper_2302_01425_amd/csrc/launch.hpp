@@ -132,6 +132,18 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
 // index order, as a dense list per row in the "a" arrays; B.sel[row] = {window, length, above}.
 int launch_candidate_lists(bool mag, int pc, const float* x, int64_t rows, int64_t n, int64_t k,
                            const Reg& R, const SortBuffers& B, hipStream_t st);
+// Wide route (rows that several workgroups share; 0 < k < n): the same candidate selection with
+// the candidates left in the tiles' slots of the "b" arrays (B.tcnt, B.tabove); one workgroup per
+// row then collects them, sorts their keys, grows the block and adds up the tangent over it
+// (B.info[row]: gamma, d gamma and the block's value window); one dense pass computes every
+// output from its element's value.  refine: second histogram level (worth it for very long rows).
+int launch_wide_select(bool mag, int pc, bool refine, const float* x, int64_t rows, int64_t n,
+                       int64_t k, const Reg& R, const SortBuffers& B, hipStream_t st);
+int launch_wide_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, int64_t rows,
+                       int64_t n, int64_t k, const Reg& R, hipStream_t st);
+int launch_wide_dense(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
+                      float* out, float* jvp, int64_t rows, int64_t n, const Reg& R,
+                      hipStream_t st);
 // Lists of up to kFinishMax candidates: sort + solve by one workgroup per row -> B.info[row].
 int launch_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, int64_t rows,
                   int64_t n, int64_t k, const Reg& R, hipStream_t st);

@@ -90,6 +90,83 @@ __global__ __launch_bounds__(kThreads) void long_window_kernel(
   }
 }
 
+
+// Wide route: the whole output of a row in one pass in original order, every element from its own
+// value: above the block's value window the literal 1 (mask) or its own singleton solution
+// (magnitude), below it 0, inside it (lo_incl <= value <= hi_incl: exactly the block, elements of
+// equal value pool together) the pooled formula with the row's gamma and d gamma.
+template <bool MAG, int PC>
+__global__ __launch_bounds__(kThreads) void wide_dense_kernel(
+    const float* __restrict__ x_all, const float* __restrict__ tangent_all,
+    const RowInfo* __restrict__ info, float* __restrict__ out_all, float* __restrict__ jvp_all,
+    int64_t n, int chunks, Reg R) {
+  using P = Pool<MAG, PC>;
+  const int64_t row = blockIdx.x / chunks;
+  const int64_t chunk = blockIdx.x % chunks;
+  const RowInfo ri = info[row];
+  const int64_t base = row * n;
+  const int64_t first = chunk * int64_t(kThreads * 8);
+  const float* tangent = tangent_all != nullptr ? tangent_all + base : nullptr;
+  float* out = out_all != nullptr ? out_all + base : nullptr;
+  float* jvp = jvp_all != nullptr ? jvp_all + base : nullptr;
+  const bool have_block = ri.a <= ri.b;
+  float xv[8], tv[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
+    xv[i] = e < n ? load_stream(x_all + base + e) : 0.0f;
+    tv[i] = (e < n && jvp != nullptr) ? load_stream(tangent + e) : 0.0f;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
+    if (e >= n) continue;
+    const float v = MAG ? fabsf(xv[i]) : xv[i];
+    const bool above = v > ri.hi_incl;
+    const bool inside = have_block && !above && v >= ri.lo_incl;
+    const bool neg = MAG && (__float_as_uint(xv[i]) >> 31);
+    float y = 0.0f, d = 0.0f;
+    if (inside) {
+      const double c = double(v) - ri.center;
+      y = float(P::y_in_block(c, ri.gamma, R));
+      if (MAG) y = (y == 0.0f) ? 0.0f : (neg ? -y : y);
+      if (jvp != nullptr) {
+        double t = double(tv[i]);
+        if (neg) t = -t;
+        if (MAG && v == 0.0f) t = 0.0;
+        float df = float(P::hess(c, ri.gamma, R) * (t - ri.dgamma));
+        if (MAG && v == 0.0f) df = 0.0f;
+        d = (df == 0.0f) ? 0.0f : (neg ? -df : df);
+      }
+    } else if (above) {
+      if constexpr (MAG && PC == kP43) {
+        if (xv[i] != 0.0f) {
+          double g, slope;
+          P::above_both(double(v), R, 0.0, &g, &slope);
+          y = float(neg ? -g : g);
+          if (jvp != nullptr) d = float(slope * double(tv[i]));
+        }
+      } else if (MAG) {
+        const float inv_1pl = float(R.inv_1pl);
+        y = xv[i] * inv_1pl;
+        if (jvp != nullptr && xv[i] != 0.0f) d = tv[i] * inv_1pl;
+      } else {
+        y = 1.0f;
+      }
+    }
+    if (out != nullptr) store_stream(out + e, y);
+    if (jvp != nullptr) store_stream(jvp + e, d);
+  }
+}
+
+template <bool MAG, int PC>
+void launch_wide_dense_t(const SortBuffers& B, const float* x, const float* tangent, float* out,
+                         float* jvp, int64_t rows, int64_t n, const Reg& R, hipStream_t st) {
+  const int chunks = int((n + kThreads * 8 - 1) / (kThreads * 8));
+  hipLaunchKernelGGL((wide_dense_kernel<MAG, PC>), dim3(unsigned(rows * chunks)), dim3(kThreads), 0,
+                     st, x, jvp ? tangent : nullptr, B.info, out, jvp, n, chunks, R);
+}
+
 template <bool MAG, int PC>
 void launch_tail(bool selected, const SortBuffers& B, const float* x, const float* tangent,
                  float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
@@ -107,6 +184,19 @@ void launch_tail(bool selected, const SortBuffers& B, const float* x, const floa
 }
 
 }  // namespace
+
+int launch_wide_dense(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
+                      float* out, float* jvp, int64_t rows, int64_t n, const Reg& R,
+                      hipStream_t st) {
+  const int64_t chunks = (n + kThreads * 8 - 1) / (kThreads * 8);
+  if (rows * chunks > 0x7fffffffLL) return -1;
+  if (!mag && pc == kP2) launch_wide_dense_t<false, kP2>(B, x, tangent, out, jvp, rows, n, R, st);
+  else if (!mag && pc == kP43) launch_wide_dense_t<false, kP43>(B, x, tangent, out, jvp, rows, n, R, st);
+  else if (mag && pc == kP2) launch_wide_dense_t<true, kP2>(B, x, tangent, out, jvp, rows, n, R, st);
+  else if (mag && pc == kP43) launch_wide_dense_t<true, kP43>(B, x, tangent, out, jvp, rows, n, R, st);
+  else return -1;
+  return 0;
+}
 
 int launch_long_tail(bool mag, int pc, bool selected, const SortBuffers& B, const float* x,
                      const float* tangent, float* out, float* jvp, int64_t rows, int64_t n,

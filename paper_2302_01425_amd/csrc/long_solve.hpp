@@ -272,7 +272,10 @@ struct RowSolver {
   // can draw from, k the number of them that belong to the top-k; tangent: the row's tangent in
   // original order, or null.  Every thread returns the same RowInfo (positions relative to
   // skeys).
-  template <bool MAG, int PC>
+  // VALUE_ONLY: the caller computes the outputs from values (thresholds hi_incl, lo_incl) and adds
+  // up the tangent itself: no index payload is read and the tie runs are not counted (wa, wb are
+  // then just a, b).
+  template <bool MAG, int PC, bool VALUE_ONLY = false>
   __device__ static RowInfo solve(const uint32_t* __restrict__ skeys,
                                   const uint32_t* __restrict__ sidx,
                                   const float* __restrict__ tangent, int64_t n, int64_t k,
@@ -316,7 +319,7 @@ struct RowSolver {
                           MAG ? da : db, center);
       }
     }
-    if (grow && tangent != nullptr) {
+    if (!VALUE_ONLY && grow && tangent != nullptr) {
       // Prop. 7: d gamma = sum_B c_j tau_j / (sum_B c_j [+ lambda m]),  c_j = |gamma - s_j|^(q-2)
       Acc acc{0.0, 0.0, 0.0, 0};
       for (int64_t p0 = a + threadIdx.x; p0 <= b; p0 += 4 * NT) {
@@ -360,8 +363,8 @@ struct RowSolver {
       const uint32_t key_a = skeys[a - 1], key_b = skeys[b - 1];
       ri.hi_incl = key_to_float(key_a);
       ri.lo_incl = key_to_float(key_b);
-      ri.wa = a - count_equal_run<false>(skeys, n, a - 1, key_a, sm);
-      ri.wb = b + count_equal_run<true>(skeys, n, b + 1, key_b, sm);
+      ri.wa = VALUE_ONLY ? a : a - count_equal_run<false>(skeys, n, a - 1, key_a, sm);
+      ri.wb = VALUE_ONLY ? b : b + count_equal_run<true>(skeys, n, b + 1, key_b, sm);
     } else if (k >= 1 && k < n) {
       // no violation: s_k > s_{k+1} strictly; "above hi" = the top k, "below lo" = the rest
       ri.hi_incl = key_to_float(skeys[k]);        // s_{k+1}

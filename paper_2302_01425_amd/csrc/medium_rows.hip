@@ -473,6 +473,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(uint32_t* keys_a
   if (threadIdx.x == 0) info[row] = ri;
 }
 
+
 template <bool MAG, int PC>
 void launch(const SortBuffers& B, const float* x, const float* tangent, float* out, float* jvp,
             int64_t rows, int n, int k, const Reg& R, hipStream_t st) {

@@ -411,7 +411,7 @@ __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t*
 // the tile above the window.  The candidates are staged in LDS in order, so that the slot is
 // written with full wavefronts; candidates inside the histogram bins of positions k and k+1 are
 // also counted by their next kSel2Bits key bits (second selection level, one histogram per tile).
-template <bool MAG>
+template <bool MAG, bool HIST2 = true>
 __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     const float* __restrict__ x, const RowSel* __restrict__ sel, uint32_t* __restrict__ keys_out,
     uint32_t* __restrict__ idx_out, uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove,
@@ -419,8 +419,9 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
   __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
   __shared__ uint32_t kbuf[kTile];
   __shared__ uint32_t ibuf[kTile];
-  __shared__ uint32_t h2[2 * kSel2Bins];
-  for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads) h2[i] = 0;
+  __shared__ uint32_t h2[HIST2 ? 2 * kSel2Bins : 1];
+  if (HIST2)
+    for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads) h2[i] = 0;
   const int64_t row = blockIdx.x / tiles;
   const int tile = blockIdx.x % tiles;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
@@ -475,18 +476,22 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     const uint32_t key = kbuf[j];
     keys_out[row_base + tile_first + j] = key;
     idx_out[row_base + tile_first + j] = ibuf[j];
-    const uint32_t top = key >> kSelShift;
-    const uint32_t sub = (key >> (kSelShift - kSel2Bits)) & (kSel2Bins - 1);
-    if (top == bin_k) atomicAdd(&h2[sub], 1u);
-    if (top == bin_k1) atomicAdd(&h2[kSel2Bins + sub], 1u);
+    if (HIST2) {
+      const uint32_t top = key >> kSelShift;
+      const uint32_t sub = (key >> (kSelShift - kSel2Bits)) & (kSel2Bins - 1);
+      if (top == bin_k) atomicAdd(&h2[sub], 1u);
+      if (top == bin_k1) atomicAdd(&h2[kSel2Bins + sub], 1u);
+    }
   }
   if (threadIdx.x == 0) {
     tcnt[row * tiles + tile] = total;
     tabove[row * tiles + tile] = above;
   }
-  __syncthreads();
-  uint32_t* dst = tile_hist2 + (row * tiles + tile) * (2 * kSel2Bins);
-  for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads) dst[i] = h2[i];
+  if (HIST2) {
+    __syncthreads();
+    uint32_t* dst = tile_hist2 + (row * tiles + tile) * (2 * kSel2Bins);
+    for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads) dst[i] = h2[i];
+  }
 }
 
 // Second compaction, in place, of every tile's slot to the refined window; adds the elements
@@ -684,7 +689,60 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
                      B.keys_b, B.idx_b, B.keys_a, B.idx_a, n, tiles);
 }
 
+// The candidate selection of the wide route: the same levels, but the candidates stay in the
+// per-tile slots of the "b" arrays (B.tcnt / B.tabove per tile); the workgroup that sorts and
+// solves a row collects them itself.  Sums of partial histograms are only launched when there are
+// more partials than the consumers add up themselves; `refine`: second histogram level.
+template <bool MAG>
+void wide_select(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& R, bool cubic,
+                 bool refine, const SortBuffers& B, hipStream_t st) {
+  const int tiles = int((n + kTile - 1) / kTile);
+  const unsigned blocks = unsigned(rows * tiles);
+  const int parts = sel_parts(rows, n);
+  const int64_t span = sel_span(rows, n);
+  hipLaunchKernelGGL((select_hist_kernel<MAG>), dim3(unsigned(rows * parts)), dim3(kSelThreads), 0,
+                     st, x, B.hpart, n, span, parts);
+  if (parts > kSelSlices) {
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(unsigned(rows * kSelSlices * (kSelBins / 128))),
+                       dim3(kThreads), 0, st, B.hpart, B.bins, parts, kSelSlices, kSelBins);
+    hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
+                       B.bins, B.sel, k, kSelSlices, R, cubic);
+  } else {
+    hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
+                       B.hpart, B.sel, k, parts, R, cubic);
+  }
+  if (!refine) {
+    hipLaunchKernelGGL((select_compact_kernel<MAG, false>), dim3(blocks), dim3(kThreads), 0, st, x,
+                       B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles);
+    return;
+  }
+  hipLaunchKernelGGL((select_compact_kernel<MAG, true>), dim3(blocks), dim3(kThreads), 0, st, x,
+                     B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles);
+  if (tiles > kSelSlices) {
+    hipLaunchKernelGGL(reduce_partials_kernel,
+                       dim3(unsigned(rows * kSelSlices * (2 * kSel2Bins / 128))), dim3(kThreads), 0,
+                       st, B.tile_hist2, B.bins2, tiles, kSelSlices, 2 * kSel2Bins);
+    hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
+                       B.bins2, B.sel, kSelSlices, R, cubic);
+  } else {
+    hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
+                       B.tile_hist2, B.sel, tiles, R, cubic);
+  }
+  hipLaunchKernelGGL(select_recompact_kernel, dim3(blocks), dim3(kThreads), 0, st, B.sel, B.keys_b,
+                     B.idx_b, B.tcnt, B.tabove, n, tiles);
+}
+
 }  // namespace
+
+int launch_wide_select(bool mag, int pc, bool refine, const float* x, int64_t rows, int64_t n,
+                       int64_t k, const Reg& R, const SortBuffers& B, hipStream_t st) {
+  const int64_t tiles = radix_tiles(n);
+  if (k < 1 || k >= n) return -1;
+  if (rows * tiles > 0x7fffffffLL || rows * kRadix > 0x7fffffffLL) return -1;
+  if (mag) wide_select<true>(x, rows, n, k, R, pc == kP43, refine, B, st);
+  else wide_select<false>(x, rows, n, k, R, pc == kP43, refine, B, st);
+  return 0;
+}
 
 int radix_tiles(int64_t n) { return int((n + kTile - 1) / kTile); }
 

@@ -28,7 +28,7 @@ import contextlib
 def long_rows_route(gpu, mode):
     """Run the body with rows above 1024 elements on the named route ("auto", "select", "sort")."""
     code = {"auto": gpu.TOPK_LONG_ROWS_AUTO, "select": gpu.TOPK_LONG_ROWS_SELECT,
-            "sort": gpu.TOPK_LONG_ROWS_SORT}[mode]
+            "sort": gpu.TOPK_LONG_ROWS_SORT, "wide": gpu.TOPK_LONG_ROWS_WIDE}[mode]
     gpu.set_route(gpu.TOPK_ROUTE_LONG_ROWS, code)
     try:
         yield
@@ -169,13 +169,13 @@ def test_long_rows_kinks_ties_and_full_sort_agreement(gpu, oracle):
         run_case(gpu, oracle, op, x, t, k, p, lam, check_perm=False)
         jvpf = gpu.topk_mask_jvp if op == "mask" else gpu.topkmag_jvp
         o_def, j_def = (host(a) for a in jvpf(xd, td, k, p, lam))
-        for mode in ("select", "sort"):
+        for mode in ("select", "sort", "wide"):
             with long_rows_route(gpu, mode):
                 o_alt, j_alt = (host(a) for a in jvpf(xd, td, k, p, lam))
             assert np.array_equal(o_def, o_alt) and np.array_equal(j_def, j_alt), (mode, op, p, k, lam)
 
 
-@pytest.mark.parametrize("mode", ["auto", "select"])
+@pytest.mark.parametrize("mode", ["auto", "select", "wide"])
 def test_degenerate_windows(gpu, oracle, mode):
     """Rows whose candidate window degenerates: constant rows (one key), two values, windows that
     touch +0 / -0, rows of mostly zeros where s_k itself is zero."""
@@ -197,7 +197,7 @@ def test_degenerate_windows(gpu, oracle, mode):
             run_case(gpu, oracle, "mag", x, t, k, P2, 0.1, check_perm=False)
 
 
-@pytest.mark.parametrize("mode", ["select", "sort"])
+@pytest.mark.parametrize("mode", ["select", "sort", "wide"])
 def test_long_rows_multi_launch_paths(gpu, oracle, mode):
     """The multi-launch paths (candidate selection + sort of the candidates; full sort), which by
     default only rows above 131072 elements take, on sizes the oracle finishes quickly."""
