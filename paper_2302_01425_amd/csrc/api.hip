@@ -147,14 +147,14 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   const LongMode mode = long_mode();
   // k = 0 and k = n pool nothing and read no sorted value: no sort at all
   const bool trivial = (k == 0 || k == n);
-  // Few long rows: one workgroup per row would leave most of the chip idle, so the streaming steps
-  // of a row are spread over many workgroups (separate launches) and only the sort + solve of its
-  // candidates is left to one.  Also every row above kMediumRowMax elements.
-  const bool few_long_rows = rows <= 96 && n >= 16384;
-  if (!trivial && (mode == kWide || (mode == kAuto && (n > topk::kMediumRowMax || few_long_rows)))) {
+  // Rows above kMediumRowMax elements: the streaming steps of a row are spread over many
+  // workgroups (separate launches) and only the sort + solve of its candidates is left to one.
+  if (!trivial && (mode == kWide || (mode == kAuto && n > topk::kMediumRowMax))) {
     const bool refine = n > (int64_t(1) << 18);
-    if (topk::launch_wide_select(mag, pc, refine, x, rows, n, k, R, B, st) != 0) return TOPK_ERR_INVALID;
-    if (topk::launch_wide_finish(mag, pc, B, need_jvp ? tangent : nullptr, rows, n, k, R, st) != 0)
+    if (topk::launch_wide_select(mag, pc, refine, x, need_jvp ? tangent : nullptr, rows, n, k, R, B,
+                                 st) != 0)
+      return TOPK_ERR_INVALID;
+    if (topk::launch_wide_finish(mag, pc, B, need_jvp, rows, n, k, R, st) != 0)
       return TOPK_ERR_INVALID;
     if (topk::launch_wide_dense(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
                                 need_jvp ? jvp : nullptr, rows, n, R, st) != 0)

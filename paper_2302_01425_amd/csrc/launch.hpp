@@ -137,9 +137,11 @@ int launch_candidate_lists(bool mag, int pc, const float* x, int64_t rows, int64
 // row then collects them, sorts their keys, grows the block and adds up the tangent over it
 // (B.info[row]: gamma, d gamma and the block's value window); one dense pass computes every
 // output from its element's value.  refine: second histogram level (worth it for very long rows).
-int launch_wide_select(bool mag, int pc, bool refine, const float* x, int64_t rows, int64_t n,
-                       int64_t k, const Reg& R, const SortBuffers& B, hipStream_t st);
-int launch_wide_finish(bool mag, int pc, const SortBuffers& B, const float* tangent, int64_t rows,
+// tangent (may be null): the candidates carry their tangent as payload instead of their index.
+int launch_wide_select(bool mag, int pc, bool refine, const float* x, const float* tangent,
+                       int64_t rows, int64_t n, int64_t k, const Reg& R, const SortBuffers& B,
+                       hipStream_t st);
+int launch_wide_finish(bool mag, int pc, const SortBuffers& B, bool want_jvp, int64_t rows,
                        int64_t n, int64_t k, const Reg& R, hipStream_t st);
 int launch_wide_dense(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
                       float* out, float* jvp, int64_t rows, int64_t n, const Reg& R,

@@ -411,11 +411,15 @@ __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t*
 // the tile above the window.  The candidates are staged in LDS in order, so that the slot is
 // written with full wavefronts; candidates inside the histogram bins of positions k and k+1 are
 // also counted by their next kSel2Bits key bits (second selection level, one histogram per tile).
-template <bool MAG, bool HIST2 = true>
+// TAU: the payload of a candidate is not its index but the bits of its tangent in sorted-value
+// coordinates (t, or sign(x) t for the magnitude operator; 0 without a tangent): what the wide
+// route needs, whose outputs are computed from values.
+template <bool MAG, bool HIST2 = true, bool TAU = false>
 __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     const float* __restrict__ x, const RowSel* __restrict__ sel, uint32_t* __restrict__ keys_out,
     uint32_t* __restrict__ idx_out, uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove,
-    uint32_t* __restrict__ tile_hist2, int64_t n, int tiles) {
+    uint32_t* __restrict__ tile_hist2, int64_t n, int tiles,
+    const float* __restrict__ tangent = nullptr) {
   __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
   __shared__ uint32_t kbuf[kTile];
   __shared__ uint32_t ibuf[kTile];
@@ -468,7 +472,13 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     if (pos[i] != 0xffffffffu) {
       const int64_t e = tile_first + chunk + i * kWave + lane;
       kbuf[before + pos[i]] = first_key<MAG>(val[i]);
-      ibuf[before + pos[i]] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(val[i]) >> 31)) : uint32_t(e);
+      if (TAU) {
+        float t = tangent != nullptr ? tangent[row_base + e] : 0.0f;
+        if (MAG) t = val[i] == 0.0f ? 0.0f : (val[i] < 0.0f ? -t : t);
+        ibuf[before + pos[i]] = __float_as_uint(t);
+      } else {
+        ibuf[before + pos[i]] = MAG ? ((uint32_t(e) << 1) | (__float_as_uint(val[i]) >> 31)) : uint32_t(e);
+      }
     }
   }
   __syncthreads();
@@ -496,9 +506,13 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
 
 // Second compaction, in place, of every tile's slot to the refined window; adds the elements
 // that fall above it to the tile's count of elements above.
+// TAU: the surviving candidates' index payloads are replaced by tangent bits (see
+// select_compact_kernel); MAG says how the payload encodes the index.
+template <bool TAU = false, bool MAG = false>
 __global__ __launch_bounds__(kThreads) void select_recompact_kernel(
     const RowSel* __restrict__ sel, uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
-    uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove, int64_t n, int tiles) {
+    uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove, int64_t n, int tiles,
+    const float* __restrict__ tangent = nullptr) {
   __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
   const int64_t row = blockIdx.x / tiles;
   const int tile = blockIdx.x % tiles;
@@ -538,7 +552,17 @@ __global__ __launch_bounds__(kThreads) void select_recompact_kernel(
   for (int i = 0; i < kItems; ++i) {
     if (pos[i] != 0xffffffffu) {
       keys[slot + before + pos[i]] = key[i];
-      idx[slot + before + pos[i]] = id[i];
+      uint32_t payload = id[i];
+      if (TAU) {
+        float t = 0.0f;
+        if (tangent != nullptr) {
+          t = tangent[row * n + (MAG ? (id[i] >> 1) : id[i])];
+          // the key of |x| = 0 is that of +0.0: sign(0) = 0
+          if (MAG) t = key[i] == 0x7fffffffu ? 0.0f : ((id[i] & 1u) ? -t : t);
+        }
+        payload = __float_as_uint(t);
+      }
+      idx[slot + before + pos[i]] = payload;
     }
   }
   if (threadIdx.x == 0) {
@@ -681,8 +705,8 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
                      B.tile_hist2, B.bins2, tiles, slices2, 2 * kSel2Bins);
   hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
                      B.bins2, B.sel, slices2, R, cubic);
-  hipLaunchKernelGGL(select_recompact_kernel, dim3(blocks), dim3(kThreads), 0, st, B.sel, B.keys_b,
-                     B.idx_b, B.tcnt, B.tabove, n, tiles);
+  hipLaunchKernelGGL((select_recompact_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, st,
+                     B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles, nullptr);
   hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
                      B.tabove, B.toff, B.sel, tiles);
   hipLaunchKernelGGL(select_gather_kernel, dim3(blocks), dim3(kThreads), 0, st, B.tcnt, B.toff,
@@ -694,8 +718,8 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
 // solves a row collects them itself.  Sums of partial histograms are only launched when there are
 // more partials than the consumers add up themselves; `refine`: second histogram level.
 template <bool MAG>
-void wide_select(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& R, bool cubic,
-                 bool refine, const SortBuffers& B, hipStream_t st) {
+void wide_select(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
+                 const Reg& R, bool cubic, bool refine, const SortBuffers& B, hipStream_t st) {
   const int tiles = int((n + kTile - 1) / kTile);
   const unsigned blocks = unsigned(rows * tiles);
   const int parts = sel_parts(rows, n);
@@ -712,12 +736,13 @@ void wide_select(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& 
                        B.hpart, B.sel, k, parts, R, cubic);
   }
   if (!refine) {
-    hipLaunchKernelGGL((select_compact_kernel<MAG, false>), dim3(blocks), dim3(kThreads), 0, st, x,
-                       B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles);
+    hipLaunchKernelGGL((select_compact_kernel<MAG, false, true>), dim3(blocks), dim3(kThreads), 0,
+                       st, x, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles,
+                       tangent);
     return;
   }
-  hipLaunchKernelGGL((select_compact_kernel<MAG, true>), dim3(blocks), dim3(kThreads), 0, st, x,
-                     B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles);
+  hipLaunchKernelGGL((select_compact_kernel<MAG, true, false>), dim3(blocks), dim3(kThreads), 0, st,
+                     x, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles, nullptr);
   if (tiles > kSelSlices) {
     hipLaunchKernelGGL(reduce_partials_kernel,
                        dim3(unsigned(rows * kSelSlices * (2 * kSel2Bins / 128))), dim3(kThreads), 0,
@@ -728,19 +753,20 @@ void wide_select(const float* x, int64_t rows, int64_t n, int64_t k, const Reg& 
     hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
                        B.tile_hist2, B.sel, tiles, R, cubic);
   }
-  hipLaunchKernelGGL(select_recompact_kernel, dim3(blocks), dim3(kThreads), 0, st, B.sel, B.keys_b,
-                     B.idx_b, B.tcnt, B.tabove, n, tiles);
+  hipLaunchKernelGGL((select_recompact_kernel<true, MAG>), dim3(blocks), dim3(kThreads), 0, st,
+                     B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles, tangent);
 }
 
 }  // namespace
 
-int launch_wide_select(bool mag, int pc, bool refine, const float* x, int64_t rows, int64_t n,
-                       int64_t k, const Reg& R, const SortBuffers& B, hipStream_t st) {
+int launch_wide_select(bool mag, int pc, bool refine, const float* x, const float* tangent,
+                       int64_t rows, int64_t n, int64_t k, const Reg& R, const SortBuffers& B,
+                       hipStream_t st) {
   const int64_t tiles = radix_tiles(n);
   if (k < 1 || k >= n) return -1;
   if (rows * tiles > 0x7fffffffLL || rows * kRadix > 0x7fffffffLL) return -1;
-  if (mag) wide_select<true>(x, rows, n, k, R, pc == kP43, refine, B, st);
-  else wide_select<false>(x, rows, n, k, R, pc == kP43, refine, B, st);
+  if (mag) wide_select<true>(x, tangent, rows, n, k, R, pc == kP43, refine, B, st);
+  else wide_select<false>(x, tangent, rows, n, k, R, pc == kP43, refine, B, st);
   return 0;
 }
 
