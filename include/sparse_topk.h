@@ -275,7 +275,9 @@ int topk_set_workspace(void* dev_ptr, size_t bytes);
  *                               selection, sorted (key, index) lists and scatter, for every such
  *                               row), _SORT (rows sorted completely), _WIDE (multi-launch
  *                               selection, key-only sort and outputs by value: what AUTO takes
- *                               for few or very long rows)
+ *                               for rows above 131072 elements), _ONE_LAUNCH_INDEXED (up to 131072
+ *                               elements: the one-launch kernel that sorts (key, index) pairs,
+ *                               which AUTO only takes up to 8192 elements)
  *   TOPK_ROUTE_SHORT_ROW_LANES  lanes of a wavefront that share a short row: 0 (by shape) or a
  *                               power of two up to 64 (clamped to what the row length allows)
  *   TOPK_ROUTE_SHORT_ROW_KERNEL for rows of up to 128 elements: TOPK_SHORT_ROW_KERNEL_AUTO (dense
@@ -292,6 +294,7 @@ int topk_set_workspace(void* dev_ptr, size_t bytes);
 #define TOPK_LONG_ROWS_SELECT 1
 #define TOPK_LONG_ROWS_SORT 2
 #define TOPK_LONG_ROWS_WIDE 3
+#define TOPK_LONG_ROWS_ONE_LAUNCH_INDEXED 4
 #define TOPK_SHORT_ROW_KERNEL_AUTO 0
 #define TOPK_SHORT_ROW_KERNEL_INDEXED 1
 #define TOPK_SHORT_ROW_KERNEL_GENERAL 2

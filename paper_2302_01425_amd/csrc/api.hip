@@ -51,7 +51,8 @@ bool is_long(int64_t n) { return n > TOPK_SHORT_ROW_MAX; }
 // topk_set_route the multi-launch selection path can be chosen for every such row, or a complete
 // sort of the rows (same results; for tests and comparisons).
 enum LongMode { kAuto = TOPK_LONG_ROWS_AUTO, kSelect = TOPK_LONG_ROWS_SELECT,
-                kFullSort = TOPK_LONG_ROWS_SORT, kWide = TOPK_LONG_ROWS_WIDE };
+                kFullSort = TOPK_LONG_ROWS_SORT, kWide = TOPK_LONG_ROWS_WIDE,
+                kOneLaunchIndexed = TOPK_LONG_ROWS_ONE_LAUNCH_INDEXED };
 LongMode long_mode() { return static_cast<LongMode>(topk::routes().long_rows); }
 
 struct Layout {
@@ -147,9 +148,9 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   const LongMode mode = long_mode();
   // k = 0 and k = n pool nothing and read no sorted value: no sort at all
   const bool trivial = (k == 0 || k == n);
-  // Rows above kMediumRowMax elements: the streaming steps of a row are spread over many
-  // workgroups (separate launches) and only the sort + solve of its candidates is left to one.
-  if (!trivial && (mode == kWide || (mode == kAuto && n > topk::kMediumRowMax))) {
+  // Rows above 32768 elements: the streaming steps of a row are spread over many workgroups
+  // (separate launches) and only the sort + solve of its candidates is left to one.
+  if (!trivial && (mode == kWide || (mode == kAuto && n > 32768))) {
     const bool refine = n > (int64_t(1) << 18);
     if (topk::launch_wide_select(mag, pc, refine, x, need_jvp ? tangent : nullptr, rows, n, k, R, B,
                                  st) != 0)
@@ -161,10 +162,16 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
       return TOPK_ERR_INVALID;
     return finish();
   }
-  if (mode == kAuto && n <= topk::kMediumRowMax) {
-    if (topk::launch_medium_rows(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
-                                 need_jvp ? jvp : nullptr, rows, n, k, R, st) != 0)
-      return TOPK_ERR_INVALID;
+  if ((mode == kAuto || mode == kOneLaunchIndexed) && n <= topk::kMediumRowMax) {
+    // one launch, one workgroup per row; above 8192 elements the kernel that orders values only
+    const bool by_value = mode == kAuto && n > 8192 && n <= 32768;
+    const int lrc = by_value ? topk::launch_medium_rows2(mag, pc, B, x, need_jvp ? tangent : nullptr,
+                                                         out, need_jvp ? jvp : nullptr, rows, n, k,
+                                                         R, st)
+                             : topk::launch_medium_rows(mag, pc, B, x, need_jvp ? tangent : nullptr,
+                                                        out, need_jvp ? jvp : nullptr, rows, n, k,
+                                                        R, st);
+    if (lrc != 0) return TOPK_ERR_INVALID;
     return finish();
   }
   const bool selected = !trivial && mode != kFullSort;
@@ -261,7 +268,8 @@ int topk_set_route(int which, int value) {
   topk::Routes& r = topk::routes();
   switch (which) {
     case TOPK_ROUTE_LONG_ROWS:
-      if (value < TOPK_LONG_ROWS_AUTO || value > TOPK_LONG_ROWS_WIDE) return TOPK_ERR_INVALID;
+      if (value < TOPK_LONG_ROWS_AUTO || value > TOPK_LONG_ROWS_ONE_LAUNCH_INDEXED)
+        return TOPK_ERR_INVALID;
       r.long_rows = value;
       return TOPK_OK;
     case TOPK_ROUTE_SHORT_ROW_LANES:

@@ -127,6 +127,12 @@ int launch_medium_rows(bool mag, int pc, const SortBuffers& B, const float* x, c
                        float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
                        hipStream_t st);
 
+// The same for rows of 8193 .. kMediumRowMax elements with dense outputs computed from values:
+// keys-only sort and block growth in LDS, no permutation (medium_rows2.hip).
+int launch_medium_rows2(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
+                        float* out, float* jvp, int64_t rows, int64_t n, int64_t k, const Reg& R,
+                        hipStream_t st);
+
 // Long rows without a full sort (0 < k < n): two histogram levels of the leading key bits -> key
 // window around positions k, k+1 that holds every element able to pool -> those candidates, in
 // index order, as a dense list per row in the "a" arrays; B.sel[row] = {window, length, above}.

@@ -115,7 +115,8 @@ __global__ __launch_bounds__(kThreads) void wide_dense_kernel(
   for (int i = 0; i < 8; ++i) {
     const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
     xv[i] = e < n ? load_stream(x_all + base + e) : 0.0f;
-    tv[i] = (e < n && jvp != nullptr) ? load_stream(tangent + e) : 0.0f;
+    // the mask's JVP is zero outside the block: only the magnitude operator streams the tangent
+    tv[i] = (MAG && e < n && jvp != nullptr) ? load_stream(tangent + e) : 0.0f;
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void wide_dense_kernel(
       y = float(P::y_in_block(c, ri.gamma, R));
       if (MAG) y = (y == 0.0f) ? 0.0f : (neg ? -y : y);
       if (jvp != nullptr) {
-        double t = double(tv[i]);
+        double t = double(MAG ? tv[i] : tangent[e]);
         if (neg) t = -t;
         if (MAG && v == 0.0f) t = 0.0;
         float df = float(P::hess(c, ri.gamma, R) * (t - ri.dgamma));

@@ -17,6 +17,7 @@
 #include "common.hpp"
 #include "launch.hpp"
 #include "radix.hpp"
+#include "wave.hpp"
 
 namespace topk {
 namespace {
@@ -251,35 +252,47 @@ constexpr int kSelShift = 32 - kSelBits;
 constexpr int kSelThreads = 1024;
 constexpr int kSelChunk = kSelThreads * 16;
 
+// kHistCopies copies of the histogram, chosen by the lane: lanes that hit the same bin in one
+// instruction (frequent: a handful of bins hold most of a row) then mostly go to different words,
+// and the copies start 8 banks apart, so that those words also lie in different banks.
+constexpr int kHistCopies = 4;
+constexpr int kHistStride = kSelBins + 8;
+
 template <bool MAG>
 __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const float* __restrict__ x,
                                                                   uint32_t* __restrict__ partial,
                                                                   int64_t n, int64_t span,
                                                                   int parts) {
-  __shared__ uint32_t h[kSelBins];
+  __shared__ uint32_t h[kHistCopies * kHistStride];
   const int64_t row = blockIdx.x / parts;
   const int part = blockIdx.x % parts;
   const int64_t first = int64_t(part) * span;
   const int64_t last = (first + span < n) ? first + span : n;
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) h[i] = 0;
+  for (int i = threadIdx.x; i < kHistCopies * kHistStride; i += kSelThreads) h[i] = 0;
   __syncthreads();
+  uint32_t* mine = h + (threadIdx.x & (kHistCopies - 1)) * kHistStride;
   const float* xr = x + row * n;
   for (int64_t c0 = first; c0 < last; c0 += kSelChunk) {
     float v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int64_t e = c0 + int64_t(i) * kSelThreads + threadIdx.x;
-      v[i] = e < last ? xr[e] : 0.0f;
+      v[i] = e < last ? load_stream(xr + e) : 0.0f;
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int64_t e = c0 + int64_t(i) * kSelThreads + threadIdx.x;
-      if (e < last) atomicAdd(&h[first_key<MAG>(v[i]) >> kSelShift], 1u);
+      if (e < last) atomicAdd(&mine[first_key<MAG>(v[i]) >> kSelShift], 1u);
     }
   }
   __syncthreads();
   uint32_t* dst = partial + (row * parts + part) * kSelBins;
-  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) dst[i] = h[i];
+  for (int i = threadIdx.x; i < kSelBins; i += kSelThreads) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int q = 0; q < kHistCopies; ++q) c += h[q * kHistStride + i];
+    dst[i] = c;
+  }
 }
 
 // First stage of the sum of partial histograms: src[row][parts][counters] ->
@@ -330,12 +343,24 @@ __global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t*
   static_assert(kPerThread % 4 == 0, "bins are read as uint4");
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) c[i] = 0;
-  for (int g = 0; g < gcopies; ++g) {
-    const uint4* src = reinterpret_cast<const uint4*>(b + g * kSelBins + threadIdx.x * kPerThread);
+  for (int g0 = 0; g0 < gcopies; g0 += 4) {            // four slices' loads in flight
+    uint4 v[4][kPerThread / 4];
 #pragma unroll
-    for (int i = 0; i < kPerThread / 4; ++i) {
-      const uint4 v = src[i];
-      c[4 * i] += v.x; c[4 * i + 1] += v.y; c[4 * i + 2] += v.z; c[4 * i + 3] += v.w;
+    for (int q = 0; q < 4; ++q) {
+      const uint4* src = reinterpret_cast<const uint4*>(
+          b + (g0 + q < gcopies ? g0 + q : g0) * kSelBins + threadIdx.x * kPerThread);
+#pragma unroll
+      for (int i = 0; i < kPerThread / 4; ++i) v[q][i] = src[i];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (g0 + q < gcopies) {
+#pragma unroll
+        for (int i = 0; i < kPerThread / 4; ++i) {
+          c[4 * i] += v[q][i].x; c[4 * i + 1] += v[q][i].y;
+          c[4 * i + 2] += v[q][i].z; c[4 * i + 3] += v[q][i].w;
+        }
+      }
     }
   }
 #pragma unroll
@@ -381,17 +406,28 @@ __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t*
   const int64_t row = blockIdx.x;
   if (threadIdx.x < 2) found[threadIdx.x] = 0;       // (stays 0 only for rows with NaNs)
   const uint32_t rank[2] = {sel[row].rank_k, sel[row].rank_k1};
+  uint32_t cs[2] = {0u, 0u};
+  {
+    const uint32_t* src = bins2 + row * slices * 2 * kSel2Bins + threadIdx.x;
+    int sl = 0;
+    for (; sl + 7 < slices; sl += 8) {                   // sixteen loads in flight
+      uint32_t a[8][2];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        a[q][0] = src[((sl + q) * 2 + 0) * kSel2Bins];
+        a[q][1] = src[((sl + q) * 2 + 1) * kSel2Bins];
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) { cs[0] += a[q][0]; cs[1] += a[q][1]; }
+    }
+    for (; sl < slices; ++sl) {
+      cs[0] += src[(sl * 2 + 0) * kSel2Bins];
+      cs[1] += src[(sl * 2 + 1) * kSel2Bins];
+    }
+  }
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    uint32_t c = 0;
-    const uint32_t* src = bins2 + (row * slices * 2 + h) * kSel2Bins + threadIdx.x;
-    int sl = 0;
-    for (; sl + 3 < slices; sl += 4) {                   // four loads in flight
-      const uint32_t a0 = src[(sl + 0) * 2 * kSel2Bins], a1 = src[(sl + 1) * 2 * kSel2Bins];
-      const uint32_t a2 = src[(sl + 2) * 2 * kSel2Bins], a3 = src[(sl + 3) * 2 * kSel2Bins];
-      c += a0 + a1 + a2 + a3;
-    }
-    for (; sl < slices; ++sl) c += src[sl * 2 * kSel2Bins];
+    const uint32_t c = cs[h];
     const uint32_t run = block_exclusive_scan(c, wave_tot, nullptr);
     if (run < rank[h] && rank[h] <= run + c) found[h] = threadIdx.x;
   }
@@ -467,13 +503,21 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     total += wave_cand[q];
     above += wave_above[q];
   }
+  float tq[TAU ? kItems : 1];              // the candidates' tangents: all loads in flight at once
+  if (TAU) {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+      const int64_t e = tile_first + chunk + i * kWave + lane;
+      tq[i] = (tangent != nullptr && pos[i] != 0xffffffffu) ? tangent[row_base + e] : 0.0f;
+    }
+  }
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
     if (pos[i] != 0xffffffffu) {
       const int64_t e = tile_first + chunk + i * kWave + lane;
       kbuf[before + pos[i]] = first_key<MAG>(val[i]);
       if (TAU) {
-        float t = tangent != nullptr ? tangent[row_base + e] : 0.0f;
+        float t = tq[TAU ? i : 0];
         if (MAG) t = val[i] == 0.0f ? 0.0f : (val[i] < 0.0f ? -t : t);
         ibuf[before + pos[i]] = __float_as_uint(t);
       } else {
@@ -772,10 +816,10 @@ int launch_wide_select(bool mag, int pc, bool refine, const float* x, const floa
 
 int radix_tiles(int64_t n) { return int((n + kTile - 1) / kTile); }
 
-// The first histogram level: about 512 workgroups of 1024 threads in all, each with a span of
-// at least one chunk of its row.
+// The first histogram level: about 256 workgroups of 1024 threads in all (one per compute unit),
+// each with a span of at least one chunk of its row.
 int64_t sel_span(int64_t rows, int64_t n) {
-  int64_t span = (n * rows + 511) / 512;
+  int64_t span = (n * rows + 255) / 256;
   return (span + kSelChunk - 1) / kSelChunk * kSelChunk;
 }
 int sel_parts(int64_t rows, int64_t n) {

@@ -28,7 +28,8 @@ import contextlib
 def long_rows_route(gpu, mode):
     """Run the body with rows above 1024 elements on the named route ("auto", "select", "sort")."""
     code = {"auto": gpu.TOPK_LONG_ROWS_AUTO, "select": gpu.TOPK_LONG_ROWS_SELECT,
-            "sort": gpu.TOPK_LONG_ROWS_SORT, "wide": gpu.TOPK_LONG_ROWS_WIDE}[mode]
+            "sort": gpu.TOPK_LONG_ROWS_SORT, "wide": gpu.TOPK_LONG_ROWS_WIDE,
+            "indexed": gpu.TOPK_LONG_ROWS_ONE_LAUNCH_INDEXED}[mode]
     gpu.set_route(gpu.TOPK_ROUTE_LONG_ROWS, code)
     try:
         yield
@@ -169,7 +170,7 @@ def test_long_rows_kinks_ties_and_full_sort_agreement(gpu, oracle):
         run_case(gpu, oracle, op, x, t, k, p, lam, check_perm=False)
         jvpf = gpu.topk_mask_jvp if op == "mask" else gpu.topkmag_jvp
         o_def, j_def = (host(a) for a in jvpf(xd, td, k, p, lam))
-        for mode in ("select", "sort", "wide"):
+        for mode in ("select", "sort", "wide", "indexed"):
             with long_rows_route(gpu, mode):
                 o_alt, j_alt = (host(a) for a in jvpf(xd, td, k, p, lam))
             assert np.array_equal(o_def, o_alt) and np.array_equal(j_def, j_alt), (mode, op, p, k, lam)
