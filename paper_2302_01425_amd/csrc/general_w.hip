@@ -55,11 +55,13 @@ __device__ double block_root(double cnt, double W, double S1, double S2, double 
     if (F == 0.0) return x;
     if (F > 0.0) b = x; else a = x;
     const double D = (3.0 * cnt * x - 6.0 * S1) * x + 3.0 * S2 + (MAG ? R.lam3 * W : 0.0);
-    double xn = x - F / D;
+    const double dx = F / D;
+    // a step of rounding size ends the iteration before the bracket test: at the root the
+    // bracket end is x itself, and bisecting from there would throw the converged value away
+    if (fabs(dx) <= tol) return x - dx;
+    double xn = x - dx;
     if (!(xn > a && xn < b)) xn = 0.5 * (a + b);
-    const double step = fabs(xn - x);
     x = xn;
-    if (step <= tol) break;
   }
   return x;
 }

@@ -67,11 +67,14 @@ __device__ __forceinline__ double singleton_root_mag43(double s, const Reg& R) {
     const double F = u * u * u + R.lam3 * g;
     if (F == 0.0) return g;
     if (F > 0.0) b = g; else a = g;
-    double gn = g - F * recip(3.0 * u * u + R.lam3);
+    const double dg = F * recip(3.0 * u * u + R.lam3);
+    // a step of rounding size ends the iteration BEFORE the bracket test: at the root the bracket
+    // end is g itself, g - dg == g is then "outside", and the bisection that followed threw the
+    // converged value away (some forty more iterations to come back)
+    if (fabs(dg) <= tol) { g -= dg; break; }
+    double gn = g - dg;
     if (!(gn > a && gn < b)) gn = 0.5 * (a + b);
-    const double step = fabs(gn - g);
     g = gn;
-    if (step <= tol) break;
   }
   const double u = g - s;
   return g - (u * u * u + R.lam3 * g) * recip(3.0 * u * u + R.lam3);
@@ -171,11 +174,12 @@ struct Pool {
       if (F == 0.0) break;
       if (F > 0.0) b = x; else a = x;
       const double D = (3.0 * cnt * x - 6.0 * S.s1) * x + 3.0 * S.s2 + (MAG ? R.lam3 * m : 0.0);
-      double xn = x - F * recip(D);
+      const double dx = F * recip(D);
+      // (a step of rounding size ends the iteration before the bracket test, see above)
+      if (fabs(dx) <= tol) { x -= dx; break; }
+      double xn = x - dx;
       if (!(xn > a && xn < b)) xn = 0.5 * (a + b);   // also catches D <= 0 (inf / nan)
-      const double step = fabs(xn - x);
       x = xn;
-      if (step <= tol) break;
     }
     return x;
   }
