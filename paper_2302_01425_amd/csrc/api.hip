@@ -193,6 +193,12 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
 // kernels run on them into (out, jvp), an element-wise pass turns those into the results.
 size_t abs_scratch_bytes(int64_t rows, int64_t n) { return 2 * align_up(size_t(rows) * size_t(n) * 4); }
 
+// Rows of 3..128 elements: these operators run inside the short-row kernel and need no scratch
+// (unless another short-row kernel was asked for with topk_set_route).
+bool abs_fused(int64_t n) {
+  return n >= 3 && n <= 128 && topk::routes().short_kernel == TOPK_SHORT_ROW_KERNEL_AUTO;
+}
+
 int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int64_t rows,
                      int64_t n, int64_t k, double p, double lambda, float* out, float* jvp,
                      bool need_jvp, void* stream) {
@@ -203,6 +209,15 @@ int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int
   if (rows == 0) return TOPK_OK;
   if (x == nullptr || out == nullptr) return TOPK_ERR_NULL;
   if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
+  // rows of up to 128 elements: one fused kernel, no scratch
+  if (abs_fused(n)) {
+    begin();
+    const int frc = topk::launch_short_rows_fused_variant(
+        signed_mask ? 1 : 2, pc, x, need_jvp ? tangent : nullptr, out, need_jvp ? jvp : nullptr,
+        nullptr, 0.0, rows, int(n), int(k), make_reg(lambda), static_cast<hipStream_t>(stream));
+    if (frc == 0) return finish();
+    if (frc != -2) return TOPK_ERR_INVALID;
+  }
   // the whole workspace is checked before the first launch: two arrays here, then the mask's own
   const size_t skip = abs_scratch_bytes(rows, n);
   const size_t need = skip + (is_long(n) ? layout_for(rows, n).total : 0);
@@ -426,6 +441,17 @@ int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_
     const int rc = check_shape(rows, n, k, lambda);
     return rc != TOPK_OK ? rc : (p_code(p) < 0 ? TOPK_ERR_UNSUPPORTED_P : TOPK_ERR_NULL);
   }
+  if (rows > 0 && !is_long(n) && grad_out != nullptr && theta != nullptr &&
+      check_shape(rows, n, k, lambda) == TOPK_OK && p_code(p) >= 0) {
+    // rows of up to 128 elements: mask, loss and gradient in one kernel
+    const double p_ex = p_code(p) == topk::kP2 ? 2.0 : 4.0 / 3.0;
+    begin();
+    const int frc = topk::launch_short_rows_fused_variant(
+        3, p_code(p), theta, target, grad_out, nullptr, loss_out, lambda / p_ex, rows, int(n),
+        int(k), make_reg(lambda), static_cast<hipStream_t>(stream));
+    if (frc == 0) return finish();
+    if (frc != -2) return TOPK_ERR_INVALID;
+  }
   // the mask goes to grad_out, the reduction turns it into y - target
   const int rc = run_operator(false, theta, nullptr, rows, n, k, p, lambda, grad_out, nullptr, true,
                               false, stream);
@@ -475,7 +501,7 @@ size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p
   (void)p;
   if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_MASKED_VALUE) return 0;
   if (rows <= 0 || n < 1 || n >= (int64_t(1) << 30)) return 0;
-  const size_t own = (op == TOPK_OP_SIGNED_MASK || op == TOPK_OP_MASKED_VALUE)
+  const size_t own = ((op == TOPK_OP_SIGNED_MASK || op == TOPK_OP_MASKED_VALUE) && !abs_fused(n))
                          ? abs_scratch_bytes(rows, n) : 0;
   if (!is_long(n)) return own;
   return own + layout_for(rows, n).total;

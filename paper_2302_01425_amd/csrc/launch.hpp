@@ -96,6 +96,15 @@ int launch_short_rows_fast(int np, int lg, bool vec, bool mag, int pc, const flo
 int launch_short_rows_value(int np, int lg, bool vec, bool mag, int pc, const float* x,
                             const float* tangent, float* out, float* jvp, int64_t rows, int n,
                             int k, const Reg& R, hipStream_t st);
+int launch_short_rows_variant(int np, int lg, bool vec, int var, int pc, const float* x,
+                              const float* tangent, float* out, float* jvp, float* loss,
+                              double lam_over_p, int64_t rows, int n, int k, const Reg& R,
+                              hipStream_t st);
+// Operators built on the mask (var: 1 signed mask, 2 x o mask(|x|), 3 Fenchel-Young loss), fused
+// into the short-row kernel when a shape fits (-2 otherwise).
+int launch_short_rows_fused_variant(int var, int pc, const float* x, const float* tangent, float* out,
+                                    float* jvp, float* loss, double lam_over_p, int64_t rows, int n,
+                                    int k, const Reg& R, hipStream_t st);
 int launch_short_argsort_fast(int np, int lg, bool vec, const float* x, int32_t* perm,
                               int64_t rows, int n, hipStream_t st);
 int launch_short_rows_fast_sparse(int np, int lg, bool vec, int pc, const float* x, int64_t rows,

@@ -461,6 +461,26 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
   return -1;
 }
 
+// The operators built on the mask, fused into the value-ordering kernel of rows up to 128
+// elements (var: 1 signed mask, 2 x o mask(|x|), 3 Fenchel-Young loss with tangent = target and
+// out = gradient).  Returns -2 when no fused kernel fits the shape: the caller then runs the
+// mask kernels between element-wise passes.
+int launch_short_rows_fused_variant(int var, int pc, const float* x, const float* tangent, float* out,
+                                    float* jvp, float* loss, double lam_over_p, int64_t rows, int n,
+                                    int k, const Reg& R, hipStream_t st) {
+  if (!value_enabled()) return -2;
+  const bool vec = (n % 4 == 0) && aligned16(x) && aligned16(tangent) && aligned16(out) &&
+                   aligned16(jvp);
+  int np = 2;
+  while (np < n) np <<= 1;
+  if (np < 4 || np > 128) return -2;
+  // the kernel's shapes: 1..16 lanes per row with 4 or 8 elements each
+  int lg = pick_log_gl(np, rows);
+  if (lg > 4 || ((np >> lg) != 4 && (np >> lg) != 8)) lg = np >= 8 ? ilog2(np / 8) : 0;
+  return launch_short_rows_variant(np, lg, vec, var, pc, x, tangent, out, jvp, loss, lam_over_p,
+                                   rows, n, k, R, st);
+}
+
 int launch_short_rows_sparse(int pc, const float* x, int64_t rows, int n, int k, const Reg& R,
                              const SparseOut& sp, hipStream_t st) {
   const bool vec = (n % 4 == 0) && aligned16(x);

@@ -138,11 +138,26 @@ __device__ __forceinline__ void sort_listed(float* ls, int lr) {
 // float4 by float4).  FULL: additionally n == GL * E, so there is no padding and no bounds test.
 // MODE: 0 forward only, 1 JVP only, 2 forward + JVP.
 // SELECT: 1 <= k <= GL and k < n (checked by the launcher): order only the values above T.
-template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE, bool SELECT, int WPB>
+// VAR: what is made of the mask (MAG = false only; kVarPlain: the operator itself):
+//   kVarSigned  signed mask, phi = |x| (Sec. 4 on the OWL norm): the mask m of |x| with the
+//               tangent sign(x) t, then y = sign(x) min(m, cap), cap = grad r*(|x|): the truncation
+//               v >= 0 of Prop. 6 is active exactly where m > cap, and there dy = hess r*(|x|) t;
+//   kVarMasked  x o mask(|x|) (Sec. 7): y = x m, dy = t m + x J_m (sign(x) o t);
+//   kVarLoss    Fenchel-Young loss of Sec. 6 (MODE 0; `tangent` is the target t): out = y - t
+//               and loss[row] = sum_i y_i x_i - (lambda / p) y_i^p - x_i t_i, the maximisation
+//               form of Prop. 2 at its maximiser y.
+constexpr int kVarPlain = 0, kVarSigned = 1, kVarMasked = 2, kVarLoss = 3;
+
+template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE, bool SELECT, int WPB,
+          int VAR = kVarPlain>
 __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
     const float* __restrict__ x, const float* __restrict__ tangent, float* __restrict__ out,
     float* __restrict__ jvp, int64_t rows, int n, int k, Reg R, float inv_lambda32,
-    float inv_1pl32) {
+    float inv_1pl32, float* __restrict__ loss = nullptr, double lam_over_p = 0.0) {
+  static_assert(VAR == kVarPlain || !MAG, "the variants are built on the mask");
+  static_assert(VAR != kVarLoss || MODE == 0, "the loss is a forward quantity");
+  constexpr bool ABS = MAG || VAR == kVarSigned || VAR == kVarMasked;   // values ordered: |x|
+  constexpr bool LOSS = VAR == kVarLoss;
   using P = Pool<MAG, PC>;
   using C = SelCfg<GL, E>;
   constexpr int NP = C::NP, RS = C::RS;
@@ -164,11 +179,11 @@ __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
   // ---- load ------------------------------------------------------------------------------------
   float xin[E], tin[E];
   load_row<GL, E, VEC, true>(x, base, lr, nn, xin);
-  if (want_jvp) load_row<GL, E, VEC, true>(tangent, base, lr, nn, tin);
+  if (want_jvp || LOSS) load_row<GL, E, VEC, true>(tangent, base, lr, nn, tin);
   float v[E];                                        // the values that are ordered; padding -inf
 #pragma unroll
   for (int r = 0; r < E; ++r) {
-    const float a = MAG ? fabsf(xin[r]) : xin[r];
+    const float a = ABS ? fabsf(xin[r]) : xin[r];
     v[r] = (FULL || elem_of<GL, E, VEC>(lr, r) < nn) ? a : neg_inf();
   }
 
@@ -357,7 +372,7 @@ __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
 #pragma unroll
     for (int r = 0; r < E; ++r) {
       float t = tin[r];
-      if (MAG) {
+      if (ABS) {
         t = (__float_as_uint(xin[r]) >> 31) ? -t : t;
         t = (v[r] == 0.0f) ? 0.0f : t;               // sign(0) = 0
       }
@@ -409,33 +424,111 @@ __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
       if (MAG) dy = (dy == 0.0f || v[r] == 0.0f) ? 0.0f : (neg ? -dy : dy);
       jv[r] = dy;
     }
+    // ---- what the variants make of the mask (float32, element-wise) --------------------------------
+    if (VAR == kVarSigned) {
+      const float xv = xin[r];
+      const float sg = float((xv > 0.0f) - (xv < 0.0f));
+      const float u = v[r] * inv_lambda32;
+      const float cap = CUBIC ? u * u * u : u;
+      const bool clipped = yv[r] > cap;
+      if (want_jvp) {
+        const float hess = CUBIC ? 3.0f * u * u * inv_lambda32 : inv_lambda32;
+        float jm = clipped ? hess * tin[r] : sg * jv[r];
+        jv[r] = (jm == 0.0f) ? 0.0f : jm;
+      }
+      const float y = sg * (clipped ? cap : yv[r]);
+      yv[r] = (y == 0.0f) ? 0.0f : y;
+    } else if (VAR == kVarMasked) {
+      if (want_jvp) jv[r] = tin[r] * yv[r] + xin[r] * jv[r];
+      yv[r] = xin[r] * yv[r];
+    }
+  }
+  if (LOSS) {
+    double acc = 0.0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const bool real = FULL || elem_of<GL, E, VEC>(lr, r) < nn;
+      const double yd = double(yv[r]);
+      double yp = yd * yd;                           // y^p: p = 2, or the exact ends of p = 4/3
+      if (CUBIC && __any(yv[r] != 0.0f && yv[r] != 1.0f)) {
+        const double c = cbrt(yd);                   // y^(4/3), y in [0, 1]
+        yp = c * c * c * c;
+      }
+      if (real) acc += yd * double(xin[r]) - lam_over_p * yp - double(xin[r]) * double(tin[r]);
+      yv[r] = yv[r] - tin[r];                        // the gradient y - t
+    }
+    acc = group_sum_f64<GL>(acc);
+    if (valid && lr == 0) loss[row] = float(acc);
   }
   if (!valid) return;
   if (want_out) store_row<GL, E, VEC, true>(out, base, lr, nn, yv);
   if (want_jvp) store_row<GL, E, VEC, true>(jvp, base, lr, nn, jv);
 }
 
-template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE, bool SELECT, int WPB>
+template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE, bool SELECT, int WPB,
+          int VAR = kVarPlain>
 int launch_value_wpb(const float* x, const float* t, float* out, float* jvp, int64_t rows, int n,
-                     int k, const Reg& R, hipStream_t st) {
+                     int k, const Reg& R, hipStream_t st, float* loss = nullptr,
+                     double lam_over_p = 0.0) {
   using C = SelCfg<GL, E>;
   const int64_t waves = (rows + C::RPW - 1) / C::RPW;
   const int64_t blocks = (waves + WPB - 1) / WPB;
   if (blocks > 0x7fffffffLL) return -1;
   const float il = float(R.inv_lambda), i1 = float(R.inv_1pl);
-  hipLaunchKernelGGL((short_rows_value_kernel<GL, E, MAG, PC, VEC, FULL, MODE, SELECT, WPB>),
+  hipLaunchKernelGGL((short_rows_value_kernel<GL, E, MAG, PC, VEC, FULL, MODE, SELECT, WPB, VAR>),
                      dim3((unsigned)blocks), dim3(WPB * kWave), 0, st, x, t, out, jvp, rows, n, k, R,
-                     il, i1);
+                     il, i1, loss, lam_over_p);
   return 0;
 }
 
-template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE>
+template <int GL, int E, bool MAG, int PC, bool VEC, bool FULL, int MODE, int VAR = kVarPlain>
 int launch_value_mode(const float* x, const float* t, float* out, float* jvp, int64_t rows, int n,
-                      int k, const Reg& R, hipStream_t st) {
+                      int k, const Reg& R, hipStream_t st, float* loss = nullptr,
+                      double lam_over_p = 0.0) {
   constexpr int WPB = TOPK_VALUE_WPB;
   if (k >= 1 && k <= GL && k < n)
-    return launch_value_wpb<GL, E, MAG, PC, VEC, FULL, MODE, true, WPB>(x, t, out, jvp, rows, n, k, R, st);
-  return launch_value_wpb<GL, E, MAG, PC, VEC, FULL, MODE, false, WPB>(x, t, out, jvp, rows, n, k, R, st);
+    return launch_value_wpb<GL, E, MAG, PC, VEC, FULL, MODE, true, WPB, VAR>(x, t, out, jvp, rows, n,
+                                                                            k, R, st, loss, lam_over_p);
+  return launch_value_wpb<GL, E, MAG, PC, VEC, FULL, MODE, false, WPB, VAR>(x, t, out, jvp, rows, n,
+                                                                           k, R, st, loss, lam_over_p);
+}
+
+// the operators built on the mask (see VAR): forward, or forward + JVP (out is always written)
+template <int GL, int E, bool VEC, bool FULL>
+int launch_variant_shape2(int var, int pc, const float* x, const float* t, float* out, float* jvp,
+                          float* loss, double lam_over_p, int64_t rows, int n, int k, const Reg& R,
+                          hipStream_t st) {
+#define TOPK_VAR_CALL(PCV, M, V) \
+  return launch_value_mode<GL, E, false, PCV, VEC, FULL, M, V>(x, t, out, jvp, rows, n, k, R, st, loss, lam_over_p)
+  if (var == kVarLoss) {
+    if (pc == kP2) TOPK_VAR_CALL(kP2, 0, kVarLoss);
+    if (pc == kP43) TOPK_VAR_CALL(kP43, 0, kVarLoss);
+    return -2;
+  }
+  const bool with_jvp = jvp != nullptr;
+  if (var == kVarSigned) {
+    if (pc == kP2 && !with_jvp) TOPK_VAR_CALL(kP2, 0, kVarSigned);
+    if (pc == kP2) TOPK_VAR_CALL(kP2, 2, kVarSigned);
+    if (pc == kP43 && !with_jvp) TOPK_VAR_CALL(kP43, 0, kVarSigned);
+    if (pc == kP43) TOPK_VAR_CALL(kP43, 2, kVarSigned);
+  }
+  if (var == kVarMasked) {
+    if (pc == kP2 && !with_jvp) TOPK_VAR_CALL(kP2, 0, kVarMasked);
+    if (pc == kP2) TOPK_VAR_CALL(kP2, 2, kVarMasked);
+    if (pc == kP43 && !with_jvp) TOPK_VAR_CALL(kP43, 0, kVarMasked);
+    if (pc == kP43) TOPK_VAR_CALL(kP43, 2, kVarMasked);
+  }
+#undef TOPK_VAR_CALL
+  return -2;
+}
+
+template <int GL, int E, bool VEC>
+int launch_variant_shape(int var, int pc, const float* x, const float* t, float* out, float* jvp,
+                         float* loss, double lam_over_p, int64_t rows, int n, int k, const Reg& R,
+                         hipStream_t st) {
+  if (VEC && n == GL * E)
+    return launch_variant_shape2<GL, E, true, true>(var, pc, x, t, out, jvp, loss, lam_over_p, rows, n, k, R, st);
+  return launch_variant_shape2<GL, E, VEC, false>(var, pc, x, t, out, jvp, loss, lam_over_p, rows, n, k, R, st);
 }
 
 // mask: p = 2 and p = 4/3; magnitude: p = 2
@@ -488,6 +581,26 @@ int launch_short_rows_value(int np, int lg, bool vec, bool mag, int pc, const fl
   TOPK_VALUE_SHAPE(4, 4) TOPK_VALUE_SHAPE(4, 8) TOPK_VALUE_SHAPE(8, 4) TOPK_VALUE_SHAPE(8, 8)
   TOPK_VALUE_SHAPE(16, 4) TOPK_VALUE_SHAPE(16, 8)
 #undef TOPK_VALUE_SHAPE
+  return -2;
+}
+
+// The operators built on the mask, fused into the same kernel: var = 1 signed mask, 2 x o mask(|x|)
+// (tangent / jvp may be null: forward only), 3 Fenchel-Young loss (tangent = target, out = the
+// gradient y - target, loss[rows]).  Returns -2 when the shape is not one of the kernel's.
+int launch_short_rows_variant(int np, int lg, bool vec, int var, int pc, const float* x,
+                              const float* tangent, float* out, float* jvp, float* loss,
+                              double lam_over_p, int64_t rows, int n, int k, const Reg& R,
+                              hipStream_t st) {
+#define TOPK_VARIANT_SHAPE(GL, E)                                                               \
+  if (np == (GL) * (E) && lg == ilog2(GL))                                                      \
+    return vec ? launch_variant_shape<GL, E, true>(var, pc, x, tangent, out, jvp, loss,         \
+                                                   lam_over_p, rows, n, k, R, st)               \
+               : launch_variant_shape<GL, E, false>(var, pc, x, tangent, out, jvp, loss,        \
+                                                    lam_over_p, rows, n, k, R, st);
+  TOPK_VARIANT_SHAPE(1, 4) TOPK_VARIANT_SHAPE(1, 8) TOPK_VARIANT_SHAPE(2, 4) TOPK_VARIANT_SHAPE(2, 8)
+  TOPK_VARIANT_SHAPE(4, 4) TOPK_VARIANT_SHAPE(4, 8) TOPK_VARIANT_SHAPE(8, 4) TOPK_VARIANT_SHAPE(8, 8)
+  TOPK_VARIANT_SHAPE(16, 4) TOPK_VARIANT_SHAPE(16, 8)
+#undef TOPK_VARIANT_SHAPE
   return -2;
 }
 

@@ -468,7 +468,8 @@ def test_dykstra_iterations(gpu, oracle, n):
 
 
 # ---- the operators on |x|: signed mask (phi = |x|) and x o mask(|x|) --------------------------------
-@pytest.mark.parametrize("rows,n", [(1, 1), (37, 64), (5, 300), (3, 5000), (1, 200000)])
+@pytest.mark.parametrize("rows,n", [(1, 1), (129, 7), (70, 33), (37, 64), (9, 100), (50, 128),
+                                    (5, 300), (3, 5000), (1, 200000)])
 def test_signed_mask_and_masked_value(gpu, oracle, rows, n):
     r = np.random.default_rng(31 * n + rows)
     x = r.normal(size=(rows, n)).astype(np.float32)
@@ -580,7 +581,8 @@ def test_fenchel_young_loss(gpu, oracle):
     """Smooth top-k loss (Sec. 6) and its gradient against the oracle's value of f (computed from
     the minimisation form of Prop. 2, the library uses the maximisation form)."""
     r = np.random.default_rng(23)
-    for rows, n, k, lam in [(64, 10, 3, 0.5), (300, 100, 3, 1.0), (33, 1000, 5, 0.2), (4, 5000, 50, 0.3),
+    for rows, n, k, lam in [(64, 10, 3, 0.5), (17, 5, 4, 2.0), (1000, 64, 2, 1.0), (70, 128, 40, 3.0),
+                            (300, 100, 3, 1.0), (33, 1000, 5, 0.2), (4, 5000, 50, 0.3),
                             (2, 150000, 100, 0.5)]:
         x = (r.normal(size=(rows, n)) * 2).astype(np.float32)
         t = np.zeros((rows, n), dtype=np.float32)
@@ -648,6 +650,8 @@ def test_workspace_growth_keeps_captured_graphs_valid(gpu, oracle):
     t = r.normal(size=(3, 5000)).astype(np.float32)
     xd, td = dev(x), dev(t)
     out, jvp = torch.empty_like(xd), torch.empty_like(xd)
+    torch.cuda.synchronize()
+    gpu.set_workspace(None)            # whatever earlier tests of this process left registered
     gpu.topk_mask_jvp(xd, td, 200, P2, 0.3, out=out, jvp_out=jvp)      # sizes the workspace
     torch.cuda.synchronize()
     ref_o, ref_j = out.clone(), jvp.clone()
