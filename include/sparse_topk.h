@@ -286,11 +286,14 @@ int topk_set_workspace(void* dev_ptr, size_t bytes);
  *                               kernel that builds the permutation, as the compact output and
  *                               topk_argsort_desc always do), _GENERAL (the general short-row
  *                               kernel of rows up to TOPK_SHORT_ROW_MAX elements)
+ *   TOPK_ROUTE_GENERAL_ROUNDS   topk_general_*: merging rounds after which a wavefront hands its rows
+ *                               to the sequential block stack; 0 = the default, 1..4096
  * Returns TOPK_OK or TOPK_ERR_INVALID (unknown control or value).
  */
 #define TOPK_ROUTE_LONG_ROWS 0
 #define TOPK_ROUTE_SHORT_ROW_LANES 1
 #define TOPK_ROUTE_SHORT_ROW_KERNEL 2
+#define TOPK_ROUTE_GENERAL_ROUNDS 3
 #define TOPK_LONG_ROWS_AUTO 0
 #define TOPK_LONG_ROWS_SELECT 1
 #define TOPK_LONG_ROWS_SORT 2

@@ -176,6 +176,7 @@ def ensure_workspace(op: int, rows: int, n: int, k: int, p: float, device) -> No
 
 
 TOPK_ROUTE_LONG_ROWS, TOPK_ROUTE_SHORT_ROW_LANES, TOPK_ROUTE_SHORT_ROW_KERNEL = 0, 1, 2
+TOPK_ROUTE_GENERAL_ROUNDS = 3
 (TOPK_LONG_ROWS_AUTO, TOPK_LONG_ROWS_SELECT, TOPK_LONG_ROWS_SORT, TOPK_LONG_ROWS_WIDE,
  TOPK_LONG_ROWS_ONE_LAUNCH_INDEXED) = range(5)
 TOPK_SHORT_ROW_KERNEL_AUTO, TOPK_SHORT_ROW_KERNEL_INDEXED, TOPK_SHORT_ROW_KERNEL_GENERAL = 0, 1, 2

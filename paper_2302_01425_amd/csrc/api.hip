@@ -296,6 +296,10 @@ int topk_set_route(int which, int value) {
         return TOPK_ERR_INVALID;
       r.short_kernel = value;
       return TOPK_OK;
+    case TOPK_ROUTE_GENERAL_ROUNDS:
+      if (value < 0 || value > 4096) return TOPK_ERR_INVALID;
+      r.general_rounds = value;
+      return TOPK_OK;
     default:
       return TOPK_ERR_INVALID;
   }

@@ -2,17 +2,30 @@
 // soft rank, soft sort and partial ranks through the LP forms of Sec. 3), rows up to 1024 elements.
 //
 // With w = 1_k one pooled block suffices and the other kernels exploit that.  For a general w the
-// partition of pool-adjacent-violators (App. "PAV algorithm") can have any number of blocks, so
-// after the same register sort the partition is built by the usual left-to-right block stack:
-// one lane per row runs it (the rows of a wavefront run side by side in different lanes), all the
-// per-row state lives in LDS.  Every merge is decided by the strict test gamma_prev < gamma_top;
-// block sums are accumulated on the stack in merge order, and the p = 2 pooled values are computed
-// without fused multiply-adds, so exact ties are seen as ties.  A second stack walk gives each
-// block's d gamma (Prop. 7); the outputs are then written by all lanes, each position finding its
-// block by bisection on the block starts.
+// partition of pool-adjacent-violators (App. "PAV algorithm") can have any number of blocks.  After
+// the same register sort, the lanes of a row build the partition together, in ROUNDS:
 //
-// This is a correctness-first kernel: the stack walk is serial per row (one LDS round trip per
-// step), which bounds it far below the memory roofline.
+//   * float64 prefix sums of (s, w [, s^2, s^3]) over the sorted positions live in LDS, so the sums
+//     of any block [lo, hi) are two reads and a subtraction;
+//   * every lane owns E consecutive positions and keeps the block starts among them as a bit mask;
+//     a suffix-minimum / prefix-maximum over the lanes tells each block where its neighbours start;
+//   * a round computes the pooled value of every block that changed since the last round, then
+//     tests every boundary with the strict test of the PAV loop (gamma_left < gamma_right) and
+//     removes ALL violating boundaries at once.
+//
+// Removing several violating boundaries together is legal: a violating pair of neighbours stays
+// violating whatever else is merged first (merging the right block with a block that violates
+// against it raises its pooled value, merging the left block with one on its left lowers it), so
+// every such pair ends in one block of the sequential algorithm as well, and the partition in
+// which no strict violation is left is unique.  Typical rows need a handful of rounds.  A row
+// built so that only one boundary violates at a time (a low value followed by a slowly falling
+// ramp) needs one round per element: after 32 + n / 4 rounds (p = 2) the wavefront gives up and one
+// lane per row walks the usual left-to-right block stack instead.
+//
+// Pooled values of p = 2 are computed without fused multiply-adds, from sums that are exact
+// whenever the float32 inputs span fewer than ~2^19 in magnitude, so exact ties are seen as ties.
+// d gamma of every block (Prop. 7) comes from two more prefix sums (weights c_j and c_j tau_j);
+// the outputs are then written by all lanes, each position looking up its block's start.
 #include "common.hpp"
 #include "pooling.hpp"
 #include "launch.hpp"
@@ -22,15 +35,21 @@
 namespace topk {
 namespace {
 
+constexpr int kMinRounds = 32;
+
 template <int GL, int E, bool CUBIC>
 struct GenCfg {
   static constexpr int NP = GL * E;                 // padded row length
+  static constexpr int NQ = NP + 1;                 // entries of a prefix array
   static constexpr int RPW = kWave / GL;            // rows per wavefront
   static constexpr int IDXB = ilog2(NP) + 1;
-  static constexpr int ND = CUBIC ? 5 : 3;          // float64 arrays: S1, W, gamma (+ S2, S3)
-  // bytes per wavefront: float64 stack arrays, block starts (one extra slot per row), and the
-  // float arrays ss (sorted values), lw (weights, later y), lt (tangent, later dy), ltau
-  static constexpr int WaveBytes = RPW * (ND * NP * 8 + (NP + 2) * 4 + 4 * NP * 4);
+  // float64 arrays per row: prefix S1, prefix W, gamma per block start (+ prefix S2, S3)
+  static constexpr int ND = CUBIC ? 5 : 3;
+  // bytes per wavefront: the float64 arrays, the cached block ends (16 bits) and their round
+  // stamps (8 bits), and the float arrays ss (sorted values), lw (weights, later y), ltau
+  static constexpr int WaveBytes = RPW * (ND * NQ * 8 + (NP + 2) * 2 + NP + 3 * NP * 4);
+  // wavefronts per workgroup: rows of 1024 elements take 40 KB (p = 2), one wavefront each, so that
+  // four workgroups fit the 160 KB of a compute unit
   static constexpr int WPB = (4 * WaveBytes <= 60 * 1024) ? 4 : ((2 * WaveBytes <= 60 * 1024) ? 2 : 1);
 };
 
@@ -47,9 +66,13 @@ template <bool MAG>
 __device__ double block_root(double cnt, double W, double S1, double S2, double S3, const Reg& R,
                              double lo, double hi) {
   double a = lo, b = hi;
-  double x = S1 / cnt - (MAG ? 0.0 : R.lambda * cbrt(W / cnt));
+  // start: the root the cubic would have with every s_i at the block's mean
+  const double mean = S1 / cnt;
+  double x = mean - R.lambda * cbrt(MAG ? W * fmax(mean, 0.0) / cnt : W / cnt);
   if (!(x > a && x < b)) x = 0.5 * (a + b);
-  const double tol = 1e-15 * fmax(fmax(fabs(a), fabs(b)), R.lambda);
+  const double scale = fmax(fmax(fabs(a), fabs(b)), R.lambda);
+  const double tol = 1e-15 * scale;
+  double last = 1e300;
   for (int it = 0; it < 200; ++it) {
     const double F = block_cubic<MAG>(x, cnt, W, S1, S2, S3, R);
     if (F == 0.0) return x;
@@ -57,8 +80,12 @@ __device__ double block_root(double cnt, double W, double S1, double S2, double 
     const double D = (3.0 * cnt * x - 6.0 * S1) * x + 3.0 * S2 + (MAG ? R.lam3 * W : 0.0);
     const double dx = F / D;
     // a step of rounding size ends the iteration before the bracket test: at the root the
-    // bracket end is x itself, and bisecting from there would throw the converged value away
-    if (fabs(dx) <= tol) return x - dx;
+    // bracket end is x itself, and bisecting from there would throw the converged value away.
+    // Small steps that have stopped shrinking are the rounding noise of the expanded cubic (the
+    // block's values lie close together compared with their size): nothing more to gain.
+    const double adx = fabs(dx);
+    if (adx <= tol || (adx < 1e-7 * scale && adx >= 0.25 * last)) return x - dx;
+    last = adx;
     double xn = x - dx;
     if (!(xn > a && xn < b)) xn = 0.5 * (a + b);
     x = xn;
@@ -66,17 +93,100 @@ __device__ double block_root(double cnt, double W, double S1, double S2, double 
   return x;
 }
 
+// Singleton minimiser of the magnitude operator with p = 4/3 and weight W > 0: the root g in
+// [0, s] of (g - s)^3 + lambda^3 W g = 0 (App. "Subproblem derivation", one element), evaluated in
+// this form: the expanded cubic of block_root loses the small difference g - s.
+__device__ double singleton_root_mag(double s, double W, const Reg& R) {
+  if (!(s > 0.0)) return 0.0;
+  const double L = R.lam3 * W;
+  double a = 0.0, b = s;
+  double g = s - cbrt(L * s);                  // large-s asymptote
+  if (!(g > a && g < b)) g = 0.5 * s;
+  const double tol = 1e-8 * s;                 // Newton converges quadratically: the step after
+  for (int it = 0; it < 64; ++it) {            // one below tol lands within rounding of the root
+    const double u = g - s;
+    const double F = u * u * u + L * g;
+    if (F == 0.0) return g;
+    if (F > 0.0) b = g; else a = g;
+    const double dg = F / (3.0 * u * u + L);
+    if (fabs(dg) <= tol) { g -= dg; break; }
+    double gn = g - dg;
+    if (!(gn > a && gn < b)) gn = 0.5 * (a + b);
+    g = gn;
+  }
+  const double u = g - s;
+  return g - (u * u * u + L * g) / (3.0 * u * u + L);
+}
+
+// first block start in the lanes after this one / last block start in the lanes before it
+template <int GL>
+__device__ __forceinline__ int lanes_after_min(int v, int lr, int none) {
+#pragma unroll
+  for (int off = 1; off < GL; off <<= 1) {
+    const int o = __shfl_down(v, off, GL);
+    if (lr + off < GL) v = min(v, o);
+  }
+  const int nx = __shfl_down(v, 1, GL);
+  return lr + 1 < GL ? nx : none;
+}
+template <int GL>
+__device__ __forceinline__ int lanes_before_max(int v, int lr, int none) {
+#pragma unroll
+  for (int off = 1; off < GL; off <<= 1) {
+    const int o = __shfl_up(v, off, GL);
+    if (lr >= off) v = max(v, o);
+  }
+  const int pv = __shfl_up(v, 1, GL);
+  return lr >= 1 ? pv : none;
+}
+
+struct Blk {
+  double cnt, W, S1, S2, S3;
+};
+
+// pooled value of a block (App. "Subproblem derivation"); smax, smin: its largest / smallest value
+template <bool MAG, bool CUBIC>
+__device__ __forceinline__ double block_gamma(const Blk& b, double smax, double smin, const Reg& R) {
+  if (!CUBIC)
+    return MAG ? __ddiv_rn(b.S1, __dadd_rn(__dmul_rn(R.lambda, b.W), b.cnt))
+               : __ddiv_rn(__dsub_rn(b.S1, __dmul_rn(R.lambda, b.W)), b.cnt);
+  if (b.cnt == 1.0) {
+    if (!MAG) return smax - R.lambda * cbrt(b.W);
+    return (b.W == 0.0) ? smax : singleton_root_mag(smax, b.W, R);
+  }
+  return MAG ? block_root<true>(b.cnt, b.W, b.S1, b.S2, b.S3, R, 0.0, smax)
+             : block_root<false>(b.cnt, b.W, b.S1, b.S2, b.S3, R,
+                                 smin - R.lambda * cbrt(b.W) - 1e-300, smax);
+}
+
+// strict violation between the block `p` (pooled value gp) and the block `t` to its right (gt):
+// gamma_p < gamma_t.  For p = 4/3 a singleton with a closed-form minimiser is compared through the
+// other block's cubic (its sign at that value), as exact as the closed form itself.
+template <bool MAG, bool CUBIC>
+__device__ __forceinline__ bool blocks_violate(const Blk& p, double gp, const Blk& t, double gt,
+                                               const Reg& R) {
+  if (!CUBIC) return gp < gt;
+  const bool p_closed = (p.cnt == 1.0) && (!MAG || p.W == 0.0);
+  const bool t_closed = (t.cnt == 1.0) && (!MAG || t.W == 0.0);
+  if (p_closed == t_closed) return gp < gt;
+  if (p_closed) return block_cubic<MAG>(gp, t.cnt, t.W, t.S1, t.S2, t.S3, R) < 0.0;
+  return block_cubic<MAG>(gt, p.cnt, p.W, p.S1, p.S2, p.S3, R) > 0.0;
+}
+
 template <int GL, int E, bool MAG, int PC>
 __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void general_rows_kernel(
     const float* __restrict__ x, const float* __restrict__ w_all, int64_t w_stride,
     const float* __restrict__ tangent, float* __restrict__ out, float* __restrict__ jvp,
-    int64_t rows, int n, Reg R) {
+    int64_t rows, int n, Reg R, int max_rounds) {
   constexpr bool CUBIC = (PC == kP43);
   using C = GenCfg<GL, E, CUBIC>;
-  constexpr int NP = C::NP, RPW = C::RPW, IDXB = C::IDXB;
-  __shared__ __attribute__((aligned(16))) double ldsd[C::WPB][C::ND][RPW * NP];
-  __shared__ int lds_lo[C::WPB][RPW * (NP + 2)];
-  __shared__ __attribute__((aligned(16))) float ldsf[C::WPB][4][RPW * NP];
+  constexpr int NP = C::NP, NQ = C::NQ, RPW = C::RPW, IDXB = C::IDXB;
+  static_assert(E <= 16, "the block starts of a lane are kept in a 32-bit mask");
+  static_assert(NP < 0xffff, "block ends are kept in 16 bits");
+  __shared__ __attribute__((aligned(16))) double ldsd[C::WPB][C::ND][RPW * NQ];
+  __shared__ uint16_t lds_hi[C::WPB][RPW * (NP + 2)];
+  __shared__ uint8_t lds_ver[C::WPB][RPW * NP];
+  __shared__ __attribute__((aligned(16))) float ldsf[C::WPB][3][RPW * NP];
 
   const int lane = threadIdx.x & (kWave - 1);
   const int lr = lane_in_group<GL>();
@@ -87,16 +197,18 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
   if (!valid) row = rows - 1;            // keep the lanes alive for the exchanges; no stores
   const int64_t base = row * n;
   const int e0 = lr * E;
-  double* st_s1 = &ldsd[wv][0][rg * NP];                 // stack: sum of s   (later: d gamma)
-  double* st_w = &ldsd[wv][1][rg * NP];                  //        sum of w
-  double* st_g = &ldsd[wv][2][rg * NP];                  //        pooled value
-  double* st_s2 = CUBIC ? &ldsd[wv][C::ND - 2][rg * NP] : nullptr;
-  double* st_s3 = CUBIC ? &ldsd[wv][C::ND - 1][rg * NP] : nullptr;
-  int* st_lo = &lds_lo[wv][rg * (NP + 2)];               // block starts; [top] = n; [NP + 1] = top
+  // float64 arrays of the row.  P*: prefix sums over sorted positions, P[i] = sum of j < i.
+  double* P1 = &ldsd[wv][0][rg * NQ];    // of s; after the rounds: of c_j tau_j (Prop. 7)
+  double* PW = &ldsd[wv][1][rg * NQ];    // of w
+  double* G = &ldsd[wv][2][rg * NQ];     // pooled value by block start; at the very end d gamma
+  double* P2 = CUBIC ? &ldsd[wv][3][rg * NQ] : nullptr;   // of s^2; after the rounds: of c_j
+  double* P3 = CUBIC ? &ldsd[wv][4][rg * NQ] : nullptr;   // of s^3
+  uint16_t* hi_of = &lds_hi[wv][rg * (NP + 2)];  // end of the block that G[lo] was computed for
+  uint8_t* ver = &lds_ver[wv][rg * NP];          // round (mod 256) in which that last changed
   float* ss = &ldsf[wv][0][rg * NP];                     // sorted values
   float* lw = &ldsf[wv][1][rg * NP];                     // weights by sorted position; later y
-  float* lt = &ldsf[wv][2][rg * NP];                     // tangent, original order; later dy
-  float* ltau = &ldsf[wv][3][rg * NP];                   // tangent in sorted order (times sign)
+  float* ltau = &ldsf[wv][2][rg * NP];                   // tangent in sorted order (times sign)
+  float* lt = reinterpret_cast<float*>(G);               // tangent, original order; later dy
 
   // ---- load, sort ----------------------------------------------------------------------------
   float xin[E], win[E];
@@ -120,6 +232,7 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
     s32[r] = key_to_float(key);
     ss[e0 + r] = s32[r];
     lw[e0 + r] = win[r];
+    hi_of[e0 + r] = 0xffff;
   }
   __builtin_amdgcn_wave_barrier();
   if (jvp != nullptr) {
@@ -134,146 +247,321 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
       ltau[e0 + r] = tf;
     }
   }
+
+  // ---- prefix sums of the sorted row --------------------------------------------------------------
+  {
+    double t1 = 0.0, tw = 0.0, t2 = 0.0, t3 = 0.0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const bool real = e0 + r < n;
+      const double sd = real ? double(s32[r]) : 0.0, wd = real ? double(win[r]) : 0.0;
+      t1 += sd;
+      tw += wd;
+      if (CUBIC) { t2 += sd * sd; t3 += sd * sd * sd; }
+    }
+    double r1 = group_exclusive_scan_f64<GL>(t1, lr), rw = group_exclusive_scan_f64<GL>(tw, lr);
+    double r2 = 0.0, r3 = 0.0;
+    if (CUBIC) { r2 = group_exclusive_scan_f64<GL>(t2, lr); r3 = group_exclusive_scan_f64<GL>(t3, lr); }
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      P1[e0 + r] = r1;
+      PW[e0 + r] = rw;
+      if (CUBIC) { P2[e0 + r] = r2; P3[e0 + r] = r3; }
+      const bool real = e0 + r < n;
+      const double sd = real ? double(s32[r]) : 0.0, wd = real ? double(win[r]) : 0.0;
+      r1 += sd;
+      rw += wd;
+      if (CUBIC) { r2 += sd * sd; r3 += sd * sd * sd; }
+    }
+    if (lr == GL - 1) {
+      P1[NP] = r1;
+      PW[NP] = rw;
+      if (CUBIC) { P2[NP] = r2; P3[NP] = r3; }
+    }
+  }
+  __builtin_amdgcn_wave_barrier();               // (also: the tangent in G's place has been read)
+
+  auto block_sums = [&](int lo, int hi) -> Blk {
+    Blk b;
+    b.cnt = double(hi - lo);
+    b.S2 = b.S3 = 0.0;
+    if (hi - lo == 1) {                      // a singleton: its own value and weight, exactly
+      b.S1 = double(ss[lo]);
+      b.W = double(lw[lo]);
+      if (CUBIC) { b.S2 = b.S1 * b.S1; b.S3 = b.S2 * b.S1; }
+    } else {
+      b.S1 = P1[hi] - P1[lo];
+      b.W = PW[hi] - PW[lo];
+      if (CUBIC) { b.S2 = P2[hi] - P2[lo]; b.S3 = P3[hi] - P3[lo]; }
+    }
+    return b;
+  };
+
+  // ---- pool adjacent violators in rounds ------------------------------------------------------------
+  uint32_t hm = 0;                           // block starts among my positions (bit r: e0 + r)
+#pragma unroll
+  for (int r = 0; r < E; ++r)
+    if (e0 + r < n) hm |= 1u << r;
+  bool gave_up = false;
+  for (int round = 0;; ++round) {
+    const uint8_t now = uint8_t(round);
+    const int first = hm ? e0 + __builtin_ctz(hm) : n;
+    const int last = hm ? e0 + 31 - __builtin_clz(hm) : -1;
+    const int nxt = lanes_after_min<GL>(first, lr, n);
+    const int prv = lanes_before_max<GL>(last, lr, -1);
+    // pooled value of every block that is not the one of the last round
+    for (uint32_t m = hm; m != 0;) {
+      const int r = __builtin_ctz(m);
+      m &= m - 1;
+      const int lo = e0 + r, hi = m ? e0 + __builtin_ctz(m) : nxt;
+      if (int(hi_of[lo]) != hi) {
+        hi_of[lo] = uint16_t(hi);
+        ver[lo] = now;
+        G[lo] = block_gamma<MAG, CUBIC>(block_sums(lo, hi), double(ss[lo]), double(ss[hi - 1]), R);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    // every boundary whose two blocks violate goes; a boundary between two blocks that are both
+    // those of the last round was tested then
+    uint32_t keep = hm;
+    for (uint32_t m = hm; m != 0;) {
+      const int r = __builtin_ctz(m);
+      m &= m - 1;
+      const int lo = e0 + r, hi = m ? e0 + __builtin_ctz(m) : nxt;
+      const uint32_t below = hm & ((1u << r) - 1u);
+      const int p = below ? e0 + 31 - __builtin_clz(below) : prv;
+      if (p < 0) continue;                   // the first block of the row
+      if (ver[p] != now && ver[lo] != now) continue;
+      bool viol;
+      if (!CUBIC) viol = G[p] < G[lo];
+      else viol = blocks_violate<MAG, CUBIC>(block_sums(p, lo), G[p], block_sums(lo, hi), G[lo], R);
+      if (viol) keep &= ~(1u << r);
+    }
+    const bool changed = keep != hm;
+    hm = keep;
+    if (!__any(changed)) break;
+    if (round + 1 >= max_rounds) { gave_up = true; break; }
+    __builtin_amdgcn_wave_barrier();
+  }
   __builtin_amdgcn_wave_barrier();
 
-  // ---- pool adjacent violators, one lane per row ---------------------------------------------
-  if (lr == 0) {
-    // The block on top of the stack is kept in registers (t*), so the first test of every
-    // position needs no LDS read; its copy in LDS is written when the next block is pushed
-    // above it.  The next position's value and weight are read one iteration ahead.
-    int top = 0;                           // blocks in LDS below the register-held top
-    bool have = false;
-    int tlo = 0;
-    double tS1 = 0.0, tW = 0.0, tS2 = 0.0, tS3 = 0.0, tg = 0.0;
-    float s_next = ss[0], w_next = lw[0];
-    for (int i = 0; i < n; ++i) {
-      const double si = double(s_next), wi = double(w_next);
-      if (i + 1 < n) { s_next = ss[i + 1]; w_next = lw[i + 1]; }
-      int lo = i;
-      double S1 = si, W = wi, S2 = 0.0, S3 = 0.0, g;
-      if (CUBIC) { S2 = si * si; S3 = S2 * si; }
-      // singleton minimiser
-      if (!CUBIC) g = MAG ? __ddiv_rn(S1, __dadd_rn(__dmul_rn(R.lambda, W), 1.0))
-                          : __dsub_rn(S1, __dmul_rn(R.lambda, W));
-      else if (!MAG) g = si - R.lambda * cbrt(W);
-      else g = (W == 0.0) ? si : block_root<true>(1.0, W, S1, S2, S3, R, 0.0, si);
-      while (have) {
-        bool viol;
-        if (!CUBIC) {
-          viol = tg < g;
-        } else {
-          const double pcnt = double(lo - tlo), cnt = double(i + 1 - lo);
-          const bool p_closed = (lo - tlo == 1) && (!MAG || tW == 0.0);
-          const bool t_closed = (i + 1 - lo == 1) && (!MAG || W == 0.0);
-          if (p_closed == t_closed) viol = tg < g;
-          else if (p_closed) viol = block_cubic<MAG>(tg, cnt, W, S1, S2, S3, R) < 0.0;
-          else viol = block_cubic<MAG>(g, pcnt, tW, tS1, tS2, tS3, R) > 0.0;
-        }
-        if (!viol) break;
-        // merge the previous block into the current one
-        S1 = __dadd_rn(S1, tS1);
-        W = __dadd_rn(W, tW);
-        if (CUBIC) { S2 += tS2; S3 += tS3; }
-        lo = tlo;
-        // the block below becomes the top
-        have = top > 0;
-        if (have) {
-          --top;
-          tlo = st_lo[top]; tS1 = st_s1[top]; tW = st_w[top]; tg = st_g[top];
-          if (CUBIC) { tS2 = st_s2[top]; tS3 = st_s3[top]; }
-        }
-        const double cnt = double(i + 1 - lo);
-        if (!CUBIC) {
-          g = MAG ? __ddiv_rn(S1, __dadd_rn(__dmul_rn(R.lambda, W), cnt))
-                  : __ddiv_rn(__dsub_rn(S1, __dmul_rn(R.lambda, W)), cnt);
-        } else {
-          const double smax = double(ss[lo]), smin = si;
-          g = MAG ? block_root<true>(cnt, W, S1, S2, S3, R, 0.0, smax)
-                  : block_root<false>(cnt, W, S1, S2, S3, R, smin - R.lambda * cbrt(W) - 1e-300, smax);
-        }
+  double* DG = G;                            // d gamma by block start
+  float yv[E];
+  double tt[E];                              // (s - gamma) / lambda
+  if (!gave_up) {
+    // ---- y; then Prop. 7: d gamma of every block from prefix sums of c_j tau_j and c_j --------------
+    const int last = hm ? e0 + 31 - __builtin_clz(hm) : -1;
+    const int prv = lanes_before_max<GL>(last, lr, -1);
+    double cq[E], cc[E];
+    double tq = 0.0, tc = 0.0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const uint32_t upto = hm & ((2u << r) - 1u);
+      int b = upto ? e0 + 31 - __builtin_clz(upto) : prv;
+      if (b < 0) b = 0;
+      const double g = G[b];
+      tt[r] = (double(s32[r]) - g) * R.inv_lambda;
+      double c = 1.0;
+      if (CUBIC) {
+        const double d = g - double(s32[r]);
+        c = MAG ? 3.0 * d * d : d * d;
       }
-      if (have) {                          // spill the old top below the new one
-        st_lo[top] = tlo; st_s1[top] = tS1; st_w[top] = tW; st_g[top] = tg;
-        if (CUBIC) { st_s2[top] = tS2; st_s3[top] = tS3; }
-        ++top;
-      }
-      have = true;
-      tlo = lo; tS1 = S1; tW = W; tS2 = S2; tS3 = S3; tg = g;
+      const bool real = e0 + r < n;
+      cc[r] = real ? c : 0.0;
+      cq[r] = (real && jvp != nullptr) ? c * double(ltau[e0 + r]) : 0.0;
+      tq += cq[r];
+      tc += cc[r];
     }
-    if (have) {
-      st_lo[top] = tlo; st_s1[top] = tS1; st_w[top] = tW; st_g[top] = tg;
-      if (CUBIC) { st_s2[top] = tS2; st_s3[top] = tS3; }
-      ++top;
-    }
-    st_lo[top] = n;
-    st_lo[NP + 1] = top;
-    // ---- Prop. 7: d gamma of every block (overwrites the S1 column of the stack) ---------------
     if (jvp != nullptr) {
-      for (int bk = 0; bk < top; ++bk) {
-        const int lo = st_lo[bk], hi = st_lo[bk + 1];
-        const double g = st_g[bk], W = st_w[bk];
+      double rq = group_exclusive_scan_f64<GL>(tq, lr);
+      double rc = CUBIC ? group_exclusive_scan_f64<GL>(tc, lr) : 0.0;
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        P1[e0 + r] = rq;
+        if (CUBIC) P2[e0 + r] = rc;
+        rq += cq[r];
+        rc += cc[r];
+      }
+      if (lr == GL - 1) {
+        P1[NP] = rq;
+        if (CUBIC) P2[NP] = rc;
+      }
+      __builtin_amdgcn_wave_barrier();
+      const int first = hm ? e0 + __builtin_ctz(hm) : n;
+      const int nxt = lanes_after_min<GL>(first, lr, n);
+      for (uint32_t m = hm; m != 0;) {
+        const int r = __builtin_ctz(m);
+        m &= m - 1;
+        const int lo = e0 + r, hi = m ? e0 + __builtin_ctz(m) : nxt;
         double dg;
         if (hi - lo == 1) {
-          const double tau = double(ltau[lo]);
+          const double tau = double(ltau[lo]), W = double(lw[lo]);
           if (!MAG) dg = tau;
           else if (!CUBIC) dg = tau / (1.0 + R.lambda * W);
           else if (W == 0.0) dg = tau;
           else {
-            const double c = (g - double(ss[lo])) * (g - double(ss[lo]));
-            dg = 3.0 * c * tau / (3.0 * c + R.lam3 * W);
+            const double d = G[lo] - double(ss[lo]);
+            dg = 3.0 * d * d * tau / (3.0 * d * d + R.lam3 * W);
           }
         } else {
-          double num = 0.0, den = 0.0;
-          for (int j = lo; j < hi; ++j) {
-            const double d = g - double(ss[j]);
-            const double c = CUBIC ? d * d : 1.0;
-            const double q = (MAG && CUBIC) ? 3.0 * c : c;
-            num += q * double(ltau[j]);
-            den += q;
-          }
-          if (MAG) den += (CUBIC ? R.lam3 : R.lambda) * W;
+          const double num = P1[hi] - P1[lo];
+          double den = CUBIC ? P2[hi] - P2[lo] : double(hi - lo);
+          if (MAG) den += (CUBIC ? R.lam3 : R.lambda) * (PW[hi] - PW[lo]);
           dg = num / den;
         }
-        st_s1[bk] = dg;
+        DG[lo] = dg;                         // G[lo] is read by this lane only, above
       }
+    }
+  } else {
+    // ---- too many rounds: the left-to-right block stack, one lane per row ---------------------------
+    // (stack columns in the arrays of the rounds, block starts in hi_of; the block on top of the
+    // stack is kept in registers)
+    double* st_s1 = P1;
+    double* st_w = PW;
+    double* st_g = G;
+    double* st_s2 = P2;
+    double* st_s3 = P3;
+    uint16_t* st_lo = hi_of;
+    DG = P1;
+    __builtin_amdgcn_wave_barrier();
+    if (lr == 0) {
+      int top = 0;                           // blocks in LDS below the register-held top
+      bool have = false;
+      int tlo = 0;
+      double tS1 = 0.0, tW = 0.0, tS2 = 0.0, tS3 = 0.0, tg = 0.0;
+      float s_next = ss[0], w_next = lw[0];
+      for (int i = 0; i < n; ++i) {
+        const double si = double(s_next), wi = double(w_next);
+        if (i + 1 < n) { s_next = ss[i + 1]; w_next = lw[i + 1]; }
+        int lo = i;
+        Blk cur{1.0, wi, si, 0.0, 0.0};
+        if (CUBIC) { cur.S2 = si * si; cur.S3 = cur.S2 * si; }
+        double g = block_gamma<MAG, CUBIC>(cur, si, si, R);
+        while (have) {
+          const Blk prev{double(lo - tlo), tW, tS1, tS2, tS3};
+          if (!blocks_violate<MAG, CUBIC>(prev, tg, cur, g, R)) break;
+          // merge the previous block into the current one
+          cur.S1 = __dadd_rn(cur.S1, tS1);
+          cur.W = __dadd_rn(cur.W, tW);
+          if (CUBIC) { cur.S2 += tS2; cur.S3 += tS3; }
+          lo = tlo;
+          cur.cnt = double(i + 1 - lo);
+          // the block below becomes the top
+          have = top > 0;
+          if (have) {
+            --top;
+            tlo = st_lo[top]; tS1 = st_s1[top]; tW = st_w[top]; tg = st_g[top];
+            if (CUBIC) { tS2 = st_s2[top]; tS3 = st_s3[top]; }
+          }
+          g = block_gamma<MAG, CUBIC>(cur, double(ss[lo]), si, R);
+        }
+        if (have) {                          // spill the old top below the new one
+          st_lo[top] = uint16_t(tlo); st_s1[top] = tS1; st_w[top] = tW; st_g[top] = tg;
+          if (CUBIC) { st_s2[top] = tS2; st_s3[top] = tS3; }
+          ++top;
+        }
+        have = true;
+        tlo = lo; tS1 = cur.S1; tW = cur.W; tS2 = cur.S2; tS3 = cur.S3; tg = g;
+      }
+      if (have) {
+        st_lo[top] = uint16_t(tlo); st_s1[top] = tS1; st_w[top] = tW; st_g[top] = tg;
+        if (CUBIC) { st_s2[top] = tS2; st_s3[top] = tS3; }
+        ++top;
+      }
+      // Prop. 7 per block; then everything moves from the stack slot to the block's start (marked
+      // 0xffff in hi_of).  Slots are visited from the top and start >= slot, so nothing that is
+      // still to be read gets overwritten.
+      int hi = n;
+      for (int bk = top - 1; bk >= 0; --bk) {
+        const int lo = st_lo[bk];
+        const double g = st_g[bk], W = st_w[bk];
+        double dg = 0.0;
+        if (jvp != nullptr) {
+          if (hi - lo == 1) {
+            const double tau = double(ltau[lo]);
+            if (!MAG) dg = tau;
+            else if (!CUBIC) dg = tau / (1.0 + R.lambda * W);
+            else if (W == 0.0) dg = tau;
+            else {
+              const double c = (g - double(ss[lo])) * (g - double(ss[lo]));
+              dg = 3.0 * c * tau / (3.0 * c + R.lam3 * W);
+            }
+          } else {
+            double num = 0.0, den = 0.0;
+            for (int j = lo; j < hi; ++j) {
+              const double d = g - double(ss[j]);
+              const double c = CUBIC ? d * d : 1.0;
+              const double q = (MAG && CUBIC) ? 3.0 * c : c;
+              num += q * double(ltau[j]);
+              den += q;
+            }
+            if (MAG) den += (CUBIC ? R.lam3 : R.lambda) * W;
+            dg = num / den;
+          }
+        }
+        st_lo[bk] = 0;
+        G[lo] = g;
+        DG[lo] = dg;
+        st_lo[lo] = 0xffff;
+        hi = lo;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    hm = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r)
+      if (e0 + r < n && hi_of[e0 + r] == 0xffff) hm |= 1u << r;
+    const int last = hm ? e0 + 31 - __builtin_clz(hm) : -1;
+    const int prv = lanes_before_max<GL>(last, lr, -1);
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const uint32_t upto = hm & ((2u << r) - 1u);
+      int b = upto ? e0 + 31 - __builtin_clz(upto) : prv;
+      if (b < 0) b = 0;
+      tt[r] = (double(s32[r]) - G[b]) * R.inv_lambda;
     }
   }
   __builtin_amdgcn_wave_barrier();
 
   // ---- outputs: y = sign o grad r*(s - v), dy = sign o hess r*(s - v) (tau - d gamma) ------------
-  const int top = st_lo[NP + 1];
+  {
+    const int last = hm ? e0 + 31 - __builtin_clz(hm) : -1;
+    const int prv = lanes_before_max<GL>(last, lr, -1);
+    float dv[E];
+    uint32_t orig[E];
 #pragma unroll
-  for (int r = 0; r < E; ++r) {
-    const int pos = e0 + r;
-    if (pos >= n) continue;
-    int lo_b = 0, hi_b = top - 1;                        // last block whose start is <= pos
-    while (lo_b < hi_b) {
-      const int mid = (lo_b + hi_b + 1) >> 1;
-      if (st_lo[mid] <= pos) lo_b = mid; else hi_b = mid - 1;
-    }
-    const double g = st_g[lo_b];
-    const double tt = (double(s32[r]) - g) * R.inv_lambda;
-    const bool neg = MAG && (field[r] & 1u);
-    const uint32_t orig = MAG ? (field[r] >> 1) : field[r];
-    if (out != nullptr) {
-      float y = float(CUBIC ? tt * tt * tt : tt);
+    for (int r = 0; r < E; ++r) {
+      const uint32_t upto = hm & ((2u << r) - 1u);
+      int b = upto ? e0 + 31 - __builtin_clz(upto) : prv;
+      if (b < 0) b = 0;                                    // padding of an empty tail
+      const bool neg = MAG && (field[r] & 1u);
+      orig[r] = MAG ? (field[r] >> 1) : field[r];
+      float y = float(CUBIC ? tt[r] * tt[r] * tt[r] : tt[r]);
       if (MAG) y = (y == 0.0f || s32[r] == 0.0f) ? 0.0f : (neg ? -y : y);
-      lw[orig] = y;
+      yv[r] = y;
+      dv[r] = 0.0f;
+      if (jvp != nullptr) {
+        const double h = CUBIC ? 3.0 * tt[r] * tt[r] * R.inv_lambda : R.inv_lambda;
+        float dy = float(h * (double(ltau[e0 + r]) - DG[b]));
+        if (MAG) dy = (dy == 0.0f || s32[r] == 0.0f) ? 0.0f : (neg ? -dy : dy);
+        dv[r] = dy;
+      }
     }
-    if (jvp != nullptr) {
-      const double h = CUBIC ? 3.0 * tt * tt * R.inv_lambda : R.inv_lambda;
-      float dy = float(h * (double(ltau[pos]) - st_s1[lo_b]));
-      if (MAG) dy = (dy == 0.0f || s32[r] == 0.0f) ? 0.0f : (neg ? -dy : dy);
-      lt[orig] = dy;
+    __builtin_amdgcn_wave_barrier();             // lw and G's place are free: everything was read
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      if (e0 + r >= n) continue;
+      if (out != nullptr) lw[orig[r]] = yv[r];
+      if (jvp != nullptr) lt[orig[r]] = dv[r];
     }
   }
   __builtin_amdgcn_wave_barrier();
   if (!valid) return;
   if (out != nullptr) {
-    float yv[E];
+    float ov[E];
 #pragma unroll
-    for (int r = 0; r < E; ++r) yv[r] = lw[e0 + r];
-    store_elems<E, false>(out, base, e0, n, yv);
+    for (int r = 0; r < E; ++r) ov[r] = lw[e0 + r];
+    store_elems<E, false>(out, base, e0, n, ov);
   }
   if (jvp != nullptr) {
     float jv[E];
@@ -286,7 +574,7 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
 template <int GL, int E>
 int launch_general_shape(bool mag, int pc, const float* x, const float* w, int64_t w_stride,
                          const float* t, float* out, float* jvp, int64_t rows, int n, const Reg& R,
-                         hipStream_t st) {
+                         hipStream_t st, int max_rounds) {
 #define TOPK_GENERAL_CALL(MAGV, PCV)                                                            \
   do {                                                                                          \
     using C = GenCfg<GL, E, PCV == kP43>;                                                       \
@@ -294,7 +582,8 @@ int launch_general_shape(bool mag, int pc, const float* x, const float* w, int64
     const int64_t blocks = (waves + C::WPB - 1) / C::WPB;                                       \
     if (blocks > 0x7fffffffLL) return -1;                                                       \
     hipLaunchKernelGGL((general_rows_kernel<GL, E, MAGV, PCV>), dim3((unsigned)blocks),          \
-                       dim3(C::WPB * kWave), 0, st, x, w, w_stride, t, out, jvp, rows, n, R);   \
+                       dim3(C::WPB * kWave), 0, st, x, w, w_stride, t, out, jvp, rows, n, R,   \
+                       max_rounds);                                                             \
     return 0;                                                                                   \
   } while (0)
   if (!mag && pc == kP2) TOPK_GENERAL_CALL(false, kP2);
@@ -312,7 +601,13 @@ int launch_general_rows(bool mag, int pc, const float* x, const float* w, int64_
                         const Reg& R, hipStream_t st) {
   int np = 2;
   while (np < n) np <<= 1;
-#define CALL(GL, E) launch_general_shape<GL, E>(mag, pc, x, w, w_stride, tangent, out, jvp, rows, n, R, st)
+  // Rounds before the hand-over to the sequential walk.  A round costs about as much as four
+  // steps of the walk for p = 2; for p = 4/3 every step of the walk solves a cubic, and the rounds
+  // (n - 1 of them at most: each removes a boundary) always win.
+  const int forced = routes().general_rounds;            // test control
+  const int max_rounds = forced > 0 ? forced : (pc == kP43 ? n + 1 : kMinRounds + n / 4);
+#define CALL(GL, E) \
+  launch_general_shape<GL, E>(mag, pc, x, w, w_stride, tangent, out, jvp, rows, n, R, st, max_rounds)
   switch (np) {
     case 2: return CALL(1, 2);
     case 4: return CALL(1, 4);

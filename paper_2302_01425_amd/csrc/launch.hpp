@@ -14,6 +14,7 @@ struct Routes {
   int long_rows = 0;      // TOPK_LONG_ROWS_*
   int short_lanes = 0;    // lanes per row of the short-row kernels, 0 = chosen from the shape
   int short_kernel = 0;   // TOPK_SHORT_ROW_KERNEL_*
+  int general_rounds = 0; // general weights: merging rounds before the sequential fallback, 0 = default
 };
 Routes& routes();
 

@@ -441,6 +441,38 @@ def test_general_weights(gpu, oracle, n):
     close(got, ref, "soft sort")
 
 
+def test_general_weights_many_rounds_and_stack_fallback(gpu, oracle):
+    """Rows on which the merging rounds remove one boundary at a time (one heavy first weight in
+    front of a slowly falling ramp: the pooled block takes in one neighbour per round, some 220 of
+    them), so the wavefront hands over to the sequential block stack; and ordinary rows with the
+    hand-over forced after 1 and 3 rounds."""
+    r = np.random.default_rng(91)
+    for n in (300, 1024):
+        x = r.normal(size=(6, n)).astype(np.float32)
+        w = -np.sort(-np.abs(r.normal(size=(6, n))).astype(np.float32), axis=1)
+        ramp = (10.0 - 0.001 * np.arange(n)).astype(np.float32)
+        ramp[0] = 10.0005
+        x[1] = ramp[r.permutation(n)]
+        w[1] = 0.0
+        w[1, 0] = 50.0
+        x[4] = x[1]
+        w[4] = w[1]
+        w[4, 1:n // 2] = 0.25                                 # the same, on top of a step
+        t = r.normal(size=(6, n)).astype(np.float32)
+        for phi, phic in (("id", gpu.TOPK_PHI_IDENTITY), ("half_sq", gpu.TOPK_PHI_HALF_SQUARE)):
+            for p in (P2, P43):
+                print(f"ramp n={n} phi={phi} p={p:.3f}", flush=True)
+                ref = oracle.topk_general(x, w, p, 1.0, phi, tangent=t)
+                for rounds in (0, 1, 3):
+                    gpu.set_route(gpu.TOPK_ROUTE_GENERAL_ROUNDS, rounds)
+                    try:
+                        out, jv = (host(a) for a in gpu.topk_general_jvp(dev(x), dev(w), dev(t), phic, p, 1.0))
+                    finally:
+                        gpu.set_route(gpu.TOPK_ROUTE_GENERAL_ROUNDS, 0)
+                    close(out, ref["out"], f"general fwd rounds={rounds}")
+                    close(jv, ref["jvp"], f"general jvp rounds={rounds}")
+
+
 # ---- Dykstra's algorithm with a fixed number of iterations ----------------------------------------
 @pytest.mark.parametrize("n", [1, 2, 3, 16, 63, 64, 100, 400, 1024])
 def test_dykstra_iterations(gpu, oracle, n):
