@@ -209,7 +209,7 @@ def sweep_solvers(a):
     """Forward pass of the relaxed top-k mask (p = 2, lambda = 0.1) against the row length, with
     k = ceil(n / 10) as in the paper's run-time comparison (Sec. 5, figure "Runtime comparison"):
     the library's exact solve, 100 iterations of Dykstra's algorithm (rows up to 1024 elements;
-    there also the general-weights kernel on rank weights), and a hard top-k (torch.topk, the framework's own primitive).  2^22 elements per call,
+    the general-weights kernels on rank weights up to 131072), and a hard top-k (torch.topk, the framework's own primitive).  2^22 elements per call,
     stream launches timed with events.  Not the benchmark contract: one JSON line per length."""
     import torch
     from paper_2302_01425_amd import binding
@@ -247,9 +247,11 @@ def sweep_solvers(a):
             exact = binding.topk_mask_fwd(x, k, 2.0, 0.1)
             approx = binding.topk_mask_dykstra_fwd(x, k, 0.1, 100)
             line["dykstra100_max_abs_diff"] = float((exact - approx).abs().max())
+        if n <= binding.TOPK_GENERAL_ROW_MAX:
             # the full PAV partition for general weights, here the relaxed ranks y(-theta, rho)
             rho = torch.arange(n, 0, -1, dtype=torch.float32, device=x.device)
             xneg = -x
+            binding.ensure_workspace(binding.TOPK_OP_GENERAL, rows, n, 0, 2.0, x.device)
             line["general_w_rank_us"] = timed(
                 lambda: binding.topk_general_fwd(xneg, rho, binding.TOPK_PHI_IDENTITY, 2.0, 0.1,
                                                  out=out, stream=stream))

@@ -65,7 +65,8 @@ enum {
   TOPK_OP_MAG_JVP = 3,
   TOPK_OP_ARGSORT = 4,
   TOPK_OP_SIGNED_MASK = 5,   /* topk_signed_mask_fwd and _jvp */
-  TOPK_OP_MASKED_VALUE = 6   /* topk_masked_value_fwd and _jvp */
+  TOPK_OP_MASKED_VALUE = 6,  /* topk_masked_value_fwd and _jvp */
+  TOPK_OP_GENERAL = 7        /* topk_general_fwd and _jvp */
 };
 
 /* phi of topk_general_*: phi(x) = x (mask-like operators) or phi(x) = x^2 / 2 (in magnitude). */
@@ -76,6 +77,8 @@ enum {
 
 /* Rows up to this length are handled by one wavefront in registers (no workspace needed). */
 #define TOPK_SHORT_ROW_MAX 1024
+/* Longest row of topk_general_*: above TOPK_SHORT_ROW_MAX one workgroup solves a sorted row. */
+#define TOPK_GENERAL_ROW_MAX 131072
 
 /*
  * Relaxed top-k mask, forward (phi(x) = x; Prop. 2 + Prop. 5; pooling steps from Sec. 5
@@ -177,9 +180,13 @@ int topk_mask_sparse_fwd(const float* theta, int64_t rows, int64_t n, int64_t k,
  *   checked, the result is unspecified otherwise): [n] shared by all rows when w_stride == 0,
  *   [rows][n] when w_stride == n (anything else: TOPK_ERR_INVALID).  phi: a TOPK_PHI_* code.
  *   out, jvp_out [rows][n] out (out may be NULL in the *_jvp call).
- *   Rows up to TOPK_SHORT_ROW_MAX elements only (TOPK_ERR_INVALID beyond); no workspace.
- *   One lane per row walks the block stack, so this entry point is far slower per element than
- *   the top-k ones.  Other arguments and errors as topk_mask_fwd / topk_mask_jvp.
+ *   Rows up to TOPK_GENERAL_ROW_MAX elements (TOPK_ERR_INVALID beyond).  Up to TOPK_SHORT_ROW_MAX
+ *   elements the lanes of a wavefront build the partition of a row together and no workspace is
+ *   needed; longer rows are sorted completely and then solved by one workgroup each, with
+ *   topk_workspace_bytes(TOPK_OP_GENERAL, rows, n, 0, p) bytes of workspace (TOPK_ERR_WORKSPACE
+ *   without).  The partition is built in rounds that remove all violating block boundaries at
+ *   once; rows on which only one boundary violates at a time fall back to the sequential walk of
+ *   the block stack and are slow.  Other arguments and errors as topk_mask_fwd / topk_mask_jvp.
  */
 int topk_general_fwd(const float* x, const float* w, int64_t w_stride, int64_t rows, int64_t n,
                      int phi, double p, double lambda, float* out, void* stream);

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
 
 (TOPK_OP_MASK_FWD, TOPK_OP_MASK_JVP, TOPK_OP_MAG_FWD, TOPK_OP_MAG_JVP, TOPK_OP_ARGSORT,
- TOPK_OP_SIGNED_MASK, TOPK_OP_MASKED_VALUE) = range(7)
+ TOPK_OP_SIGNED_MASK, TOPK_OP_MASKED_VALUE, TOPK_OP_GENERAL) = range(8)
 
 EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
@@ -177,6 +177,7 @@ def ensure_workspace(op: int, rows: int, n: int, k: int, p: float, device) -> No
 
 TOPK_ROUTE_LONG_ROWS, TOPK_ROUTE_SHORT_ROW_LANES, TOPK_ROUTE_SHORT_ROW_KERNEL = 0, 1, 2
 TOPK_ROUTE_GENERAL_ROUNDS = 3
+TOPK_SHORT_ROW_MAX, TOPK_GENERAL_ROW_MAX = 1024, 131072
 (TOPK_LONG_ROWS_AUTO, TOPK_LONG_ROWS_SELECT, TOPK_LONG_ROWS_SORT, TOPK_LONG_ROWS_WIDE,
  TOPK_LONG_ROWS_ONE_LAUNCH_INDEXED) = range(5)
 TOPK_SHORT_ROW_KERNEL_AUTO, TOPK_SHORT_ROW_KERNEL_INDEXED, TOPK_SHORT_ROW_KERNEL_GENERAL = 0, 1, 2
@@ -314,6 +315,7 @@ def topk_general_fwd(x, w, phi, p, lam, out=None, stream=None):
     rows, n = x.shape
     w, stride = _weights(w, rows, n, x.device)
     out = _out(out, x, "out", (x, w))
+    ensure_workspace(TOPK_OP_GENERAL, rows, n, 0, p, x.device)
     _check(load().topk_general_fwd(x.data_ptr(), w.data_ptr(), stride, rows, n, int(phi), float(p),
                                    float(lam), out.data_ptr(), _stream(stream)), "topk_general_fwd")
     return out
@@ -330,6 +332,7 @@ def topk_general_jvp(x, w, tangent, phi, p, lam, out=None, jvp_out=None, want_ou
     jvp_out = _out(jvp_out, x, "jvp_out", (x, w, tangent))
     if out is not None and _overlap(out, jvp_out):
         raise TopkError("out and jvp_out overlap")
+    ensure_workspace(TOPK_OP_GENERAL, rows, n, 0, p, x.device)
     _check(load().topk_general_jvp(x.data_ptr(), w.data_ptr(), stride, tangent.data_ptr(), rows, n,
                                    int(phi), float(p), float(lam),
                                    None if out is None else out.data_ptr(), jvp_out.data_ptr(),

@@ -310,7 +310,7 @@ static int run_general(int phi, const float* x, const float* w, int64_t w_stride
                        float* out, float* jvp, bool need_jvp, void* stream) {
   const int rc = check_shape(rows, n, 0, lambda);
   if (rc != TOPK_OK) return rc;
-  if (n > TOPK_SHORT_ROW_MAX || (w_stride != 0 && w_stride != n)) return TOPK_ERR_INVALID;
+  if (n > TOPK_GENERAL_ROW_MAX || (w_stride != 0 && w_stride != n)) return TOPK_ERR_INVALID;
   if (phi != TOPK_PHI_IDENTITY && phi != TOPK_PHI_HALF_SQUARE) return TOPK_ERR_INVALID;
   const int pc = p_code(p);
   if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
@@ -318,10 +318,26 @@ static int run_general(int phi, const float* x, const float* w, int64_t w_stride
   if (x == nullptr || w == nullptr) return TOPK_ERR_NULL;
   if (!need_jvp && out == nullptr) return TOPK_ERR_NULL;
   if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
+  const bool mag = phi == TOPK_PHI_HALF_SQUARE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!is_long(n)) {
+    begin();
+    if (topk::launch_general_rows(mag, pc, x, w, w_stride, need_jvp ? tangent : nullptr, out,
+                                  need_jvp ? jvp : nullptr, rows, int(n), make_reg(lambda), st) != 0)
+      return TOPK_ERR_INVALID;
+    return finish();
+  }
+  // long rows: a complete sort of every row, then one workgroup per row; the solver's float64
+  // arrays come first in the workspace, the sort's arrays after them
+  const size_t skip = topk::general_long_bytes(rows, n, pc);
+  SortBuffers B;
+  const int crc = carve(rows, n, &B, skip);
+  if (crc != TOPK_OK) return crc;
+  const topk::GeneralBuffers gb = topk::general_long_carve(g_ws.ptr, rows, n, pc);
   begin();
-  if (topk::launch_general_rows(phi == TOPK_PHI_HALF_SQUARE, pc, x, w, w_stride,
-                                need_jvp ? tangent : nullptr, out, need_jvp ? jvp : nullptr, rows,
-                                int(n), make_reg(lambda), static_cast<hipStream_t>(stream)) != 0)
+  if (topk::launch_segmented_sort(mag, x, rows, n, B, st) != 0) return TOPK_ERR_INVALID;
+  if (topk::launch_general_long(mag, pc, B, gb, x, w, w_stride, need_jvp ? tangent : nullptr, out,
+                                need_jvp ? jvp : nullptr, rows, n, make_reg(lambda), st) != 0)
     return TOPK_ERR_INVALID;
   return finish();
 }
@@ -503,8 +519,13 @@ int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm
 size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p) {
   (void)k;
   (void)p;
-  if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_MASKED_VALUE) return 0;
+  if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_GENERAL) return 0;
   if (rows <= 0 || n < 1 || n >= (int64_t(1) << 30)) return 0;
+  if (op == TOPK_OP_GENERAL) {
+    if (!is_long(n) || n > TOPK_GENERAL_ROW_MAX) return 0;
+    return topk::general_long_bytes(rows, n, p_code(p) == topk::kP2 ? topk::kP2 : topk::kP43) +
+           layout_for(rows, n).total;
+  }
   const size_t own = ((op == TOPK_OP_SIGNED_MASK || op == TOPK_OP_MASKED_VALUE) && !abs_fused(n))
                          ? abs_scratch_bytes(rows, n) : 0;
   if (!is_long(n)) return own;

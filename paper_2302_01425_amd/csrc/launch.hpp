@@ -188,6 +188,30 @@ int launch_general_rows(bool mag, int pc, const float* x, const float* w, int64_
                         const float* tangent, float* out, float* jvp, int64_t rows, int n,
                         const Reg& R, hipStream_t st);
 
+// The same for rows of 1025 .. kGeneralLongMax elements, sorted completely beforehand
+// (launch_segmented_sort): one workgroup per row, float64 prefix sums and per-block values in
+// global scratch.
+constexpr int64_t kGeneralLongMax = 131072;
+struct DD {          // an unevaluated sum h + l of two float64 (general_long.hip)
+  double h, l;
+};
+struct GeneralBuffers {
+  DD* p1;            // [rows][n + 1] each: prefix sums of s and of w,
+  DD* pw;
+  double* g;         // pooled values and d gamma by block start
+  double* dg;
+  DD* p2;            // p = 4/3 only: prefix sums of s^2, s^3
+  DD* p3;
+  uint32_t* hi_of;   // [rows][n]
+  float* ltau;       // [rows][n]
+};
+size_t general_long_bytes(int64_t rows, int64_t n, int pc);
+GeneralBuffers general_long_carve(void* ptr, int64_t rows, int64_t n, int pc);
+int launch_general_long(bool mag, int pc, const SortBuffers& B, const GeneralBuffers& gb,
+                        const float* x, const float* w, int64_t w_stride, const float* tangent,
+                        float* out, float* jvp, int64_t rows, int64_t n, const Reg& R,
+                        hipStream_t st);
+
 // Relaxed top-k mask, p = 2, by `iters` iterations of Dykstra's alternating projections (Alg. 1)
 // on the sorted row instead of the exact block search; n <= 1024.
 int launch_short_dykstra(const float* x, float* out, int64_t rows, int n, int k, double lambda,

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kWT) void medium2_kernel(
     if (cn <= uint32_t(kMedCap)) {
       ri = solve_lds_list<MAG, PC, kMedCap>(cn, k, klo, khi, R, sm);
     } else {
-      ri = solve_global_list<MAG, PC, kMedCap>(ka, pa, kb, pb, cn, k, klo, khi, R, false, sm);
+      ri = solve_unsorted_list<MAG, PC, kMedCap>(ka, pa, cn, k, klo, khi, R, false, sm);
     }
     // d gamma (Prop. 7): the tangent of the list's elements whose value lies inside the block's
     // window, gathered through their indices

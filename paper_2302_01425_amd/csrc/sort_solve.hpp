@@ -48,6 +48,11 @@ struct ListShared {
     int a, b;
     Sums pa1, pb;                              // prefix sums up to positions a - 1 and b
   } grow;
+  // solve of an unsorted list (solve_unsorted_list)
+  uint32_t red[4][kWW];
+  struct {
+    uint32_t bin, below;
+  } pick;
 };
 
 // exclusive scan of one value per thread over the workgroup; *total gets the sum
@@ -582,20 +587,219 @@ __device__ __forceinline__ double list_dgamma(const uint32_t* ka, const uint32_t
   return num / P::jac_denominator(den, double(k - ri.a + 1), R);
 }
 
-// A list that does not fit the LDS buffers (rare: the window holds more than CAP elements):
-// keys-only radix passes from ka through the two global buffers b0, b1 (each at least cn words,
-// contents destroyed), the block growth of long_solve.hpp on the result, d gamma from (ka, pa).
+// ---- lists that do not fit the LDS buffers: solved WITHOUT sorting them ---------------------------
+// The block is a set of values: with gamma its pooled value, a candidate above s_k belongs to it
+// iff its singleton minimiser lies below gamma, one below s_{k+1} iff its value lies above gamma
+// (the tests of the growth, which hold for every member of the final block and fail for every
+// non-member, all values being compared with the same gamma), and everything from s_{k+1} to s_k
+// belongs to it.  gamma is therefore the root of the non-increasing function
+//     Psi(g) = #above(g) + sum over the set at g of grad r*(s - g) - k,
+// found by solving one piece after the other: classify the list at g (one pass: counts, sums and
+// extreme values of the set), take the pooled value g' of that set - the root of the piece of Psi
+// that g lies on - and classify again at g'; when the set does not change, g' is the root.  A
+// bracket [lo, hi] from the signs seen so far (g' > g means Psi(g) > 0) guards the iteration.
+// s_k and s_{k+1} come from a radix selection on the keys (11 bits per pass).
+
+// key of rank r (1-based) in ascending key order among list[0, cn); also the number of keys
+// below it and the number equal to it
+template <int CAP>
+__device__ uint32_t list_select(const uint32_t* list, uint32_t cn, uint32_t klo, int nbits,
+                                uint32_t rank, uint32_t* below_out, uint32_t* equal_out,
+                                ListShared<CAP>& sm) {
+  uint32_t prefix = 0, pmask = 0, r = rank - 1, equal = cn;   // r: 0-based rank among the matches
+  for (int top = nbits; top > 0;) {
+    const int width = top < 11 ? top : 11;
+    const int shift = top - width;
+    const uint32_t bins = 1u << width;
+    uint32_t* hist = sm.u.bucket;
+    for (uint32_t i = threadIdx.x; i < bins; i += kWT) hist[i] = 0;
+    __syncthreads();
+    for (uint32_t j = threadIdx.x; j < cn; j += kWT) {
+      const uint32_t u = list[j] - klo;
+      if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (bins - 1u)], 1u);
+    }
+    __syncthreads();
+    const uint32_t b0 = 2u * threadIdx.x, b1 = b0 + 1u;       // two bins per thread (2048 at most)
+    const uint32_t c0 = b0 < bins ? hist[b0] : 0u, c1 = b1 < bins ? hist[b1] : 0u;
+    const uint32_t ex = wide_exclusive_scan(c0 + c1, sm.wave_tot, nullptr);
+    if (r >= ex && r < ex + c0) sm.pick = {b0, ex};
+    else if (r >= ex + c0 && r < ex + c0 + c1) sm.pick = {b1, ex + c0};
+    __syncthreads();
+    const uint32_t bin = sm.pick.bin;
+    r -= sm.pick.below;
+    equal = hist[bin];
+    prefix |= bin << shift;
+    pmask |= (bins - 1u) << shift;
+    top = shift;
+    __syncthreads();
+  }
+  *below_out = rank - 1 - r;
+  *equal_out = equal;
+  return klo + prefix;
+}
+
+struct SetStats {
+  uint32_t above, cnt;       // candidates above the set, members of the set
+  uint32_t kmin, kmax;       // smallest / largest key of the set (its largest / smallest value)
+  Sums S;                    // power sums of the members' centred values
+};
+
+// One pass over the list: the set at the pooled value g (centred), or, with seed_only, just the
+// values from s_{k+1} to s_k (keys kk .. kk1).
 template <bool MAG, int PC, int CAP>
-__device__ RowInfo solve_global_list(const uint32_t* ka, const uint32_t* pa, uint32_t* b0,
-                                     uint32_t* b1, uint32_t cn, int64_t k, uint32_t klo,
-                                     uint32_t khi, const Reg& R, bool want_jvp,
-                                     ListShared<CAP>& sm) {
+__device__ SetStats list_classify(const uint32_t* list, uint32_t cn, uint32_t kk, uint32_t kk1,
+                                  double g, bool seed_only, double center, const Reg& R,
+                                  ListShared<CAP>& sm) {
+  constexpr bool CUBIC = (PC == kP43);
+  uint32_t above = 0, cnt = 0, kmin = 0xffffffffu, kmax = 0u;
+  Sums S{0.0, 0.0, 0.0};
+  const double g_abs = g + center;
+  for (uint32_t j0 = threadIdx.x; j0 < cn; j0 += 4 * kWT) {
+    uint32_t key[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) key[i] = j0 + uint32_t(i) * kWT < cn ? list[j0 + uint32_t(i) * kWT] : 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (j0 + uint32_t(i) * kWT >= cn) continue;
+      const double v = double(key_to_float(key[i]));
+      const double d = v - center;
+      bool in = key[i] >= kk && key[i] <= kk1;
+      if (!seed_only && !in) {
+        if (key[i] < kk) {                       // above s_k: its singleton minimiser below g?
+          if (MAG && CUBIC) {
+            const double u = g_abs - v;          // sign of the one-element cubic at g
+            in = u * u * u + R.lam3 * g_abs > 0.0;
+          } else if (MAG) {
+            in = v < g_abs * R.one_p_lambda;
+          } else {
+            in = d - R.lambda < g;
+          }
+        } else {                                 // below s_{k+1}: its value above g?
+          in = d > g;
+        }
+      }
+      if (in) {
+        ++cnt;
+        kmin = min(kmin, key[i]);
+        kmax = max(kmax, key[i]);
+        S.s1 += d;
+        if (CUBIC) { S.s2 += d * d; S.s3 += d * d * d; }
+      } else if (key[i] < kk) {
+        ++above;
+      }
+    }
+  }
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+#pragma unroll
+  for (int off = kWave >> 1; off >= 1; off >>= 1) {
+    above += __shfl_xor(above, off, kWave);
+    cnt += __shfl_xor(cnt, off, kWave);
+    kmin = min(kmin, uint32_t(__shfl_xor(kmin, off, kWave)));
+    kmax = max(kmax, uint32_t(__shfl_xor(kmax, off, kWave)));
+    S.s1 += __shfl_xor(S.s1, off, kWave);
+    if (CUBIC) { S.s2 += __shfl_xor(S.s2, off, kWave); S.s3 += __shfl_xor(S.s3, off, kWave); }
+  }
+  __syncthreads();
+  if (lane == 0) {
+    sm.red[0][w] = above;
+    sm.red[1][w] = cnt;
+    sm.red[2][w] = kmin;
+    sm.red[3][w] = kmax;
+    sm.wave_sums[w] = S;
+  }
+  __syncthreads();
+  SetStats st{0u, 0u, 0xffffffffu, 0u, Sums{0.0, 0.0, 0.0}};
+#pragma unroll
+  for (int q = 0; q < kWW; ++q) {
+    st.above += sm.red[0][q];
+    st.cnt += sm.red[1][q];
+    st.kmin = min(st.kmin, sm.red[2][q]);
+    st.kmax = max(st.kmax, sm.red[3][q]);
+    st.S.s1 += sm.wave_sums[q].s1;
+    if (CUBIC) { st.S.s2 += sm.wave_sums[q].s2; st.S.s3 += sm.wave_sums[q].s3; }
+  }
+  return st;
+}
+
+// The row's unsorted candidate list (keys ka, tangent payload pa) -> RowInfo in list coordinates.
+template <bool MAG, int PC, int CAP>
+__device__ RowInfo solve_unsorted_list(const uint32_t* ka, const uint32_t* pa, uint32_t cn,
+                                       int64_t k64, uint32_t klo, uint32_t khi, const Reg& R,
+                                       bool want_jvp, ListShared<CAP>& sm) {
+  using P = Pool<MAG, PC>;
+  const int64_t k = k64;
+  RowInfo ri;
+  ri.src = 0;
+  ri.pad = 0;
+  ri.a = k64 + 1;
+  ri.b = k64;
+  ri.wa = ri.a;
+  ri.wb = ri.b;
+  ri.gamma = ri.center = ri.dgamma = 0.0;
+  if (!(k >= 1 && k < int64_t(cn))) {           // k == 0: everything is below; k == cn: above
+    ri.hi_incl = (k <= 0) ? __uint_as_float(0x7f800000u) : __uint_as_float(0xff800000u);
+    ri.lo_incl = ri.hi_incl;
+    return ri;
+  }
   const uint32_t span = khi - klo;
   const int nbits = span == 0 ? 0 : 32 - __clz(int(span));
-  const uint32_t* skeys = wide_radix_sort<16, CAP>(ka, b0, b1, cn, klo, nbits, sm);
-  RowInfo ri = RowSolver<kWT>::template solve<MAG, PC, true>(skeys, nullptr, nullptr, int64_t(cn), k,
-                                                             R, sm.solve);
-  if (ri.a <= ri.b && want_jvp) ri.dgamma = list_dgamma<MAG, PC, CAP>(ka, pa, cn, ri, k, R, sm);
+  // s_k and s_{k+1}: the keys of ranks k and k + 1
+  uint32_t below, equal;
+  const uint32_t kk = list_select<CAP>(ka, cn, klo, nbits, uint32_t(k), &below, &equal, sm);
+  uint32_t kk1 = kk;
+  if (uint32_t(k) + 1u > below + equal) {       // rank k + 1 is the next larger key
+    uint32_t nk = 0xffffffffu;
+    for (uint32_t j = threadIdx.x; j < cn; j += kWT) {
+      const uint32_t key = ka[j];
+      if (key > kk) nk = min(nk, key);
+    }
+#pragma unroll
+    for (int off = kWave >> 1; off >= 1; off >>= 1) nk = min(nk, uint32_t(__shfl_xor(nk, off, kWave)));
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) sm.red[0][threadIdx.x / kWave] = nk;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kWW; ++q) nk = min(nk, sm.red[0][q]);
+    kk1 = nk;
+  }
+  const float fk = key_to_float(kk), fk1 = key_to_float(kk1);
+  const double center = P::kCentered ? double(fk) : 0.0;
+  ri.center = center;
+  if (!P::seed_violates(double(fk) - center, double(fk1) - center, R, center)) {
+    ri.hi_incl = fk1;                           // s_{k+1} < s_k: "above hi" = the top k
+    ri.lo_incl = fk;
+    return ri;
+  }
+  auto pooled_of = [&](const SetStats& st) {
+    const double da = double(key_to_float(st.kmin)) - center, db = double(key_to_float(st.kmax)) - center;
+    // bracket of the cubic's root, valid for any set: at its largest value every term is >= 0;
+    // one lambda below its smallest value the sum is <= lambda^3 (m - cnt) <= 0 (magnitude: at 0)
+    return P::pooled(double(st.cnt), double(k - int64_t(st.above)), st.S, R,
+                     MAG ? -center : db - R.lambda, da, center);
+  };
+  SetStats st = list_classify<MAG, PC, CAP>(ka, cn, kk, kk1, 0.0, true, center, R, sm);
+  double g = pooled_of(st);
+  double lo = -1e300, hi = 1e300;
+  bool from_piece = true;                       // g is the root of the piece classified last
+  for (int it = 0; it < 200; ++it) {
+    const SetStats nx = list_classify<MAG, PC, CAP>(ka, cn, kk, kk1, g, false, center, R, sm);
+    const bool same = nx.above == st.above && nx.cnt == st.cnt;
+    st = nx;
+    if (same && from_piece) break;              // the set at its own pooled value: done
+    const double g2 = pooled_of(st);
+    if (g2 == g) break;                         // g is the root of the piece it lies on
+    if (g2 > g) lo = g; else hi = g;
+    from_piece = g2 > lo && g2 < hi;
+    g = from_piece ? g2 : 0.5 * (lo + hi);
+  }
+  ri.a = int64_t(st.above) + 1;
+  ri.b = int64_t(st.above) + int64_t(st.cnt);
+  ri.wa = ri.a;
+  ri.wb = ri.b;
+  ri.gamma = g;
+  ri.hi_incl = key_to_float(st.kmin);
+  ri.lo_incl = key_to_float(st.kmax);
+  if (want_jvp) ri.dgamma = list_dgamma<MAG, PC, CAP>(ka, pa, cn, ri, k, R, sm);
   return ri;
 }
 

@@ -12,8 +12,8 @@
 //      equal keys may come in any order.  Lists of up to kWideLdsCap keys: one bucket pass in LDS
 //      (bucket = leading bits of key - klo, about two keys per bucket; LDS atomics hand out the
 //      places inside a bucket, a count of the smaller keys of the bucket orders them); lists
-//      whose keys crowd into few buckets, and longer lists, take LSD radix passes (in LDS, resp.
-//      through the "b" arrays, which are free by then);
+//      whose keys crowd into few buckets take LSD radix passes in LDS.  Longer lists are not
+//      sorted at all: their block is found as a set of values (sort_solve.hpp);
 //   4. grows the block on the sorted keys (long_solve.hpp);
 //   5. adds up the tangent over the block's elements, found by value in the unsorted list
 //      (Prop. 7), and writes the row's RowInfo: gamma, d gamma and the block's value window.
@@ -170,42 +170,33 @@ __global__ __launch_bounds__(kWT) void wide_finish_kernel(
       ri.dgamma = num / P::jac_denominator(den, double(k - ri.a + 1), R);
     }
   } else {
-    // ---- lists too long for LDS (rare: the window holds more than kWideLdsCap elements): the
-    // same steps through global memory -----------------------------------------------------------
-    int top_step = 1;                          // largest power of two below the number of tiles
-    while (2 * top_step < tiles) top_step *= 2;
-    if (tiles <= 1) top_step = 0;
-    for (uint32_t j0 = threadIdx.x; j0 < cn; j0 += 4 * kWT) {
-      int64_t src[4];
+    // ---- lists too long for LDS (the window holds more than kWideLdsCap elements: a long pooled
+    // block).  Every lane copies whole tiles into the row's dense list, four entries in flight; the
+    // list is then solved as it is, without sorting it (sort_solve.hpp) ---------------------------
+    for (int tl = threadIdx.x; tl < tiles; tl += kWT) {
+      const uint32_t c = tc[tl], o = tf[tl];
+      const int64_t src = int64_t(tl) * kSlotTile;
+      uint32_t e = 0;
+      for (; e + 4 <= c; e += 4) {
+        uint32_t key[4], pay[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t j = j0 + uint32_t(i) * kWT;
-        int lo = 0;                            // invariant: tf[lo] <= j
-        for (int step = top_step; step > 0; step >>= 1) {
-          const int mid = lo + step;
-          const uint32_t o = tf[mid < tiles ? mid : 0];
-          lo = (mid < tiles && o <= j) ? mid : lo;
+        for (int i = 0; i < 4; ++i) {
+          key[i] = kb[src + e + i];
+          pay[i] = want_jvp ? pb[src + e + i] : 0u;
         }
-        src[i] = int64_t(lo) * kSlotTile + int64_t(j - tf[lo]);
-      }
-      uint32_t key[4], pay[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool ok = j0 + uint32_t(i) * kWT < cn;
-        key[i] = ok ? kb[src[i]] : 0u;
-        pay[i] = (ok && want_jvp) ? pb[src[i]] : 0u;
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t j = j0 + uint32_t(i) * kWT;
-        if (j < cn) {
-          ka[j] = key[i];
-          if (want_jvp) pa[j] = pay[i];
+        for (int i = 0; i < 4; ++i) {
+          ka[o + e + i] = key[i];
+          if (want_jvp) pa[o + e + i] = pay[i];
         }
+      }
+      for (; e < c; ++e) {
+        ka[o + e] = kb[src + e];
+        if (want_jvp) pa[o + e] = pb[src + e];
       }
     }
     __syncthreads();
-    ri = solve_global_list<MAG, PC, kWideLdsCap>(ka, pa, kb, pb, cn, k, klo, khi, R, want_jvp, sm);
+    ri = solve_unsorted_list<MAG, PC, kWideLdsCap>(ka, pa, cn, k, klo, khi, R, want_jvp, sm);
   }
   if (threadIdx.x == 0) info[row] = ri;
 }

@@ -79,7 +79,7 @@ def test_argument_validation_of_the_wider_entry_points(lib):
     g = lib.topk_general_fwd
     assert g(one, one, 0, 4, 8, b.TOPK_PHI_IDENTITY, 2.0, 1.0, one, None) != -1     # reaches the launch
     assert g(one, one, 3, 4, 8, 0, 2.0, 1.0, one, None) == -1                       # stride not 0 or n
-    assert g(one, one, 0, 4, 2000, 0, 2.0, 1.0, one, None) == -1                    # rows above 1024
+    assert g(one, one, 0, 4, 200000, 0, 2.0, 1.0, one, None) == -1                  # rows above 131072
     assert g(one, one, 0, 4, 8, 7, 2.0, 1.0, one, None) == -1                       # unknown phi
     assert g(one, one, 0, 4, 8, 0, 1.5, 1.0, one, None) == -3
     assert g(one, None, 0, 4, 8, 0, 2.0, 1.0, one, None) == -2                      # null weights
@@ -96,6 +96,9 @@ def test_argument_validation_of_the_wider_entry_points(lib):
         assert b.workspace_bytes(op, 4, 200, 2, 2.0) >= 2 * 4 * 200 * 4
         assert b.workspace_bytes(op, 2, 5000, 2, 2.0) > b.workspace_bytes(b.TOPK_OP_MASK_JVP, 2, 5000, 2, 2.0)
     lib.topk_set_workspace(None, 0)
+    assert g(one, one, 0, 4, 2000, 0, 2.0, 1.0, one, None) == -4                    # long rows: workspace
+    assert b.workspace_bytes(b.TOPK_OP_GENERAL, 4, 2000, 0, 2.0) > 4 * 2001 * 8 * 4
+    assert b.workspace_bytes(b.TOPK_OP_GENERAL, 4, 1000, 0, 2.0) == 0
     assert lib.topk_signed_mask_fwd(one, 4, 200, 2, 2.0, 1.0, one, None) == -4
     assert lib.topk_masked_value_jvp(one, one, 4, 8, 2, 2.0, 1.0, None, one, None) == -2   # out required
     assert lib.topk_signed_mask_fwd(one, 4, 8, 9, 2.0, 1.0, one, None) == -1

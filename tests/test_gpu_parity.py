@@ -389,10 +389,10 @@ def test_mask_sparse_output_of_longer_rows(gpu, oracle, rows, n):
 
 
 # ---- general non-increasing weights (soft rank / soft sort / partial ranks) -------------------------
-@pytest.mark.parametrize("n", [1, 2, 5, 16, 33, 64, 100, 400, 1024])
+@pytest.mark.parametrize("n", [1, 2, 5, 16, 33, 64, 100, 400, 1024, 1025, 3000, 20000])
 def test_general_weights(gpu, oracle, n):
     r = np.random.default_rng(500 + n)
-    for rows in (1, 37):
+    for rows in ((1, 37) if n <= 1024 else (1, 5)):
         x = (r.normal(size=(rows, n)) * 2).astype(np.float32)
         if n >= 4:
             x[:, 1] = x[:, 0]
@@ -447,7 +447,7 @@ def test_general_weights_many_rounds_and_stack_fallback(gpu, oracle):
     them), so the wavefront hands over to the sequential block stack; and ordinary rows with the
     hand-over forced after 1 and 3 rounds."""
     r = np.random.default_rng(91)
-    for n in (300, 1024):
+    for n in (300, 1024, 5000):
         x = r.normal(size=(6, n)).astype(np.float32)
         w = -np.sort(-np.abs(r.normal(size=(6, n))).astype(np.float32), axis=1)
         ramp = (10.0 - 0.001 * np.arange(n)).astype(np.float32)
@@ -471,6 +471,27 @@ def test_general_weights_many_rounds_and_stack_fallback(gpu, oracle):
                         gpu.set_route(gpu.TOPK_ROUTE_GENERAL_ROUNDS, 0)
                     close(out, ref["out"], f"general fwd rounds={rounds}")
                     close(jv, ref["jvp"], f"general jvp rounds={rounds}")
+
+
+def test_general_weights_longest_row(gpu, oracle):
+    """One row of TOPK_GENERAL_ROW_MAX elements: relaxed ranks (many blocks of every size) and a
+    partial-rank weight vector, both p."""
+    n = 131072
+    r = np.random.default_rng(17)
+    x = (r.normal(size=(1, n)) * 3).astype(np.float32)
+    t = r.normal(size=(1, n)).astype(np.float32)
+    rho = np.arange(n, 0, -1).astype(np.float32)
+    for w, lam in ((rho * np.float32(1e-4), 0.5), (np.maximum(rho - (n - 2000), 0.0).astype(np.float32), 0.01)):
+        for p in (P2, P43):
+            for phi, phic in (("id", gpu.TOPK_PHI_IDENTITY), ("half_sq", gpu.TOPK_PHI_HALF_SQUARE)):
+                print(f"longest general row phi={phi} p={p:.3f} lam={lam}", flush=True)
+                ref = oracle.topk_general(x, w, p, lam, phi, tangent=t)
+                out, jv = (host(a) for a in gpu.topk_general_jvp(dev(x), dev(w), dev(t), phic, p, lam))
+                close(out, ref["out"], "general fwd")
+                close(jv, ref["jvp"], "general jvp")
+    with pytest.raises(gpu.TopkError):
+        gpu.topk_general_fwd(dev(np.zeros((1, n + 1), dtype=np.float32)),
+                             dev(np.zeros(n + 1, dtype=np.float32)), gpu.TOPK_PHI_IDENTITY, P2, 1.0)
 
 
 # ---- Dykstra's algorithm with a fixed number of iterations ----------------------------------------
