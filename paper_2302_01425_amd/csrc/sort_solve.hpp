@@ -614,9 +614,16 @@ __device__ uint32_t list_select(const uint32_t* list, uint32_t cn, uint32_t klo,
     uint32_t* hist = sm.u.bucket;
     for (uint32_t i = threadIdx.x; i < bins; i += kWT) hist[i] = 0;
     __syncthreads();
-    for (uint32_t j = threadIdx.x; j < cn; j += kWT) {
-      const uint32_t u = list[j] - klo;
-      if ((u & pmask) == prefix) atomicAdd(&hist[(u >> shift) & (bins - 1u)], 1u);
+    for (uint32_t j0 = threadIdx.x; j0 < cn; j0 += 8 * kWT) {     // eight loads in flight
+      uint32_t key[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) key[i] = j0 + uint32_t(i) * kWT < cn ? list[j0 + uint32_t(i) * kWT] : 0u;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t u = key[i] - klo;
+        if (j0 + uint32_t(i) * kWT < cn && (u & pmask) == prefix)
+          atomicAdd(&hist[(u >> shift) & (bins - 1u)], 1u);
+      }
     }
     __syncthreads();
     const uint32_t b0 = 2u * threadIdx.x, b1 = b0 + 1u;       // two bins per thread (2048 at most)
@@ -644,48 +651,52 @@ struct SetStats {
   Sums S;                    // power sums of the members' centred values
 };
 
-// One pass over the list: the set at the pooled value g (centred), or, with seed_only, just the
-// values from s_{k+1} to s_k (keys kk .. kk1).
+// smallest key whose value is strictly below T / largest key whose value is strictly above T
+// (keys run against values; key + 1 is the next smaller value)
+__device__ __forceinline__ uint32_t first_key_below(double T) {
+  const float f = __double2float_rn(T);
+  return desc_key(f) + (double(f) >= T ? 1u : 0u);
+}
+__device__ __forceinline__ uint32_t last_key_above(double T) {
+  const float f = __double2float_rn(T);
+  return desc_key(f) - (double(f) <= T ? 1u : 0u);
+}
+
+// One pass over the list: the set at the pooled value g (centred).  Membership is a value
+// interval: a candidate above s_k is in iff its singleton minimiser lies below g, i.e. its value
+// below T_hi(g) = g + lambda (mask), g (1 + lambda) (magnitude, p = 2), g + lambda g^(1/3)
+// (magnitude, p = 4/3: where the one-element cubic at g changes sign); one below s_{k+1} iff its
+// value lies above g; the values from s_{k+1} to s_k (keys kk .. kk1) always.
 template <bool MAG, int PC, int CAP>
 __device__ SetStats list_classify(const uint32_t* list, uint32_t cn, uint32_t kk, uint32_t kk1,
-                                  double g, bool seed_only, double center, const Reg& R,
-                                  ListShared<CAP>& sm) {
+                                  double g, double center, const Reg& R, ListShared<CAP>& sm) {
   constexpr bool CUBIC = (PC == kP43);
+  const double g_abs = g + center;
+  double t_hi;
+  if (MAG && CUBIC) t_hi = g_abs + R.lambda * cbrt(fmax(g_abs, 0.0));
+  else if (MAG) t_hi = g_abs * R.one_p_lambda;
+  else t_hi = g_abs + R.lambda;
+  const uint32_t k_first = min(first_key_below(t_hi), kk);      // members: k_first <= key <= k_last
+  const uint32_t k_last = max(last_key_above(g_abs), kk1);
   uint32_t above = 0, cnt = 0, kmin = 0xffffffffu, kmax = 0u;
   Sums S{0.0, 0.0, 0.0};
-  const double g_abs = g + center;
-  for (uint32_t j0 = threadIdx.x; j0 < cn; j0 += 4 * kWT) {
-    uint32_t key[4];
+  for (uint32_t j0 = threadIdx.x; j0 < cn; j0 += 8 * kWT) {     // eight loads in flight
+    uint32_t key[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) key[i] = j0 + uint32_t(i) * kWT < cn ? list[j0 + uint32_t(i) * kWT] : 0u;
+    for (int i = 0; i < 8; ++i)
+      key[i] = j0 + uint32_t(i) * kWT < cn ? list[j0 + uint32_t(i) * kWT] : 0xffffffffu;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (j0 + uint32_t(i) * kWT >= cn) continue;
-      const double v = double(key_to_float(key[i]));
-      const double d = v - center;
-      bool in = key[i] >= kk && key[i] <= kk1;
-      if (!seed_only && !in) {
-        if (key[i] < kk) {                       // above s_k: its singleton minimiser below g?
-          if (MAG && CUBIC) {
-            const double u = g_abs - v;          // sign of the one-element cubic at g
-            in = u * u * u + R.lam3 * g_abs > 0.0;
-          } else if (MAG) {
-            in = v < g_abs * R.one_p_lambda;
-          } else {
-            in = d - R.lambda < g;
-          }
-        } else {                                 // below s_{k+1}: its value above g?
-          in = d > g;
-        }
-      }
+    for (int i = 0; i < 8; ++i) {
+      const bool real = j0 + uint32_t(i) * kWT < cn;
+      const bool in = real && key[i] >= k_first && key[i] <= k_last;
+      above += (real && key[i] < k_first) ? 1u : 0u;
       if (in) {
         ++cnt;
         kmin = min(kmin, key[i]);
         kmax = max(kmax, key[i]);
+        const double d = double(key_to_float(key[i])) - center;
         S.s1 += d;
         if (CUBIC) { S.s2 += d * d; S.s3 += d * d * d; }
-      } else if (key[i] < kk) {
-        ++above;
       }
     }
   }
@@ -777,12 +788,15 @@ __device__ RowInfo solve_unsorted_list(const uint32_t* ka, const uint32_t* pa, u
     return P::pooled(double(st.cnt), double(k - int64_t(st.above)), st.S, R,
                      MAG ? -center : db - R.lambda, da, center);
   };
-  SetStats st = list_classify<MAG, PC, CAP>(ka, cn, kk, kk1, 0.0, true, center, R, sm);
-  double g = pooled_of(st);
+  // start: the pooled value of the pair (s_k, s_{k+1}) alone
+  const double dk = double(fk) - center, dk1 = double(fk1) - center;
+  Sums S2{dk + dk1, dk * dk + dk1 * dk1, dk * dk * dk + dk1 * dk1 * dk1};
+  double g = P::pooled(2.0, 1.0, S2, R, MAG ? -center : dk1 - R.lambda, dk, center);
+  SetStats st{0xffffffffu, 0xffffffffu, 0u, 0u, Sums{0.0, 0.0, 0.0}};
   double lo = -1e300, hi = 1e300;
-  bool from_piece = true;                       // g is the root of the piece classified last
+  bool from_piece = false;                      // g is the root of the piece classified last
   for (int it = 0; it < 200; ++it) {
-    const SetStats nx = list_classify<MAG, PC, CAP>(ka, cn, kk, kk1, g, false, center, R, sm);
+    const SetStats nx = list_classify<MAG, PC, CAP>(ka, cn, kk, kk1, g, center, R, sm);
     const bool same = nx.above == st.above && nx.cnt == st.cnt;
     st = nx;
     if (same && from_piece) break;              // the set at its own pooled value: done

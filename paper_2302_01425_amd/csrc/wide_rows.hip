@@ -171,28 +171,32 @@ __global__ __launch_bounds__(kWT) void wide_finish_kernel(
     }
   } else {
     // ---- lists too long for LDS (the window holds more than kWideLdsCap elements: a long pooled
-    // block).  Every lane copies whole tiles into the row's dense list, four entries in flight; the
-    // list is then solved as it is, without sorting it (sort_solve.hpp) ---------------------------
-    for (int tl = threadIdx.x; tl < tiles; tl += kWT) {
-      const uint32_t c = tc[tl], o = tf[tl];
-      const int64_t src = int64_t(tl) * kSlotTile;
-      uint32_t e = 0;
-      for (; e + 4 <= c; e += 4) {
-        uint32_t key[4], pay[4];
+    // block).  A wavefront copies sixteen tiles at a time into the row's dense list (their loads in
+    // flight together); the list is then solved as it is, without sorting it (sort_solve.hpp) ----
+    for (int t0 = w * 16; t0 < tiles; t0 += kWW * 16) {
+      const int tl_l = t0 + (lane & 15);
+      const uint32_t c_l = tl_l < tiles ? tc[tl_l] : 0u, o_l = tl_l < tiles ? tf[tl_l] : 0u;
+      uint32_t cmax = c_l;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          key[i] = kb[src + e + i];
-          pay[i] = want_jvp ? pb[src + e + i] : 0u;
+      for (int off = 8; off >= 1; off >>= 1) cmax = max(cmax, uint32_t(__shfl_xor(cmax, off, kWave)));
+      for (uint32_t ch = 0; ch < cmax; ch += kWave) {
+        const uint32_t e = ch + lane;
+        uint32_t key[16], pay[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const uint32_t c = __shfl(c_l, q, kWave);
+          const int64_t src = int64_t(t0 + q) * kSlotTile + e;
+          key[q] = e < c ? kb[src] : 0u;
+          pay[q] = (e < c && want_jvp) ? pb[src] : 0u;
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          ka[o + e + i] = key[i];
-          if (want_jvp) pa[o + e + i] = pay[i];
+        for (int q = 0; q < 16; ++q) {
+          const uint32_t c = __shfl(c_l, q, kWave), o = __shfl(o_l, q, kWave);
+          if (e < c) {
+            ka[o + e] = key[q];
+            if (want_jvp) pa[o + e] = pay[q];
+          }
         }
-      }
-      for (; e < c; ++e) {
-        ka[o + e] = kb[src + e];
-        if (want_jvp) pa[o + e] = pb[src + e];
       }
     }
     __syncthreads();
