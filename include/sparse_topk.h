@@ -160,7 +160,7 @@ int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n,
  * j < min(nnz_out[r], max_nnz); the remaining slots hold -1 / 0.0f.  nnz_out[r] is the number of
  * non-zeros (k <= nnz <= n for k >= 1); if it exceeds max_nnz the list was cut off.
  *   theta [rows][n] in; idx_out (int32) and val_out (float) [rows][max_nnz], nnz_out (int32) [rows]
- *   out.  1 <= max_nnz <= n.  Rows up to 131072 elements (TOPK_ERR_INVALID beyond).  Rows above
+ *   out.  1 <= max_nnz <= n.  Rows above
  *   TOPK_SHORT_ROW_MAX need the workspace of TOPK_OP_MASK_FWD, and their lists are ordered
  *   differently: first the entries that lie above everything that can pool (value exactly 1), in
  *   ascending index order, then the remaining non-zeros in descending order of theta.

@@ -56,7 +56,7 @@ enum LongMode { kAuto = TOPK_LONG_ROWS_AUTO, kSelect = TOPK_LONG_ROWS_SELECT,
 LongMode long_mode() { return static_cast<LongMode>(topk::routes().long_rows); }
 
 struct Layout {
-  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, hpart, bins, tile_hist2, bins2, tcnt, tabove, toff, sel, total;
+  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, hpart, bins, tile_hist2, bins2, tcnt, tabove, toff, taboff, sel, total;
 };
 
 Layout layout_for(int64_t rows, int64_t n) {
@@ -78,6 +78,7 @@ Layout layout_for(int64_t rows, int64_t n) {
   L.tcnt = off; off += align_up(size_t(rows) * tiles * 4);
   L.tabove = off; off += align_up(size_t(rows) * tiles * 4);
   L.toff = off; off += align_up(size_t(rows) * tiles * 4);
+  L.taboff = off; off += align_up(size_t(rows) * tiles * 4);
   L.sel = off; off += align_up(size_t(rows) * sizeof(RowSel));
   L.total = off;
   return L;
@@ -102,6 +103,7 @@ int carve(int64_t rows, int64_t n, SortBuffers* B, size_t skip = 0, const Worksp
   B->tcnt = reinterpret_cast<uint32_t*>(base + L.tcnt);
   B->tabove = reinterpret_cast<uint32_t*>(base + L.tabove);
   B->toff = reinterpret_cast<uint32_t*>(base + L.toff);
+  B->taboff = reinterpret_cast<uint32_t*>(base + L.taboff);
   B->sel = reinterpret_cast<RowSel*>(base + L.sel);
   return TOPK_OK;
 }
@@ -358,13 +360,32 @@ int topk_mask_sparse_fwd(const float* theta, int64_t rows, int64_t n, int64_t k,
                          int32_t* nnz_out, void* stream) {
   const int rc = check_shape(rows, n, k, lambda);
   if (rc != TOPK_OK) return rc;
-  if (n > topk::kMediumRowMax || max_nnz < 1 || max_nnz > n) return TOPK_ERR_INVALID;
+  if (max_nnz < 1 || max_nnz > n || max_nnz > 0x7fffffffLL) return TOPK_ERR_INVALID;
   const int pc = p_code(p);
   if (pc < 0) return TOPK_ERR_UNSUPPORTED_P;
   if (rows == 0) return TOPK_OK;
   if (theta == nullptr || idx_out == nullptr || val_out == nullptr || nnz_out == nullptr)
     return TOPK_ERR_NULL;
   const topk::SparseOut sp{idx_out, val_out, nnz_out, int(max_nnz)};
+  if (n > topk::kMediumRowMax) {
+    // rows spread over many workgroups: the selection route with (key, index) lists, then the
+    // lists' leading positions
+    SortBuffers B;
+    const int wrc = carve(rows, n, &B);
+    if (wrc != TOPK_OK) return wrc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Reg R = make_reg(lambda);
+    begin();
+    if (k >= 1 && k < n) {
+      if (topk::launch_candidate_lists(false, pc, theta, rows, n, k, R, B, st) != 0 ||
+          topk::launch_finish(false, pc, B, nullptr, rows, n, k, R, st) != 0 ||
+          topk::launch_long_list_sort(false, rows, n, B, st) != 0 ||
+          topk::launch_long_solve(false, pc, true, B, nullptr, rows, n, k, R, st) != 0)
+        return TOPK_ERR_INVALID;
+    }
+    if (topk::launch_long_sparse(pc, B, theta, rows, n, k, R, sp, st) != 0) return TOPK_ERR_INVALID;
+    return finish();
+  }
   if (is_long(n)) {
     SortBuffers B;
     const int wrc = carve(rows, n, &B);

@@ -70,6 +70,7 @@ struct SortBuffers {
   uint32_t* tcnt;     // [rows][tiles] candidates per tile
   uint32_t* tabove;   // [rows][tiles] elements above the candidate window per tile
   uint32_t* toff;     // [rows][tiles] start of the tile's candidates in the row's dense list
+  uint32_t* taboff;   // [rows][tiles] elements above the candidate window in the tiles before
   RowSel* sel;        // [rows]
 };
 
@@ -125,6 +126,14 @@ constexpr int64_t kFinishMax = 32768;
 
 // selected: B.sel describes candidate lists (see RowSel), and rows whose list is at most
 // kFinishMax long already have their RowInfo; otherwise the "a" arrays hold fully sorted rows.
+// only the solve of launch_long_tail: B.info[row] of every row not solved yet
+int launch_long_solve(bool mag, int pc, bool selected, const SortBuffers& B, const float* tangent,
+                      int64_t rows, int64_t n, int64_t k, const Reg& R, hipStream_t st);
+// Compact output of the mask for rows above kMediumRowMax elements, after the candidate lists
+// have been sorted and solved (launch_candidate_lists .. launch_long_solve): the elements above
+// the candidate window in index order, then sorted list positions 1..b.
+int launch_long_sparse(int pc, const SortBuffers& B, const float* x, int64_t rows, int64_t n,
+                       int64_t k, const Reg& R, const SparseOut& sp, hipStream_t st);
 int launch_long_tail(bool mag, int pc, bool selected, const SortBuffers& B, const float* x,
                      const float* tangent, float* out, float* jvp, int64_t rows, int64_t n,
                      int64_t k, const Reg& R, hipStream_t st);

@@ -199,6 +199,21 @@ int launch_wide_dense(bool mag, int pc, const SortBuffers& B, const float* x, co
   return 0;
 }
 
+int launch_long_solve(bool mag, int pc, bool selected, const SortBuffers& B, const float* tangent,
+                      int64_t rows, int64_t n, int64_t k, const Reg& R, hipStream_t st) {
+  if (rows > 0x7fffffffLL) return -1;
+#define TOPK_LONG_SOLVE(M, P)                                                                      \
+  hipLaunchKernelGGL((long_solve_kernel<M, P>), dim3(unsigned(rows)), dim3(kSolveThreads), 0, st,  \
+                     B.keys_a, B.idx_a, tangent, B.info, selected ? B.sel : nullptr, n, k, R)
+  if (!mag && pc == kP2) TOPK_LONG_SOLVE(false, kP2);
+  else if (!mag && pc == kP43) TOPK_LONG_SOLVE(false, kP43);
+  else if (mag && pc == kP2) TOPK_LONG_SOLVE(true, kP2);
+  else if (mag && pc == kP43) TOPK_LONG_SOLVE(true, kP43);
+  else return -1;
+#undef TOPK_LONG_SOLVE
+  return 0;
+}
+
 int launch_long_tail(bool mag, int pc, bool selected, const SortBuffers& B, const float* x,
                      const float* tangent, float* out, float* jvp, int64_t rows, int64_t n,
                      int64_t k, const Reg& R, hipStream_t st) {

@@ -640,36 +640,44 @@ __global__ __launch_bounds__(kThreads) void select_recompact_kernel(
 __global__ __launch_bounds__(kThreads) void select_offsets_kernel(const uint32_t* __restrict__ tcnt,
                                                                   const uint32_t* __restrict__ tabove,
                                                                   uint32_t* __restrict__ toff,
+                                                                  uint32_t* __restrict__ taboff,
                                                                   RowSel* __restrict__ sel,
                                                                   int tiles) {
   __shared__ uint32_t wave_tot[kWaves];
   const int64_t row = blockIdx.x;
-  uint32_t carry = 0, above = 0;
+  uint32_t carry = 0, carry_above = 0;
   constexpr int kPer = 16;               // consecutive tiles per thread: all loads in flight at once
   for (int c = 0; c < tiles; c += kThreads * kPer) {
     const int t0 = c + threadIdx.x * kPer;
-    uint32_t v[kPer], mine = 0;
+    uint32_t v[kPer], ab[kPer], mine = 0, mine_above = 0;
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
       v[i] = (t0 + i < tiles) ? tcnt[row * tiles + t0 + i] : 0u;
-      above += (t0 + i < tiles) ? tabove[row * tiles + t0 + i] : 0u;
+      ab[i] = (t0 + i < tiles) ? tabove[row * tiles + t0 + i] : 0u;
     }
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) mine += v[i];
-    uint32_t total;
-    uint32_t run = carry + block_exclusive_scan(mine, wave_tot, &total);
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-      if (t0 + i < tiles) toff[row * tiles + t0 + i] = run;
+      mine += v[i];
+      mine_above += ab[i];
+    }
+    uint32_t total, total_above;
+    uint32_t run = carry + block_exclusive_scan(mine, wave_tot, &total);
+    uint32_t run_above = carry_above + block_exclusive_scan(mine_above, wave_tot, &total_above);
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      if (t0 + i < tiles) {
+        toff[row * tiles + t0 + i] = run;
+        taboff[row * tiles + t0 + i] = run_above;   // elements above the window in earlier tiles
+      }
       run += v[i];
+      run_above += ab[i];
     }
     carry += total;
+    carry_above += total_above;
   }
-  uint32_t above_all;
-  block_exclusive_scan(above, wave_tot, &above_all);
   if (threadIdx.x == 0) {
     sel[row].cn = carry;
-    sel[row].above = int64_t(above_all);
+    sel[row].above = int64_t(carry_above);
   }
 }
 
@@ -771,7 +779,7 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
   hipLaunchKernelGGL((select_recompact_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, st,
                      B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles, nullptr);
   hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
-                     B.tabove, B.toff, B.sel, tiles);
+                     B.tabove, B.toff, B.taboff, B.sel, tiles);
   hipLaunchKernelGGL(select_gather_kernel, dim3(blocks), dim3(kThreads), 0, st, B.tcnt, B.toff,
                      B.keys_b, B.idx_b, B.keys_a, B.idx_a, n, tiles);
 }

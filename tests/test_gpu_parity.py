@@ -355,7 +355,8 @@ def test_mask_sparse_output(gpu, oracle, n):
                         assert np.all(idx[row, m:] == -1) and np.all(val[row, m:] == 0.0)
 
 
-@pytest.mark.parametrize("rows,n", [(3, 1025), (5, 5000), (2, 8193), (64, 32768), (1, 131072)])
+@pytest.mark.parametrize("rows,n", [(3, 1025), (5, 5000), (2, 8193), (64, 32768), (1, 131072),
+                                    (2, 131073), (2, 300001)])
 def test_mask_sparse_output_of_longer_rows(gpu, oracle, rows, n):
     """Rows above 1024 elements: the list holds the same (index, value) pairs as the dense output
     has non-zeros; entries of value 1 above the key window come first in index order, the rest
@@ -378,7 +379,10 @@ def test_mask_sparse_output_of_longer_rows(gpu, oracle, rows, n):
                 got_i, got_v = idx[row, :m], val[row, :m]
                 assert np.all(idx[row, m:] == -1) and np.all(val[row, m:] == 0.0)
                 assert len(np.unique(got_i)) == m and got_i.min(initial=0) >= 0
-                assert np.array_equal(got_v, dense[row, got_i])          # the same values as the dense call
+                if n <= 131072:
+                    assert np.array_equal(got_v, dense[row, got_i])      # the same values as the dense call
+                else:           # another solver behind the dense call: the same to rounding
+                    close(got_v, dense[row, got_i], "sparse vs dense")
                 close(got_v, ref["out"][row, got_i], "sparse values")
                 ones = int(np.argmax(got_v != 1.0)) if (got_v != 1.0).any() else m
                 if m == b:      # the whole list: exactly the oracle's non-zero set
