@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="moe_router")
+    ap.add_argument("--op", choices=["jvp", "signed_mask_jvp", "masked_value_jvp", "loss"], default="jvp",
+                    help="side run: time another entry point on the workload's inputs (mask workloads): "
+                         "the operators on |x| or the Fenchel-Young loss, instead of forward + JVP")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph",
                     help="graph: the K launches are captured once in a HIP graph and replayed; "
                          "stream: K plain launches from Python")
@@ -62,7 +65,7 @@ def parse():
 class Runner:
     """Pre-marshalled calls into the C ABI (no allocation, no tensor checks in the timed loop)."""
 
-    def __init__(self, w, sets, device):
+    def __init__(self, w, sets, device, entry="jvp"):
         import ctypes
         import torch
         from paper_2302_01425_amd import binding
@@ -77,6 +80,17 @@ class Runner:
         op = binding.TOPK_OP_MASK_JVP if w.op == "mask" else binding.TOPK_OP_MAG_JVP
         binding.ensure_workspace(op, w.rows, w.n, w.k, w.p, device)
         self.fn = self.lib.topk_mask_jvp if w.op == "mask" else self.lib.topkmag_jvp
+        if entry != "jvp":
+            if w.op != "mask":
+                raise SystemExit("--op needs a mask workload")
+            which = {"signed_mask_jvp": binding.TOPK_OP_SIGNED_MASK,
+                     "masked_value_jvp": binding.TOPK_OP_MASKED_VALUE, "loss": binding.TOPK_OP_MASK_FWD}[entry]
+            binding.ensure_workspace(which, w.rows, w.n, w.k, w.p, device)
+            self.fn = {"signed_mask_jvp": self.lib.topk_signed_mask_jvp,
+                       "masked_value_jvp": self.lib.topk_masked_value_jvp,
+                       "loss": self.lib.topk_mask_loss}[entry]
+        # (the loss takes (theta, target, .., loss_out [rows], grad_out): the first floats of the
+        # third buffer hold the per-row losses)
         self.args = [(ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()),
                       ctypes.c_int64(w.rows), ctypes.c_int64(w.n), ctypes.c_int64(w.k),
                       ctypes.c_double(w.p), ctypes.c_double(w.lam),
@@ -319,8 +333,18 @@ def main():
     w = WORKLOADS[a.workload]
     algo_bytes = BYTES_PER_ELEMENT * w.rows * w.n
     set_bytes = 4 * 4 * w.rows * w.n
-    sets = max(2, -(-a.cold_mib * (1 << 20) // set_bytes))
-    r = Runner(w, sets, "cuda:0")
+    sets = min(64, max(2, -(-a.cold_mib * (1 << 20) // set_bytes)))   # (tiny: 64 sets are plenty)
+    r = Runner(w, sets, "cuda:0", a.op)
+    if a.op != "jvp":
+        # side run: another entry point on the same inputs; its own byte model (the loss reads
+        # theta and the target and writes the gradient and one float per row)
+        per_b = 12.0 + 4.0 / w.n if a.op == "loss" else 16.0
+        ms, reps = r.timed(a.steps, a.warmup, a.mode, rotate=True)
+        print(json.dumps({"side_run": a.op, "workload": w.name, "steps": a.steps, "repeats": reps,
+                          "ms_per_step": ms, "algorithmic_bytes_per_element": per_b,
+                          "gbps": per_b * w.rows * w.n / (ms * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": per_b * w.rows * w.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}))
+        return
     if a.copy_calibration:
         r.enable_copy_mode()
         ms, reps = r.timed(a.steps, a.warmup, a.mode, rotate=True)
