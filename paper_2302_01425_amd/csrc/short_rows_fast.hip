@@ -416,7 +416,8 @@ __global__ __launch_bounds__((FastCfg<GL, E>::WPB * kWave)) void short_rows_fast
       const double da = double(ls[a - 1]) - center, db = double(ls[b - 1]) - center;
       if (MAG) gamma = S.s1 * recip(cnt + R.lambda * m);
       else if (!CUBIC) gamma = (S.s1 - R.lambda * m) * recip(cnt);
-      else gamma = P::pooled(cnt, m, S, R, da - R.lambda, db);
+      else if (grew) gamma = P::pooled(cnt, m, S, R, da - R.lambda, db);   // (rows without a
+      // block skip the Newton solve: their sums may hold the -inf of an unlisted s_{k+1})
       gamma = grew ? gamma : 0.0;
     }
   }

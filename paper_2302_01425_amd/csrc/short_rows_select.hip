@@ -351,7 +351,8 @@ __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
       const double da = double(fa) - center, db = double(fb) - center;
       if (MAG) gamma = S.s1 * recip(cnt + R.lambda * m);
       else if (!CUBIC) gamma = (S.s1 - R.lambda * m) * recip(cnt);
-      else gamma = P::pooled(cnt, m, S, R, da - R.lambda, db);
+      else if (grew) gamma = P::pooled(cnt, m, S, R, da - R.lambda, db);   // (rows without a
+      // block skip the Newton solve: their sums may hold the -inf of an unlisted s_{k+1})
       gamma = grew ? gamma : 0.0;
       one_gt = grew ? fa : one_gt;
       blk_ge = grew ? fb : blk_ge;
