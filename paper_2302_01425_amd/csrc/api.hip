@@ -148,6 +148,16 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
     return finish();
   }
   const LongMode mode = long_mode();
+  // rows of up to 2048 elements still fit one wavefront's registers as values
+  if (mode == kAuto && n <= 2048 && topk::routes().short_kernel == TOPK_SHORT_ROW_KERNEL_AUTO) {
+    const bool vec = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(tangent) |
+                                       reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(jvp)) & 15u) == 0;
+    const int vrc = topk::launch_short_rows_value_wide(2048, vec, mag, pc, x, need_jvp ? tangent : nullptr,
+                                                       out, need_jvp ? jvp : nullptr, rows, int(n),
+                                                       int(k), R, st);
+    if (vrc == 0) return finish();
+    if (vrc != -2) return TOPK_ERR_INVALID;
+  }
   // k = 0 and k = n pool nothing and read no sorted value: no sort at all
   const bool trivial = (k == 0 || k == n);
   // Rows above 32768 elements: the streaming steps of a row are spread over many workgroups

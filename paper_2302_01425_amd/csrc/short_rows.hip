@@ -456,6 +456,10 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
     const int rc = launch_short_rows_fast(np, lg, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
     if (rc != -2) return rc;
   }
+  if (np >= 256 && value_enabled()) {
+    const int rc = launch_short_rows_value_wide(np, vec, mag, pc, x, tangent, out, jvp, rows, n, k, R, st);
+    if (rc != -2) return rc;
+  }
   TOPK_SHAPE_TABLE
 #undef CALL
   return -1;
