@@ -221,7 +221,7 @@ int topk_mask_dykstra_fwd(const float* theta, int64_t rows, int64_t n, int64_t k
  * y = x o m(|x|), dy = t o m(|x|) + x o J_m (sign(x) o t).
  *
  *   x, tangent [rows][n] in; out, jvp_out [rows][n] out (out is required by the *_jvp calls too).
- *   Rows of 3..128 elements run in one kernel and need no workspace; other row lengths need two
+ *   Rows of 3..2048 elements run in one kernel and need no workspace; other row lengths need two
  *   float arrays of the input's size, plus the mask's own for long rows:
  *   topk_workspace_bytes(TOPK_OP_SIGNED_MASK / TOPK_OP_MASKED_VALUE).
  *   Otherwise the arguments, p values and errors of topk_mask_fwd / topk_mask_jvp.
@@ -243,7 +243,7 @@ int topk_masked_value_jvp(const float* x, const float* tangent, int64_t rows, in
  * y = grad_1 f_{phi,R}).  f is evaluated through the maximisation form of Prop. 2 at its maximiser
  * y: f = <y, theta> - (lambda / p) sum_i y_i^p.
  *   theta, target [rows][n] in (target: usually a 0/1 encoding of the wanted classes),
- *   loss_out [rows] out, grad_out [rows][n] out (required: beyond 128 elements per row it also
+ *   loss_out [rows] out, grad_out [rows][n] out (required: beyond 2048 elements per row it also
  *   carries the mask between the two kernels; shorter rows take one kernel).  Same shape rules, p values, workspace needs and errors as topk_mask_fwd.
  */
 int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_t n, int64_t k,

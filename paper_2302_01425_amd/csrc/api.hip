@@ -205,10 +205,10 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
 // kernels run on them into (out, jvp), an element-wise pass turns those into the results.
 size_t abs_scratch_bytes(int64_t rows, int64_t n) { return 2 * align_up(size_t(rows) * size_t(n) * 4); }
 
-// Rows of 3..128 elements: these operators run inside the short-row kernel and need no scratch
+// Rows of 3..2048 elements: these operators run inside the short-row kernel and need no scratch
 // (unless another short-row kernel was asked for with topk_set_route).
 bool abs_fused(int64_t n) {
-  return n >= 3 && n <= 128 && topk::routes().short_kernel == TOPK_SHORT_ROW_KERNEL_AUTO;
+  return n >= 3 && n <= 2048 && topk::routes().short_kernel == TOPK_SHORT_ROW_KERNEL_AUTO;
 }
 
 int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int64_t rows,
@@ -221,7 +221,7 @@ int run_abs_operator(bool signed_mask, const float* x, const float* tangent, int
   if (rows == 0) return TOPK_OK;
   if (x == nullptr || out == nullptr) return TOPK_ERR_NULL;
   if (need_jvp && (jvp == nullptr || tangent == nullptr)) return TOPK_ERR_NULL;
-  // rows of up to 128 elements: one fused kernel, no scratch
+  // rows of up to 2048 elements: one fused kernel, no scratch
   if (abs_fused(n)) {
     begin();
     const int frc = topk::launch_short_rows_fused_variant(
@@ -492,9 +492,9 @@ int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_
     const int rc = check_shape(rows, n, k, lambda);
     return rc != TOPK_OK ? rc : (p_code(p) < 0 ? TOPK_ERR_UNSUPPORTED_P : TOPK_ERR_NULL);
   }
-  if (rows > 0 && !is_long(n) && grad_out != nullptr && theta != nullptr &&
+  if (rows > 0 && n <= 2048 && grad_out != nullptr && theta != nullptr &&
       check_shape(rows, n, k, lambda) == TOPK_OK && p_code(p) >= 0) {
-    // rows of up to 128 elements: mask, loss and gradient in one kernel
+    // rows of up to 2048 elements: mask, loss and gradient in one kernel
     const double p_ex = p_code(p) == topk::kP2 ? 2.0 : 4.0 / 3.0;
     begin();
     const int frc = topk::launch_short_rows_fused_variant(
@@ -557,8 +557,9 @@ size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p
     return topk::general_long_bytes(rows, n, p_code(p) == topk::kP2 ? topk::kP2 : topk::kP43) +
            layout_for(rows, n).total;
   }
-  const size_t own = ((op == TOPK_OP_SIGNED_MASK || op == TOPK_OP_MASKED_VALUE) && !abs_fused(n))
-                         ? abs_scratch_bytes(rows, n) : 0;
+  const bool abs_op = op == TOPK_OP_SIGNED_MASK || op == TOPK_OP_MASKED_VALUE;
+  if (abs_op && abs_fused(n)) return 0;
+  const size_t own = abs_op ? abs_scratch_bytes(rows, n) : 0;
   if (!is_long(n)) return own;
   return own + layout_for(rows, n).total;
 }

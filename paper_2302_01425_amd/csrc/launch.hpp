@@ -102,6 +102,10 @@ int launch_short_rows_value(int np, int lg, bool vec, bool mag, int pc, const fl
 int launch_short_rows_value_wide(int np, bool vec, bool mag, int pc, const float* x,
                                  const float* tangent, float* out, float* jvp, int64_t rows, int n,
                                  int k, const Reg& R, hipStream_t st);
+int launch_short_rows_variant_wide(int np, bool vec, int var, int pc, const float* x,
+                                   const float* tangent, float* out, float* jvp, float* loss,
+                                   double lam_over_p, int64_t rows, int n, int k, const Reg& R,
+                                   hipStream_t st);
 int launch_short_rows_variant(int np, int lg, bool vec, int var, int pc, const float* x,
                               const float* tangent, float* out, float* jvp, float* loss,
                               double lam_over_p, int64_t rows, int n, int k, const Reg& R,

@@ -465,7 +465,7 @@ int launch_short_rows(bool mag, int pc, const float* x, const float* tangent, fl
   return -1;
 }
 
-// The operators built on the mask, fused into the value-ordering kernel of rows up to 128
+// The operators built on the mask, fused into the value-ordering kernel of rows up to 2048
 // elements (var: 1 signed mask, 2 x o mask(|x|), 3 Fenchel-Young loss with tangent = target and
 // out = gradient).  Returns -2 when no fused kernel fits the shape: the caller then runs the
 // mask kernels between element-wise passes.
@@ -477,6 +477,9 @@ int launch_short_rows_fused_variant(int var, int pc, const float* x, const float
                    aligned16(jvp);
   int np = 2;
   while (np < n) np <<= 1;
+  if (np >= 256 && np <= 2048)
+    return launch_short_rows_variant_wide(np, vec, var, pc, x, tangent, out, jvp, loss, lam_over_p,
+                                          rows, n, k, R, st);
   if (np < 4 || np > 128) return -2;
   // the kernel's shapes: 1..16 lanes per row with 4 or 8 elements each
   int lg = pick_log_gl(np, rows);

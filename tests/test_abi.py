@@ -89,17 +89,18 @@ def test_argument_validation_of_the_wider_entry_points(lib):
     assert d(one, 4, 8, 2, 1.0, -1, one, None) == -1                                # iterations < 0
     assert d(None, 4, 8, 2, 1.0, 10, one, None) == -2
     assert d(one, 0, 8, 2, 1.0, 10, one, None) == 0
-    # the operators on |x| need workspace beyond the rows that one fused kernel handles (3..128)
+    # the operators on |x| need workspace beyond the rows that one fused kernel handles (3..2048)
     for op in (b.TOPK_OP_SIGNED_MASK, b.TOPK_OP_MASKED_VALUE):
         assert b.workspace_bytes(op, 4, 8, 2, 2.0) == 0
+        assert b.workspace_bytes(op, 4, 2000, 2, 2.0) == 0
         assert b.workspace_bytes(op, 4, 2, 1, 2.0) >= 2 * 4 * 2 * 4
-        assert b.workspace_bytes(op, 4, 200, 2, 2.0) >= 2 * 4 * 200 * 4
+        assert b.workspace_bytes(op, 4, 3000, 2, 2.0) >= 2 * 4 * 3000 * 4
         assert b.workspace_bytes(op, 2, 5000, 2, 2.0) > b.workspace_bytes(b.TOPK_OP_MASK_JVP, 2, 5000, 2, 2.0)
     lib.topk_set_workspace(None, 0)
     assert g(one, one, 0, 4, 2000, 0, 2.0, 1.0, one, None) == -4                    # long rows: workspace
     assert b.workspace_bytes(b.TOPK_OP_GENERAL, 4, 2000, 0, 2.0) > 4 * 2001 * 8 * 4
     assert b.workspace_bytes(b.TOPK_OP_GENERAL, 4, 1000, 0, 2.0) == 0
-    assert lib.topk_signed_mask_fwd(one, 4, 200, 2, 2.0, 1.0, one, None) == -4
+    assert lib.topk_signed_mask_fwd(one, 4, 3000, 2, 2.0, 1.0, one, None) == -4
     assert lib.topk_masked_value_jvp(one, one, 4, 8, 2, 2.0, 1.0, None, one, None) == -2   # out required
     assert lib.topk_signed_mask_fwd(one, 4, 8, 9, 2.0, 1.0, one, None) == -1
 

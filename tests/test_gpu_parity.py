@@ -526,7 +526,7 @@ def test_dykstra_iterations(gpu, oracle, n):
 
 # ---- the operators on |x|: signed mask (phi = |x|) and x o mask(|x|) --------------------------------
 @pytest.mark.parametrize("rows,n", [(1, 1), (129, 7), (70, 33), (37, 64), (9, 100), (50, 128),
-                                    (5, 300), (3, 5000), (1, 200000)])
+                                    (5, 300), (40, 512), (7, 1000), (3, 2048), (3, 5000), (1, 200000)])
 def test_signed_mask_and_masked_value(gpu, oracle, rows, n):
     r = np.random.default_rng(31 * n + rows)
     x = r.normal(size=(rows, n)).astype(np.float32)
@@ -639,7 +639,7 @@ def test_fenchel_young_loss(gpu, oracle):
     the minimisation form of Prop. 2, the library uses the maximisation form)."""
     r = np.random.default_rng(23)
     for rows, n, k, lam in [(64, 10, 3, 0.5), (17, 5, 4, 2.0), (1000, 64, 2, 1.0), (70, 128, 40, 3.0),
-                            (300, 100, 3, 1.0), (33, 1000, 5, 0.2), (4, 5000, 50, 0.3),
+                            (300, 100, 3, 1.0), (33, 1000, 5, 0.2), (9, 2048, 300, 0.4), (4, 5000, 50, 0.3),
                             (2, 150000, 100, 0.5)]:
         x = (r.normal(size=(rows, n)) * 2).astype(np.float32)
         t = np.zeros((rows, n), dtype=np.float32)
