@@ -31,8 +31,9 @@
  *   - NaN or infinite inputs are a precondition violation (the output is then unspecified, but
  *     no out-of-bounds access happens).
  *   - Return value: TOPK_OK, or a negative TOPK_ERR_* code, in which case nothing was enqueued.
- *   - Rows with n > TOPK_SHORT_ROW_MAX are sorted through HBM and need caller-provided scratch
- *     memory: query topk_workspace_bytes(), hand the buffer over with topk_set_workspace().
+ *   - Long rows (above 2048 elements; above TOPK_SHORT_ROW_MAX for top-k in magnitude with
+ *     p = 4/3) go through HBM scratch memory that the caller provides: query
+ *     topk_workspace_bytes(), hand the buffer over with topk_set_workspace().
  *     The workspace is process-global: calls that use it must not overlap in time (different
  *     streams, or host threads) -- they would race on it.
  */
@@ -66,7 +67,8 @@ enum {
   TOPK_OP_ARGSORT = 4,
   TOPK_OP_SIGNED_MASK = 5,   /* topk_signed_mask_fwd and _jvp */
   TOPK_OP_MASKED_VALUE = 6,  /* topk_masked_value_fwd and _jvp */
-  TOPK_OP_GENERAL = 7        /* topk_general_fwd and _jvp */
+  TOPK_OP_GENERAL = 7,       /* topk_general_fwd and _jvp */
+  TOPK_OP_MASK_SPARSE = 8    /* topk_mask_sparse_fwd */
 };
 
 /* phi of topk_general_*: phi(x) = x (mask-like operators) or phi(x) = x^2 / 2 (in magnitude). */
@@ -75,7 +77,9 @@ enum {
   TOPK_PHI_HALF_SQUARE = 1
 };
 
-/* Rows up to this length are handled by one wavefront in registers (no workspace needed). */
+/* Rows up to this length are handled by one wavefront in registers by every entry point (no
+ * workspace needed); the dense operators take rows of up to 2048 elements that way, except
+ * top-k in magnitude with p = 4/3. */
 #define TOPK_SHORT_ROW_MAX 1024
 /* Longest row of topk_general_*: above TOPK_SHORT_ROW_MAX one workgroup solves a sorted row. */
 #define TOPK_GENERAL_ROW_MAX 131072
@@ -114,13 +118,13 @@ int topkmag_fwd(const float* x, int64_t rows, int64_t n, int64_t k, double p, do
 /*
  * topk_mask_jvp for callers that cannot allocate or register device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for
- * bit) and errors as topk_mask_jvp, but rows above TOPK_SHORT_ROW_MAX elements use a scratch
+ * bit) and errors as topk_mask_jvp, but rows that need scratch (above 2048 elements) use a scratch
  * array that is part of the library's device image instead of the registered workspace; the
  * call allocates nothing, frees nothing and ignores topk_set_workspace.
  *   - Limit: topk_workspace_bytes(TOPK_OP_MASK_JVP, rows, n, k, p) <= TOPK_STATIC_SCRATCH_BYTES
  *     (about rows * n <= 3.6 million elements); larger shapes return TOPK_ERR_STATIC_SCRATCH
- *     with nothing enqueued.  Rows up to TOPK_SHORT_ROW_MAX elements need no scratch and have no
- *     such limit.
+ *     with nothing enqueued.  Rows of up to 2048 elements need no scratch and have no such
+ *     limit.
  *   - Every GPU the library is used on holds its own copy of the array (TOPK_STATIC_SCRATCH_BYTES
  *     of device memory, for the life of the process); the first call on a device looks its
  *     address up (make that call outside a stream capture).
@@ -161,7 +165,7 @@ int topkmag_vjp(const float* x, const float* cotangent, int64_t rows, int64_t n,
  * non-zeros (k <= nnz <= n for k >= 1); if it exceeds max_nnz the list was cut off.
  *   theta [rows][n] in; idx_out (int32) and val_out (float) [rows][max_nnz], nnz_out (int32) [rows]
  *   out.  1 <= max_nnz <= n.  Rows above
- *   TOPK_SHORT_ROW_MAX need the workspace of TOPK_OP_MASK_FWD, and their lists are ordered
+ *   TOPK_SHORT_ROW_MAX need the workspace of TOPK_OP_MASK_SPARSE, and their lists are ordered
  *   differently: first the entries that lie above everything that can pool (value exactly 1), in
  *   ascending index order, then the remaining non-zeros in descending order of theta.
  *   Other arguments and errors as topk_mask_fwd.
@@ -244,7 +248,8 @@ int topk_masked_value_jvp(const float* x, const float* tangent, int64_t rows, in
  * y: f = <y, theta> - (lambda / p) sum_i y_i^p.
  *   theta, target [rows][n] in (target: usually a 0/1 encoding of the wanted classes),
  *   loss_out [rows] out, grad_out [rows][n] out (required: beyond 2048 elements per row it also
- *   carries the mask between the two kernels; shorter rows take one kernel).  Same shape rules, p values, workspace needs and errors as topk_mask_fwd.
+ *   carries the mask between the two kernels; shorter rows take one kernel).
+ *   Same shape rules, p values, workspace needs and errors as topk_mask_fwd.
  */
 int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_t n, int64_t k,
                    double p, double lambda, float* loss_out, float* grad_out, void* stream);
@@ -261,9 +266,11 @@ int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_
 int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm_out, void* stream);
 
 /*
- * Scratch memory (bytes) that `op` (a TOPK_OP_* code) needs for this shape; for the first five
- * codes 0 when rows fit one wavefront (n <= TOPK_SHORT_ROW_MAX).  Returns 0 for invalid
- * arguments as well.
+ * Scratch memory (bytes) that `op` (a TOPK_OP_* code) needs for this shape with the routes that
+ * are set when it is called (topk_set_route; ask again after changing them); for the first five
+ * codes 0 when rows fit one wavefront (n <= TOPK_SHORT_ROW_MAX; n <= 2048 for the dense
+ * operators other than top-k in magnitude with p = 4/3).  Returns 0 for invalid arguments as
+ * well.
  */
 size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p);
 

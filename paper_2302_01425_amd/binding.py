@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libsparse_topk.so")
 
 (TOPK_OP_MASK_FWD, TOPK_OP_MASK_JVP, TOPK_OP_MAG_FWD, TOPK_OP_MAG_JVP, TOPK_OP_ARGSORT,
- TOPK_OP_SIGNED_MASK, TOPK_OP_MASKED_VALUE, TOPK_OP_GENERAL) = range(8)
+ TOPK_OP_SIGNED_MASK, TOPK_OP_MASKED_VALUE, TOPK_OP_GENERAL, TOPK_OP_MASK_SPARSE) = range(9)
 
 EXPORTS = (
     "topk_mask_fwd", "topk_mask_jvp", "topk_mask_vjp", "topkmag_fwd", "topkmag_jvp", "topkmag_vjp",
@@ -293,7 +293,7 @@ def topk_mask_sparse_fwd(theta, k, p, lam, max_nnz, idx_out=None, val_out=None, 
         if not isinstance(t, torch.Tensor) or not t.is_cuda or t.device != theta.device or \
                 t.dtype != dt or tuple(t.shape) != sh or not t.is_contiguous():
             raise TopkError(f"{name} must be a contiguous {dt} tensor of shape {sh} on {theta.device}")
-    ensure_workspace(TOPK_OP_MASK_FWD, rows, n, k, p, theta.device)
+    ensure_workspace(TOPK_OP_MASK_SPARSE, rows, n, k, p, theta.device)
     _check(load().topk_mask_sparse_fwd(theta.data_ptr(), rows, n, int(k), float(p), float(lam),
                                        int(max_nnz), idx.data_ptr(), val.data_ptr(), nnz.data_ptr(),
                                        _stream(stream)), "topk_mask_sparse_fwd")

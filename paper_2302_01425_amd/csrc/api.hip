@@ -55,6 +55,15 @@ enum LongMode { kAuto = TOPK_LONG_ROWS_AUTO, kSelect = TOPK_LONG_ROWS_SELECT,
                 kOneLaunchIndexed = TOPK_LONG_ROWS_ONE_LAUNCH_INDEXED };
 LongMode long_mode() { return static_cast<LongMode>(topk::routes().long_rows); }
 
+// Rows of 1025..2048 elements still fit one wavefront's registers as values: the values-only
+// kernel takes them in one launch without scratch (it is not built for top-k in magnitude with
+// p = 4/3; a route forced through topk_set_route uses the long-row kernels and their scratch).
+bool value_wide(bool mag, int pc, int64_t n) {
+  return is_long(n) && n <= 2048 && long_mode() == kAuto &&
+         topk::routes().short_kernel == TOPK_SHORT_ROW_KERNEL_AUTO &&
+         (pc == topk::kP2 || (pc == topk::kP43 && !mag));
+}
+
 struct Layout {
   size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, hpart, bins, tile_hist2, bins2, tcnt, tabove, toff, taboff, sel, total;
 };
@@ -136,7 +145,8 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
   hipStream_t st = static_cast<hipStream_t>(stream);
   const Reg R = make_reg(lambda);
   SortBuffers B;
-  if (is_long(n)) {
+  const bool by_value = value_wide(mag, pc, n);
+  if (is_long(n) && !by_value) {
     rc = carve(rows, n, &B, ws_skip, ws);
     if (rc != TOPK_OK) return rc;
   }
@@ -148,15 +158,13 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
     return finish();
   }
   const LongMode mode = long_mode();
-  // rows of up to 2048 elements still fit one wavefront's registers as values
-  if (mode == kAuto && n <= 2048 && topk::routes().short_kernel == TOPK_SHORT_ROW_KERNEL_AUTO) {
+  if (by_value) {
     const bool vec = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(tangent) |
                                        reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(jvp)) & 15u) == 0;
     const int vrc = topk::launch_short_rows_value_wide(2048, vec, mag, pc, x, need_jvp ? tangent : nullptr,
                                                        out, need_jvp ? jvp : nullptr, rows, int(n),
                                                        int(k), R, st);
-    if (vrc == 0) return finish();
-    if (vrc != -2) return TOPK_ERR_INVALID;
+    return vrc == 0 ? finish() : TOPK_ERR_INVALID;
   }
   // k = 0 and k = n pool nothing and read no sorted value: no sort at all
   const bool trivial = (k == 0 || k == n);
@@ -465,10 +473,11 @@ int topk_mask_jvp_static(const float* theta, const float* tangent, int64_t rows,
   // shapes whose scratch does not fit the static array are refused before anything else happens
   const int rc = check_shape(rows, n, k, lambda);
   if (rc != TOPK_OK) return rc;
-  if (is_long(n) && layout_for(rows, n).total > size_t(TOPK_STATIC_SCRATCH_BYTES))
+  const bool scratch = is_long(n) && !value_wide(false, p_code(p), n);
+  if (scratch && layout_for(rows, n).total > size_t(TOPK_STATIC_SCRATCH_BYTES))
     return TOPK_ERR_STATIC_SCRATCH;
   Workspace ws;
-  if (is_long(n)) {
+  if (scratch) {
     const int src = static_scratch(&ws);
     if (src != TOPK_OK) return src;
   }
@@ -549,8 +558,7 @@ int topk_argsort_desc(const float* theta, int64_t rows, int64_t n, int32_t* perm
 
 size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p) {
   (void)k;
-  (void)p;
-  if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_GENERAL) return 0;
+  if (op < TOPK_OP_MASK_FWD || op > TOPK_OP_MASK_SPARSE) return 0;
   if (rows <= 0 || n < 1 || n >= (int64_t(1) << 30)) return 0;
   if (op == TOPK_OP_GENERAL) {
     if (!is_long(n) || n > TOPK_GENERAL_ROW_MAX) return 0;
@@ -561,6 +569,7 @@ size_t topk_workspace_bytes(int op, int64_t rows, int64_t n, int64_t k, double p
   if (abs_op && abs_fused(n)) return 0;
   const size_t own = abs_op ? abs_scratch_bytes(rows, n) : 0;
   if (!is_long(n)) return own;
+  if (op <= TOPK_OP_MAG_JVP && value_wide(op >= TOPK_OP_MAG_FWD, p_code(p), n)) return 0;
   return own + layout_for(rows, n).total;
 }
 

@@ -56,6 +56,16 @@ def test_argument_validation_without_gpu(lib):
     assert lib.topk_argsort_desc(one, 4, 8, None, None) == -2
     # long rows without a workspace
     assert b.workspace_bytes(b.TOPK_OP_MASK_FWD, 4, 8, 2, 2.0) == 0
+    # rows of up to 2048 elements run by value in one wavefront, except top-k in magnitude, p = 4/3
+    for op in (b.TOPK_OP_MASK_FWD, b.TOPK_OP_MASK_JVP, b.TOPK_OP_MAG_FWD, b.TOPK_OP_MAG_JVP):
+        assert b.workspace_bytes(op, 4, 2048, 2, 2.0) == 0
+        assert b.workspace_bytes(op, 4, 2049, 2, 2.0) >= 4 * 4 * 2049 * 4
+    assert b.workspace_bytes(b.TOPK_OP_MASK_JVP, 4, 2048, 2, 4.0 / 3.0) == 0
+    assert b.workspace_bytes(b.TOPK_OP_MAG_JVP, 4, 2048, 2, 4.0 / 3.0) >= 4 * 4 * 2048 * 4
+    assert b.workspace_bytes(b.TOPK_OP_MAG_JVP, 4, 1024, 2, 4.0 / 3.0) == 0
+    assert b.workspace_bytes(b.TOPK_OP_MASK_SPARSE, 4, 1024, 2, 2.0) == 0
+    assert b.workspace_bytes(b.TOPK_OP_MASK_SPARSE, 4, 1025, 2, 2.0) >= 4 * 4 * 1025 * 4
+    assert b.workspace_bytes(b.TOPK_OP_ARGSORT, 4, 1025, 0, 2.0) >= 4 * 4 * 1025 * 4
     need = b.workspace_bytes(b.TOPK_OP_MASK_JVP, 2, 5000, 2, 2.0)
     assert need >= 4 * 2 * 5000 * 4
     lib.topk_set_workspace(None, 0)
