@@ -65,7 +65,7 @@ bool value_wide(bool mag, int pc, int64_t n) {
 }
 
 struct Layout {
-  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, hpart, bins, tile_hist2, bins2, tcnt, tabove, toff, taboff, sel, total;
+  size_t keys_a, keys_b, idx_a, idx_b, hist, dtot, info, hpart, bins, bins2, tcnt, tabove, toff, taboff, sel, total;
 };
 
 Layout layout_for(int64_t rows, int64_t n) {
@@ -82,7 +82,6 @@ Layout layout_for(int64_t rows, int64_t n) {
   L.info = off; off += align_up(size_t(rows) * sizeof(RowInfo));
   L.hpart = off; off += align_up(size_t(rows) * topk::sel_parts(rows, n) * topk::kSelBins * 4);
   L.bins = off; off += align_up(size_t(rows) * topk::kSelSlices * topk::kSelBins * 4);
-  L.tile_hist2 = off; off += align_up(size_t(rows) * tiles * 2 * topk::kSel2Bins * 4);
   L.bins2 = off; off += align_up(size_t(rows) * topk::kSelSlices * 2 * topk::kSel2Bins * 4);
   L.tcnt = off; off += align_up(size_t(rows) * tiles * 4);
   L.tabove = off; off += align_up(size_t(rows) * tiles * 4);
@@ -107,7 +106,6 @@ int carve(int64_t rows, int64_t n, SortBuffers* B, size_t skip = 0, const Worksp
   B->info = reinterpret_cast<RowInfo*>(base + L.info);
   B->hpart = reinterpret_cast<uint32_t*>(base + L.hpart);
   B->bins = reinterpret_cast<uint32_t*>(base + L.bins);
-  B->tile_hist2 = reinterpret_cast<uint32_t*>(base + L.tile_hist2);
   B->bins2 = reinterpret_cast<uint32_t*>(base + L.bins2);
   B->tcnt = reinterpret_cast<uint32_t*>(base + L.tcnt);
   B->tabove = reinterpret_cast<uint32_t*>(base + L.tabove);

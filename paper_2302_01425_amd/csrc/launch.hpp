@@ -65,8 +65,8 @@ struct SortBuffers {
   RowInfo* info;      // [rows]
   uint32_t* hpart;    // [rows][parts][kSelBins] partial histograms of the leading key bits
   uint32_t* bins;     // [rows][slices][kSelBins] the same, summed down to <= kSelSlices slices
-  uint32_t* tile_hist2;  // [rows][tiles][2][kSel2Bins] per tile: the next key bits inside the bins of k, k+1
-  uint32_t* bins2;    // [rows][slices][2][kSel2Bins] the same, summed down to <= kSelSlices slices
+  uint32_t* bins2;    // [rows][kSelSlices][2][kSel2Bins] the next key bits inside the bins of k, k+1:
+                      // partial histograms, tile t of a row adds to slice t % kSelSlices
   uint32_t* tcnt;     // [rows][tiles] candidates per tile
   uint32_t* tabove;   // [rows][tiles] elements above the candidate window per tile
   uint32_t* toff;     // [rows][tiles] start of the tile's candidates in the row's dense list

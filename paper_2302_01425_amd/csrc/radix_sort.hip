@@ -27,8 +27,9 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kItems = 16;
 constexpr int kTile = kThreads * kItems;          // 4096 elements per workgroup and pass
 
-// exclusive scan of one value per thread over the 256 threads of the block; also returns total
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_tot /*[kWaves]*/,
+// exclusive scan of one value per thread over the NW wavefronts of the block; also returns total
+template <int NW = kWaves>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_tot /*[NW]*/,
                                                          uint32_t* total) {
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   uint32_t inc = v;
@@ -42,7 +43,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
   __syncthreads();
   uint32_t before = 0, all = 0;
 #pragma unroll
-  for (int q = 0; q < kWaves; ++q) {
+  for (int q = 0; q < NW; ++q) {
     const uint32_t t = wave_tot[q];
     if (q < w) before += t;
     all += t;
@@ -348,43 +349,41 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const uint32_
 // below and s_{k+1} from above; the key window [klo, khi] holds both bins and every element that
 // passes the necessary conditions for joining the block (pooling.hpp: left_candidate,
 // right_candidate) for ANY s_k, s_{k+1} inside those bins.  Requires 1 <= k < n.
+// bins2 (may be null): the row's partial histograms of the second level, cleared here because the
+// compaction pass adds to them.
+constexpr int kWinThreads = 1024;              // four bins per thread: every slice's load in flight
 template <bool MAG>
-__global__ __launch_bounds__(kThreads) void select_window_kernel(const uint32_t* __restrict__ bins,
-                                                                 RowSel* __restrict__ sel,
-                                                                 int64_t k, int gcopies, Reg R,
-                                                                 bool cubic) {
-  constexpr int kPerThread = kSelBins / kThreads;
-  __shared__ uint32_t wave_tot[kWaves];
+__global__ __launch_bounds__(kWinThreads) void select_window_kernel(const uint32_t* __restrict__ bins,
+                                                                    RowSel* __restrict__ sel,
+                                                                    int64_t k, int gcopies, Reg R,
+                                                                    bool cubic,
+                                                                    uint32_t* __restrict__ bins2) {
+  constexpr int kPerThread = kSelBins / kWinThreads;
+  static_assert(kPerThread == 4, "a thread reads its bins of one slice as one uint4");
+  __shared__ uint32_t wave_tot[kWinThreads / kWave];
   __shared__ uint32_t found[2];
   const int64_t row = blockIdx.x;
+  if (bins2 != nullptr)
+    for (int i = threadIdx.x; i < kSelSlices * 2 * kSel2Bins; i += kWinThreads)
+      bins2[row * (kSelSlices * 2 * kSel2Bins) + i] = 0u;
   const uint32_t* b = bins + row * gcopies * kSelBins;
-  uint32_t c[kPerThread], mine = 0;
-  static_assert(kPerThread % 4 == 0, "bins are read as uint4");
+  uint32_t c[kPerThread] = {0u, 0u, 0u, 0u}, mine = 0;
+  for (int g0 = 0; g0 < gcopies; g0 += kSelSlices) {
+    uint4 v[kSelSlices];
 #pragma unroll
-  for (int i = 0; i < kPerThread; ++i) c[i] = 0;
-  for (int g0 = 0; g0 < gcopies; g0 += 4) {            // four slices' loads in flight
-    uint4 v[4][kPerThread / 4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const uint4* src = reinterpret_cast<const uint4*>(
-          b + (g0 + q < gcopies ? g0 + q : g0) * kSelBins + threadIdx.x * kPerThread);
-#pragma unroll
-      for (int i = 0; i < kPerThread / 4; ++i) v[q][i] = src[i];
+    for (int q = 0; q < kSelSlices; ++q) {
+      v[q] = make_uint4(0u, 0u, 0u, 0u);
+      if (g0 + q < gcopies)
+        v[q] = reinterpret_cast<const uint4*>(b + int64_t(g0 + q) * kSelBins)[threadIdx.x];
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (g0 + q < gcopies) {
-#pragma unroll
-        for (int i = 0; i < kPerThread / 4; ++i) {
-          c[4 * i] += v[q][i].x; c[4 * i + 1] += v[q][i].y;
-          c[4 * i + 2] += v[q][i].z; c[4 * i + 3] += v[q][i].w;
-        }
-      }
+    for (int q = 0; q < kSelSlices; ++q) {
+      c[0] += v[q].x; c[1] += v[q].y; c[2] += v[q].z; c[3] += v[q].w;
     }
   }
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) mine += c[i];
-  uint32_t run = block_exclusive_scan(mine, wave_tot, nullptr);
+  uint32_t run = block_exclusive_scan<kWinThreads / kWave>(mine, wave_tot, nullptr);
   // position q (1-based) lies in the first bin whose inclusive count reaches q
   const uint32_t q0 = uint32_t(k), q1 = uint32_t(k + 1);
 #pragma unroll
@@ -465,7 +464,8 @@ __global__ __launch_bounds__(kThreads) void select_refine_kernel(const uint32_t*
 // output arrays (row stride n, tile stride kTile), with their count and the number of elements of
 // the tile above the window.  The candidates are staged in LDS in order, so that the slot is
 // written with full wavefronts; candidates inside the histogram bins of positions k and k+1 are
-// also counted by their next kSel2Bits key bits (second selection level, one histogram per tile).
+// also counted by their next kSel2Bits key bits (second selection level: added to the row's
+// partial histograms bins2[row][tile % kSelSlices], which the window kernel has cleared).
 // TAU: the payload of a candidate is not its index but the bits of its tangent in sorted-value
 // coordinates (t, or sign(x) t for the magnitude operator; 0 without a tangent): what the wide
 // route needs, whose outputs are computed from values.
@@ -473,7 +473,7 @@ template <bool MAG, bool HIST2 = true, bool TAU = false>
 __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     const float* __restrict__ x, const RowSel* __restrict__ sel, uint32_t* __restrict__ keys_out,
     uint32_t* __restrict__ idx_out, uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove,
-    uint32_t* __restrict__ tile_hist2, int64_t n, int tiles,
+    uint32_t* __restrict__ bins2, int64_t n, int tiles,
     const float* __restrict__ tangent = nullptr) {
   __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
   __shared__ uint32_t kbuf[kTile];
@@ -561,9 +561,11 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
     tabove[row * tiles + tile] = above;
   }
   if (HIST2) {
+    // the tile's few non-empty counters are added to one of the row's kSelSlices partial histograms
     __syncthreads();
-    uint32_t* dst = tile_hist2 + (row * tiles + tile) * (2 * kSel2Bins);
-    for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads) dst[i] = h2[i];
+    uint32_t* dst = bins2 + (row * kSelSlices + tile % kSelSlices) * (2 * kSel2Bins);
+    for (int i = threadIdx.x; i < 2 * kSel2Bins; i += kThreads)
+      if (h2[i] != 0u) atomicAdd(&dst[i], h2[i]);
   }
 }
 
@@ -764,18 +766,14 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
                      st, x, B.hpart, n, span, parts);
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(unsigned(rows * slices * (kSelBins / 128))),
                      dim3(kThreads), 0, st, B.hpart, B.bins, parts, slices, kSelBins);
-  hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                     B.bins, B.sel, k, slices, R, cubic);
+  hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kWinThreads), 0, st,
+                     B.bins, B.sel, k, slices, R, cubic, B.bins2);
   // first-level candidates into the per-tile slots of the "b" arrays; second level; slots
   // narrowed in place; dense lists
-  const int slices2 = tiles < kSelSlices ? tiles : kSelSlices;
   hipLaunchKernelGGL((select_compact_kernel<MAG>), dim3(blocks), dim3(kThreads), 0, st, x, B.sel,
-                     B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles);
-  hipLaunchKernelGGL(reduce_partials_kernel,
-                     dim3(unsigned(rows * slices2 * (2 * kSel2Bins / 128))), dim3(kThreads), 0, st,
-                     B.tile_hist2, B.bins2, tiles, slices2, 2 * kSel2Bins);
+                     B.keys_b, B.idx_b, B.tcnt, B.tabove, B.bins2, n, tiles);
   hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                     B.bins2, B.sel, slices2, R, cubic);
+                     B.bins2, B.sel, kSelSlices, R, cubic);
   hipLaunchKernelGGL((select_recompact_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, st,
                      B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles, nullptr);
   hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
@@ -786,8 +784,9 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
 
 // The candidate selection of the wide route: the same levels, but the candidates stay in the
 // per-tile slots of the "b" arrays (B.tcnt / B.tabove per tile); the workgroup that sorts and
-// solves a row collects them itself.  Sums of partial histograms are only launched when there are
-// more partials than the consumers add up themselves; `refine`: second histogram level.
+// solves a row collects them itself.  The sum of the first level's partial histograms is only
+// launched when there are more partials than the window kernel adds up itself; `refine`: second
+// histogram level (its partial histograms are added up by the compaction pass).
 template <bool MAG>
 void wide_select(const float* x, const float* tangent, int64_t rows, int64_t n, int64_t k,
                  const Reg& R, bool cubic, bool refine, const SortBuffers& B, hipStream_t st) {
@@ -800,30 +799,22 @@ void wide_select(const float* x, const float* tangent, int64_t rows, int64_t n, 
   if (parts > kSelSlices) {
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(unsigned(rows * kSelSlices * (kSelBins / 128))),
                        dim3(kThreads), 0, st, B.hpart, B.bins, parts, kSelSlices, kSelBins);
-    hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                       B.bins, B.sel, k, kSelSlices, R, cubic);
+    hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kWinThreads), 0, st,
+                       B.bins, B.sel, k, kSelSlices, R, cubic, refine ? B.bins2 : nullptr);
   } else {
-    hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                       B.hpart, B.sel, k, parts, R, cubic);
+    hipLaunchKernelGGL((select_window_kernel<MAG>), dim3(unsigned(rows)), dim3(kWinThreads), 0, st,
+                       B.hpart, B.sel, k, parts, R, cubic, refine ? B.bins2 : nullptr);
   }
   if (!refine) {
     hipLaunchKernelGGL((select_compact_kernel<MAG, false, true>), dim3(blocks), dim3(kThreads), 0,
-                       st, x, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles,
+                       st, x, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.bins2, n, tiles,
                        tangent);
     return;
   }
   hipLaunchKernelGGL((select_compact_kernel<MAG, true, false>), dim3(blocks), dim3(kThreads), 0, st,
-                     x, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.tile_hist2, n, tiles, nullptr);
-  if (tiles > kSelSlices) {
-    hipLaunchKernelGGL(reduce_partials_kernel,
-                       dim3(unsigned(rows * kSelSlices * (2 * kSel2Bins / 128))), dim3(kThreads), 0,
-                       st, B.tile_hist2, B.bins2, tiles, kSelSlices, 2 * kSel2Bins);
-    hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                       B.bins2, B.sel, kSelSlices, R, cubic);
-  } else {
-    hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
-                       B.tile_hist2, B.sel, tiles, R, cubic);
-  }
+                     x, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.bins2, n, tiles, nullptr);
+  hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
+                     B.bins2, B.sel, kSelSlices, R, cubic);
   hipLaunchKernelGGL((select_recompact_kernel<true, MAG>), dim3(blocks), dim3(kThreads), 0, st,
                      B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles, tangent);
 }
