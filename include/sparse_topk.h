@@ -245,7 +245,9 @@ int topk_masked_value_jvp(const float* x, const float* tangent, int64_t rows, in
  *     loss = f_{phi,R}(theta, 1_k) - <theta, target>,   phi(x) = x,
  * and its gradient in theta, grad = y - target with y the mask of topk_mask_fwd (Prop. 2:
  * y = grad_1 f_{phi,R}).  f is evaluated through the maximisation form of Prop. 2 at its maximiser
- * y: f = <y, theta> - (lambda / p) sum_i y_i^p.
+ * y: f = <y, theta> - (lambda / p) sum_i y_i^p, summed in float64 together with the multiplier
+ * term - gamma (sum_i y_i - k), which is zero at the maximiser and keeps the rounding of the
+ * float32 mask out of the value in first order.
  *   theta, target [rows][n] in (target: usually a 0/1 encoding of the wanted classes),
  *   loss_out [rows] out, grad_out [rows][n] out (required: beyond 2048 elements per row it also
  *   carries the mask between the two kernels; shorter rows take one kernel).

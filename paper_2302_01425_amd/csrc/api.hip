@@ -515,7 +515,7 @@ int topk_mask_loss(const float* theta, const float* target, int64_t rows, int64_
                               false, stream);
   if (rc != TOPK_OK || rows == 0) return rc;
   const double p_exact = p_code(p) == topk::kP2 ? 2.0 : 4.0 / 3.0;
-  if (topk::launch_mask_loss(p_code(p), theta, target, grad_out, loss_out, rows, n, lambda,
+  if (topk::launch_mask_loss(p_code(p), theta, target, grad_out, loss_out, rows, n, k, lambda,
                              p_exact, static_cast<hipStream_t>(stream)) != 0)
     return TOPK_ERR_INVALID;
   return finish();

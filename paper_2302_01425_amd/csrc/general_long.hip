@@ -316,6 +316,65 @@ __global__ __launch_bounds__(kGT) void general_long_kernel(
   int nxt, prv;
   block_neighbours(jf >= 0 ? p0 + jf : n, jl >= 0 ? p0 + jl : -1, n, sm, &nxt, &prv);
 
+  // ---- 2b. p = 4/3: the roots once more, from sums of the blocks' own spread.  The expanded cubic
+  // of a block carries the rounding of its values cubed, while a block whose values lie within a
+  // small lambda of each other needs that of the spread cubed.  With the partition final, every
+  // position is taken relative to the first value c of its own block: plain float64 prefix sums
+  // of d = s - c, d^2, d^3 are as small as the blocks are narrow, and the safeguarded Newton solve
+  // of the rounds, on sum (g - d_i)^3 + lambda^3 W [c + g] = 0 with the same bracket, gives
+  // gamma = c + g to the rounding of the spread ----------------------------------------------------
+  if (CUBIC && !gave_up) {
+    double t1 = 0.0, t2 = 0.0, t3 = 0.0;
+    {
+      double c = double(ss[prv >= 0 ? prv : 0]);
+      for (int j = 0; j < own; ++j) {
+        if (mask_test(hm, j)) c = double(ss[p0 + j]);
+        const double d = double(ss[p0 + j]) - c;
+        t1 += d;
+        t2 += d * d;
+        t3 += d * d * d;
+      }
+    }
+    double r1 = block_exclusive_scan(t1, sm.q[0]), r2 = block_exclusive_scan(t2, sm.q[1]);
+    double r3 = block_exclusive_scan(t3, sm.q[0]);
+    __syncthreads();                           // (the prefix sums of the rounds have been read)
+    {
+      double c = double(ss[prv >= 0 ? prv : 0]);
+      for (int j = 0; j < own; ++j) {
+        if (mask_test(hm, j)) c = double(ss[p0 + j]);
+        const double d = double(ss[p0 + j]) - c;
+        Q1[p0 + j] = r1;
+        Q2[p0 + j] = r2;
+        Q3[p0 + j] = r3;
+        r1 += d;
+        r2 += d * d;
+        r3 += d * d * d;
+      }
+      if (own > 0 && p0 + own == n) {
+        Q1[n] = r1;
+        Q2[n] = r2;
+        Q3[n] = r3;
+      }
+    }
+    __syncthreads();
+    for (int j = jf; j >= 0;) {
+      const int jn = mask_next(hm, j);
+      const int lo = p0 + j, hi = jn >= 0 ? p0 + jn : nxt;
+      j = jn;
+      if (hi - lo == 1) continue;              // (singletons have closed forms)
+      const double cnt = double(hi - lo), c = double(ss[lo]);
+      const double S1 = Q1[hi] - Q1[lo], S2 = Q2[hi] - Q2[lo], S3 = Q3[hi] - Q3[lo];
+      const double W = dd_diff(PW[hi], PW[lo]);
+      // the bracket of the first solve, relative to c: [smin - lambda cbrt(W), smax] (mask), [0, smax]
+      const double dmin = double(ss[hi - 1]) - c;
+      const double g = MAG ? block_root<true>(cnt, W, S1, S2, S3, R, -c, 0.0, c)
+                           : block_root<false>(cnt, W, S1, S2, S3, R,
+                                               dmin - R.lambda * cbrt(W) - 1e-300, 0.0);
+      G[lo] = c + g;
+    }
+    __syncthreads();
+  }
+
   // ---- 3. Prop. 7: d gamma of every block from prefix sums of c_j tau_j and c_j ------------------------
   if (!gave_up && jvp != nullptr) {
     double tq = 0.0, tc = 0.0;

@@ -10,28 +10,30 @@
 
 namespace topk {
 
-// the increasing cubic of a block: sum_B (g - s_i)^3 + lambda^3 W [g] (magnitude: times g)
+// the increasing cubic of a block: sum_B (g - s_i)^3 + lambda^3 W [g] (magnitude: times g).
+// shift: the sums are those of s_i - shift and g stands for gamma - shift (matters for the
+// magnitude form only, whose last term is lambda^3 W gamma).
 template <bool MAG>
 __device__ __forceinline__ double block_cubic(double g, double cnt, double W, double S1, double S2,
-                                              double S3, const Reg& R) {
-  const double lin = MAG ? R.lam3 * W * g : R.lam3 * W;
+                                              double S3, const Reg& R, double shift = 0.0) {
+  const double lin = MAG ? R.lam3 * W * (g + shift) : R.lam3 * W;
   return ((cnt * g - 3.0 * S1) * g + 3.0 * S2) * g - S3 + lin;
 }
 
 // root of the block's cubic inside [lo, hi] (safeguarded Newton; the cubic is increasing)
 template <bool MAG>
 __device__ double block_root(double cnt, double W, double S1, double S2, double S3, const Reg& R,
-                             double lo, double hi) {
+                             double lo, double hi, double shift = 0.0) {
   double a = lo, b = hi;
   // start: the root the cubic would have with every s_i at the block's mean
   const double mean = S1 / cnt;
-  double x = mean - R.lambda * cbrt(MAG ? W * fmax(mean, 0.0) / cnt : W / cnt);
+  double x = mean - R.lambda * cbrt(MAG ? W * fmax(mean + shift, 0.0) / cnt : W / cnt);
   if (!(x > a && x < b)) x = 0.5 * (a + b);
   const double scale = fmax(fmax(fabs(a), fabs(b)), R.lambda);
   const double tol = 1e-15 * scale;
   double last = 1e300;
   for (int it = 0; it < 200; ++it) {
-    const double F = block_cubic<MAG>(x, cnt, W, S1, S2, S3, R);
+    const double F = block_cubic<MAG>(x, cnt, W, S1, S2, S3, R, shift);
     if (F == 0.0) return x;
     if (F > 0.0) b = x; else a = x;
     const double D = (3.0 * cnt * x - 6.0 * S1) * x + 3.0 * S2 + (MAG ? R.lam3 * W : 0.0);

@@ -252,9 +252,67 @@ __global__ __launch_bounds__((GenCfg<GL, E, PC == kP43>::WPB * kWave)) void gene
   float yv[E];
   double tt[E];                              // (s - gamma) / lambda
   if (!gave_up) {
-    // ---- y; then Prop. 7: d gamma of every block from prefix sums of c_j tau_j and c_j --------------
     const int last = hm ? e0 + 31 - __builtin_clz(hm) : -1;
     const int prv = lanes_before_max<GL>(last, lr, -1);
+    if (CUBIC) {
+      // ---- the roots once more, from sums of the blocks' own spread.  A block's sums so far are
+      // differences of prefix sums over the whole row: their rounding is that of the row's values
+      // cubed, while the cubic of a block whose values lie within a small lambda of each other
+      // needs that of the spread cubed.  With the partition final, every position is taken
+      // relative to the first value c of its own block: the prefix sums of d = s - c, d^2, d^3
+      // stay as small as the blocks are narrow (a block's sums involve its own positions only),
+      // and the safeguarded Newton solve of the rounds, on sum (g - d_i)^3 + lambda^3 W [c + g] = 0
+      // with the same bracket, gives gamma = c + g to the rounding of the spread -----------------
+      double dd[E];
+      double t1 = 0.0, t2 = 0.0, t3 = 0.0;
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        const uint32_t upto = hm & ((2u << r) - 1u);
+        int b = upto ? e0 + 31 - __builtin_clz(upto) : prv;
+        if (b < 0) b = 0;
+        dd[r] = (e0 + r < n) ? double(s32[r]) - double(ss[b]) : 0.0;
+        t1 += dd[r];
+        t2 += dd[r] * dd[r];
+        t3 += dd[r] * dd[r] * dd[r];
+      }
+      double r1 = group_exclusive_scan_f64<GL>(t1, lr), r2 = group_exclusive_scan_f64<GL>(t2, lr);
+      double r3 = group_exclusive_scan_f64<GL>(t3, lr);
+      __builtin_amdgcn_wave_barrier();           // the prefix sums of the rounds have been read
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        P1[e0 + r] = r1;
+        P2[e0 + r] = r2;
+        P3[e0 + r] = r3;
+        r1 += dd[r];
+        r2 += dd[r] * dd[r];
+        r3 += dd[r] * dd[r] * dd[r];
+      }
+      if (lr == GL - 1) {
+        P1[NP] = r1;
+        P2[NP] = r2;
+        P3[NP] = r3;
+      }
+      __builtin_amdgcn_wave_barrier();
+      const int first = hm ? e0 + __builtin_ctz(hm) : n;
+      const int nxt = lanes_after_min<GL>(first, lr, n);
+      for (uint32_t m = hm; m != 0;) {
+        const int r = __builtin_ctz(m);
+        m &= m - 1;
+        const int lo = e0 + r, hi = m ? e0 + __builtin_ctz(m) : nxt;
+        if (hi - lo == 1) continue;              // (singletons have closed forms)
+        const double cnt = double(hi - lo), c = double(ss[lo]);
+        const double S1 = P1[hi] - P1[lo], S2 = P2[hi] - P2[lo], S3 = P3[hi] - P3[lo];
+        const double W = PW[hi] - PW[lo];
+        // the bracket of the first solve, relative to c: [smin - lambda cbrt(W), smax] (mask), [0, smax]
+        const double dmin = double(ss[hi - 1]) - c;
+        const double g = MAG ? block_root<true>(cnt, W, S1, S2, S3, R, -c, 0.0, c)
+                             : block_root<false>(cnt, W, S1, S2, S3, R,
+                                                 dmin - R.lambda * cbrt(W) - 1e-300, 0.0);
+        G[lo] = c + g;
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    // ---- y; then Prop. 7: d gamma of every block from prefix sums of c_j tau_j and c_j --------------
     double cq[E], cc[E];
     double tq = 0.0, tc = 0.0;
 #pragma unroll

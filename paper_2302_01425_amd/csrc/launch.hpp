@@ -187,7 +187,7 @@ int launch_long_list_sort(bool mag, int64_t rows, int64_t n, const SortBuffers& 
 
 // Fenchel-Young top-k loss from the mask: grad holds y on entry, y - target on exit; loss[rows].
 int launch_mask_loss(int pc, const float* x, const float* target, float* grad, float* loss,
-                     int64_t rows, int64_t n, double lambda, double p, hipStream_t st);
+                     int64_t rows, int64_t n, int64_t k, double lambda, double p, hipStream_t st);
 
 // Compact output of the relaxed top-k mask of short rows (n <= 1024): per row the non-zeros in
 // descending order of theta, idx / val [rows][max_nnz] (unused slots -1 / 0), nnz [rows] = their

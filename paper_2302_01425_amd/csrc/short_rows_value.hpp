@@ -449,27 +449,38 @@ __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
       if (MAG) dy = (dy == 0.0f || v[r] == 0.0f) ? 0.0f : (neg ? -dy : dy);
       jv[r] = dy;
     }
-    // ---- what the variants make of the mask (float32, element-wise) --------------------------------
+    // ---- what the variants make of the mask (element-wise; float64 for the values: with a small
+    // lambda the factors reach the hundreds, and two or three float32 roundings would show
+    // against a bar of one float32 ulp) --------------------------------------------------------
     if (VAR == kVarSigned) {
       const float xv = xin[r];
       const float sg = float((xv > 0.0f) - (xv < 0.0f));
-      const float u = v[r] * inv_lambda32;
-      const float cap = CUBIC ? u * u * u : u;
-      const bool clipped = yv[r] > cap;
+      const double u = double(v[r]) * R.inv_lambda;
+      const float cap = float(CUBIC ? u * u * u : u);
+      // the truncation v >= 0 is active where the mask exceeds the cap: inside the block
+      // ((s - gamma) / lambda against s / lambda) exactly when gamma < 0, above it (the literal 1)
+      // when s < lambda, below it never -- decided on gamma and s themselves, so that a pooled
+      // value of exactly zero is the tie it is and not the last bit of two float32 roundings
+      const bool clipped = inb[r] ? (double(c32) + gamma < 0.0)
+                                  : (abv[r] && double(v[r]) < R.lambda);
       if (want_jvp) {
-        const float hess = CUBIC ? 3.0f * u * u * inv_lambda32 : inv_lambda32;
-        float jm = clipped ? hess * tin[r] : sg * jv[r];
+        const double hess = CUBIC ? 3.0 * u * u * R.inv_lambda : R.inv_lambda;
+        float jm = clipped ? float(hess * double(tin[r])) : sg * jv[r];
         jv[r] = (jm == 0.0f) ? 0.0f : jm;
       }
       const float y = sg * (clipped ? cap : yv[r]);
       yv[r] = (y == 0.0f) ? 0.0f : y;
     } else if (VAR == kVarMasked) {
-      if (want_jvp) jv[r] = tin[r] * yv[r] + xin[r] * jv[r];
+      if (want_jvp) jv[r] = float(double(tin[r]) * double(yv[r]) + double(xin[r]) * double(jv[r]));
       yv[r] = xin[r] * yv[r];
     }
   }
   if (LOSS) {
-    double acc = 0.0;
+    // f(x) = max_y <y, x> - (lambda / p) sum y^p over the capped simplex, evaluated at the float32
+    // mask through its Lagrangian, <y, x> - (lambda / p) sum y^p - gamma (sum y - k): the same
+    // value at the maximiser, and flat there -- x_i - lambda y_i^(p-1) = gamma on the block -- so
+    // that the rounding of the y_i does not enter in first order
+    double acc = 0.0, ysum = 0.0;
 #pragma unroll
     for (int r = 0; r < E; ++r) {
       const bool real = FULL || elem_of<GL, E, VEC>(lr, r) < nn;
@@ -479,10 +490,16 @@ __global__ __launch_bounds__(WPB * kWave) void short_rows_value_kernel(
         const double c = cbrt(yd);                   // y^(4/3), y in [0, 1]
         yp = c * c * c * c;
       }
-      if (real) acc += yd * double(xin[r]) - lam_over_p * yp - double(xin[r]) * double(tin[r]);
+      if (real) {
+        acc += yd * double(xin[r]) - lam_over_p * yp - double(xin[r]) * double(tin[r]);
+        ysum += yd;
+      }
       yv[r] = yv[r] - tin[r];                        // the gradient y - t
     }
     acc = group_sum_f64<GL>(acc);
+    ysum = group_sum_f64<GL>(ysum);
+    // (without a block every y is a literal 0 or 1 and sum y = k exactly)
+    if (have) acc -= (double(c32) + gamma) * (ysum - double(k));
     if (valid && lr == 0) loss[row] = float(acc);
   }
   if (!valid) return;

@@ -48,23 +48,25 @@ __global__ __launch_bounds__(kVT) void abs_prepare_kernel(const float* __restric
 }
 
 // in place: out holds m, jvp holds J_m (sign o t) on entry (jvp, t may be null)
+// (float64 for the values: with a small lambda the factors reach the hundreds, and two or three
+// float32 roundings would show against a bar of one float32 ulp)
 template <bool SIGNED, int PC>
 __device__ __forceinline__ void finish_element(float xv, float tv, float& m, float& jm, bool want_jvp,
-                                               float inv_lambda) {
+                                               double inv_lambda) {
   const float sg = sign_of(xv);
   if (SIGNED) {
-    const float u = fabsf(xv) * inv_lambda;
-    const float cap = PC == kP43 ? u * u * u : u;
+    const double u = double(fabsf(xv)) * inv_lambda;
+    const float cap = float(PC == kP43 ? u * u * u : u);
     const bool clipped = m > cap;
     if (want_jvp) {
-      const float hess = PC == kP43 ? 3.0f * u * u * inv_lambda : inv_lambda;
-      jm = clipped ? hess * tv : sg * jm;
+      const double hess = PC == kP43 ? 3.0 * u * u * inv_lambda : inv_lambda;
+      jm = clipped ? float(hess * double(tv)) : sg * jm;
       jm = (jm == 0.0f) ? 0.0f : jm;
     }
     const float y = sg * (clipped ? cap : m);
     m = (y == 0.0f) ? 0.0f : y;
   } else {
-    if (want_jvp) jm = tv * m + xv * jm;
+    if (want_jvp) jm = float(double(tv) * double(m) + double(xv) * double(jm));
     m = xv * m;
   }
 }
@@ -73,7 +75,7 @@ template <bool SIGNED, int PC>
 __global__ __launch_bounds__(kVT) void abs_finish_kernel(const float* __restrict__ x,
                                                          const float* __restrict__ t, float* out,
                                                          float* jvp, int64_t count,
-                                                         float inv_lambda, bool vec) {
+                                                         double inv_lambda, bool vec) {
   const bool want_jvp = jvp != nullptr;
   const int64_t stride = int64_t(gridDim.x) * kVT * kVItems;
   for (int64_t e0 = (int64_t(blockIdx.x) * kVT + threadIdx.x) * kVItems; e0 < count; e0 += stride) {
@@ -130,7 +132,7 @@ int launch_abs_finish(bool signed_mask, int pc, const float* x, const float* t, 
                       float* jvp, int64_t count, const Reg& R, hipStream_t stream) {
   if (count <= 0) return 0;
   const dim3 grid(grid_for(count)), block(kVT);
-  const float il = float(R.inv_lambda);
+  const double il = R.inv_lambda;
   if (jvp == nullptr) t = nullptr;
   const bool vec = aligned16({x, t, out, jvp});
 #define TOPK_VARIANT_CALL(S, P) \

@@ -244,6 +244,27 @@ def test_rows_above_the_fused_kernel_limit(gpu, oracle):
     run_case(gpu, oracle, "mask", z[:1], t[:1], 100, P43, 0.2, check_perm=False)
 
 
+@pytest.mark.parametrize("rows,n", [(1, 8193), (3, 12345), (2, 32768), (16, 32768), (40, 20000),
+                                    (128, 8200), (129, 8200)])
+def test_rows_of_8193_to_32768_elements(gpu, oracle, rows, n):
+    """The kernel that keeps a row in the registers of one workgroup of 1024 threads: few and many
+    rows, ragged last wavefronts, ties, windows that hold more candidates than LDS takes."""
+    r = np.random.default_rng(13 * n + rows)
+    x = r.normal(size=(rows, n)).astype(np.float32)
+    x[-1, :] = np.round(x[-1, :] * 4) / 4                 # heavy ties in the last row
+    x[0, n - 3:] = 9.0                                    # the largest values at the end of the row
+    t = r.normal(size=(rows, n)).astype(np.float32)
+    for p, k, lam in [(P2, 1, 0.1), (P2, n // 32, 0.1), (P43, n // 10, 0.05), (P2, n - 1, 0.5)]:
+        run_case(gpu, oracle, "mask", x, t, k, p, lam, check_perm=False)
+    run_case(gpu, oracle, "mag", x * np.float32(0.02), t, n // 10, P2, 1e-2, check_perm=False)
+    run_case(gpu, oracle, "mag", x[:2], t[:2], n // 7, P43, 0.05, check_perm=False)
+    # a window that holds the whole row (more candidates than one workgroup sorts in LDS)
+    run_case(gpu, oracle, "mask", x[:3], t[:3], n // 3, P2, 50.0, check_perm=False)
+    c = np.full((2, n), 0.75, dtype=np.float32)           # constant rows
+    run_case(gpu, oracle, "mask", c, t[:2] if rows >= 2 else np.vstack([t, t]), n // 2, P2, 0.3,
+             check_perm=False)
+
+
 # ---- the row lengths at which the kernel family changes ---------------------------------------------
 @pytest.mark.parametrize("n", [128, 129, 1024, 1025, 8192, 8193, 131072, 131073])
 def test_kernel_family_boundaries(gpu, oracle, n):
@@ -649,14 +670,40 @@ def test_fenchel_young_loss(gpu, oracle):
             ref_loss, ref_grad = oracle.fenchel_young_loss(x, t, k, p, lam)
             loss, grad = gpu.topk_mask_loss(dev(x), dev(t), k, p, lam)
             close(host(grad), ref_grad, "grad")
-            # f = <y, x> - (lambda / p) sum y^p is evaluated from the float32 mask y, and the loss
-            # is stored as float32: one float32 rounding (6e-8 relative) of every term that enters,
-            # i.e. 1.2e-7 (|y| . |x| + (lambda / p) sum y^p + |<x, t>|), on top of 1e-5 absolute
-            y = ref_grad + t
-            scale = (np.abs(y * x).sum(axis=1) + lam / p * (np.abs(y) ** p).sum(axis=1)
-                     + np.abs((x * t).sum(axis=1)))
+            # the loss is summed in float64 from the float32 mask through the Lagrangian of the
+            # maximisation form, which is flat at the maximiser: what is left is the float32
+            # rounding of the stored value (6e-8 relative; twice that allowed) and 2e-6 absolute
             err = np.abs(host(loss).astype(np.float64) - ref_loss)
-            assert (err <= 1e-5 + 1.2e-7 * scale).all(), (rows, n, p, float(err.max()))
+            assert (err <= 2e-6 + 1.2e-7 * np.abs(ref_loss)).all(), (rows, n, p, float(err.max()))
+
+
+def test_small_lambda_against_the_spread_of_the_row(gpu, oracle):
+    """lambda a few hundred times smaller than the values: a pooled block's own spread is then far
+    below the rounding of row-wide sums of cubes (general weights, p = 4/3), the factors of the
+    JVP reach the hundreds (operators on |x|), and the loss sums many terms of either sign."""
+    r = np.random.default_rng(77)
+    for rows, n in ((60, 66), (70, 449), (40, 963), (30, 1300), (6, 3000)):
+        x = (r.normal(size=(rows, n)) * 3).astype(np.float32)
+        x[:, : n // 2 : 7] += np.float32(1e-5) * r.normal(size=x[:, : n // 2 : 7].shape).astype(np.float32)
+        x[1::2, 1::3] = x[1::2, 0:-1:3][:, : x[1::2, 1::3].shape[1]] + np.float32(8e-6)   # near-ties
+        t = r.normal(size=(rows, n)).astype(np.float32)
+        weights = {"rank": np.arange(n, 0, -1).astype(np.float32),
+                   "per_row": -np.sort(-(r.normal(size=(rows, n)) ** 2).astype(np.float32), axis=1)}
+        for wname, w in weights.items():
+            for phi, phic in (("id", gpu.TOPK_PHI_IDENTITY), ("half_sq", gpu.TOPK_PHI_HALF_SQUARE)):
+                print(f"case shape={x.shape} w={wname} phi={phi}", flush=True)
+                ref = oracle.topk_general(x, w, P43, 0.01, phi, tangent=t)
+                o, j = (host(a) for a in gpu.topk_general_jvp(dev(x), dev(w), dev(t), phic, P43, 0.01))
+                close(o, ref["out"], "general fwd, small lambda")
+                close(j, ref["jvp"], "general jvp, small lambda")
+        xs = (x * np.float32(0.003)).astype(np.float32)           # |x| around lambda
+        for name, ofn in (("topk_signed_mask", oracle.topk_signed_mask),
+                          ("topk_masked_value", oracle.topk_masked_value)):
+            for k in (n // 10 + 1, n - 1, n):
+                ref = ofn(xs, k, P43, 0.01, tangent=t)
+                o, j = (host(a) for a in getattr(gpu, name + "_jvp")(dev(xs), dev(t), k, P43, 0.01))
+                close(o, ref["out"], name + " fwd, small lambda")
+                close(j, ref["jvp"], name + " jvp, small lambda")
 
 
 def test_binding_rejects_mismatched_tensors(gpu):
