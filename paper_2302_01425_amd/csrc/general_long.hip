@@ -31,7 +31,6 @@ static_assert(kGeneralLongMax <= 128 * kGT, "a thread keeps its block starts in 
 struct Mask128 {
   unsigned long long lo, hi;
 };
-__device__ __forceinline__ bool mask_any(const Mask128& m) { return (m.lo | m.hi) != 0; }
 __device__ __forceinline__ int mask_first(const Mask128& m) {
   if (m.lo) return __builtin_ctzll(m.lo);
   if (m.hi) return 64 + __builtin_ctzll(m.hi);
@@ -174,7 +173,6 @@ __global__ __launch_bounds__(kGT) void general_long_kernel(
   float* ss = reinterpret_cast<float*>(keys_all + base);   // keys now, sorted values from step 1 on
   const uint32_t* keys = keys_all + base;
   const uint32_t* idx = idx_all + base;
-  const float* x = x_all + base;
   const float* lw = w_all + row * w_stride;    // weights by sorted position
   const float* tangent = tangent_all != nullptr ? tangent_all + base : nullptr;
   float* out = out_all != nullptr ? out_all + base : nullptr;

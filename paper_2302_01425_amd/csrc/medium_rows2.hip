@@ -37,8 +37,6 @@ __global__ __launch_bounds__(kWT) void medium2_kernel(
   const bool want_jvp = jvp != nullptr;
   uint32_t* ka = keys_a + base;                // the row's list: keys
   uint32_t* pa = tau_a + base;                 //                 tangent bits
-  uint32_t* kb = keys_b + base;                // sorting buffers of lists that do not fit LDS
-  uint32_t* pb = idx_b + base;
 
   RowInfo ri;
   ri.src = 0;
