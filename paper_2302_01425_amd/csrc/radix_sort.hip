@@ -573,19 +573,81 @@ __global__ __launch_bounds__(kThreads) void select_compact_kernel(
 // that fall above it to the tile's count of elements above.
 // TAU: the surviving candidates' index payloads are replaced by tangent bits (see
 // select_compact_kernel); MAG says how the payload encodes the index.
-template <bool TAU = false, bool MAG = false>
-__global__ __launch_bounds__(kThreads) void select_recompact_kernel(
-    const RowSel* __restrict__ sel, uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
-    uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove, int64_t n, int tiles,
-    const float* __restrict__ tangent = nullptr) {
-  __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
-  const int64_t row = blockIdx.x / tiles;
-  const int tile = blockIdx.x % tiles;
+// A workgroup takes kWaves consecutive tiles of a row, one wavefront per tile: a slot of the first
+// level holds a few dozen entries, and with one tile per workgroup the kernel was a chain of
+// dependent latencies per tile.  Slots of more than kWaveSlot entries (a window that holds a
+// quarter of the row) are left to the whole workgroup, one after the other.
+constexpr int kWaveSlot = kItems * kWave;         // 1024 entries: kItems per lane
+
+template <bool TAU, bool MAG>
+__device__ __forceinline__ uint32_t recompact_payload(uint32_t key, uint32_t id, int64_t row_base,
+                                                      const float* __restrict__ tangent) {
+  if (!TAU) return id;
+  float t = 0.0f;
+  if (tangent != nullptr) {
+    t = tangent[row_base + (MAG ? (id >> 1) : id)];
+    // the key of |x| = 0 is that of +0.0: sign(0) = 0
+    if (MAG) t = key == 0x7fffffffu ? 0.0f : ((id & 1u) ? -t : t);
+  }
+  return __float_as_uint(t);
+}
+
+// one wavefront, a slot of at most kWaveSlot entries
+template <bool TAU, bool MAG>
+__device__ __forceinline__ void recompact_tile_wave(uint32_t klo, uint32_t khi, uint32_t* keys,
+                                                    uint32_t* idx, uint32_t* tcnt_p,
+                                                    uint32_t* tabove_p, int64_t slot,
+                                                    int64_t row_base, int nvalid,
+                                                    const float* __restrict__ tangent) {
+  const int lane = threadIdx.x & (kWave - 1);
+  uint32_t key[kItems], id[kItems], pos[kItems];
+  uint32_t ncand = 0, nabove = 0;
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    key[i] = id[i] = 0u;
+    pos[i] = 0xffffffffu;
+    if (i * kWave >= nvalid) continue;            // (uniform)
+    const int el = i * kWave + lane;
+    const bool valid = el < nvalid;
+    if (valid) {
+      key[i] = keys[slot + el];
+      id[i] = idx[slot + el];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    if (i * kWave >= nvalid) continue;
+    const bool valid = i * kWave + lane < nvalid;
+    const bool cand = valid && key[i] >= klo && key[i] <= khi;
+    const unsigned long long cm = __ballot(cand);
+    nabove += __popcll(__ballot(valid && key[i] < klo));
+    pos[i] = cand ? ncand + __popcll(cm & lanemask_lt()) : 0xffffffffu;
+    ncand += __popcll(cm);
+  }
+  // (every entry of the slot is in registers: the ballots have used them)
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    if (i * kWave >= nvalid) continue;
+    if (pos[i] != 0xffffffffu) {
+      keys[slot + pos[i]] = key[i];
+      idx[slot + pos[i]] = recompact_payload<TAU, MAG>(key[i], id[i], row_base, tangent);
+    }
+  }
+  if (lane == 0) {
+    *tcnt_p = ncand;
+    *tabove_p += nabove;
+  }
+}
+
+// the whole workgroup, any slot
+template <bool TAU, bool MAG>
+__device__ __forceinline__ void recompact_tile_block(uint32_t klo, uint32_t khi, uint32_t* keys,
+                                                     uint32_t* idx, uint32_t* tcnt_p,
+                                                     uint32_t* tabove_p, int64_t slot,
+                                                     int64_t row_base, int nvalid,
+                                                     const float* __restrict__ tangent,
+                                                     uint32_t* wave_cand, uint32_t* wave_above) {
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-  const int nvalid = int(tcnt[row * tiles + tile]);
-  if (nvalid == 0) return;
-  const uint32_t klo = sel[row].klo, khi = sel[row].khi;
-  const int64_t slot = row * n + int64_t(tile) * kTile;
   const int chunk = w * (kTile / kWaves);
   uint32_t key[kItems], id[kItems], pos[kItems];
   uint32_t ncand = 0, nabove = 0;
@@ -617,22 +679,43 @@ __global__ __launch_bounds__(kThreads) void select_recompact_kernel(
   for (int i = 0; i < kItems; ++i) {
     if (pos[i] != 0xffffffffu) {
       keys[slot + before + pos[i]] = key[i];
-      uint32_t payload = id[i];
-      if (TAU) {
-        float t = 0.0f;
-        if (tangent != nullptr) {
-          t = tangent[row * n + (MAG ? (id[i] >> 1) : id[i])];
-          // the key of |x| = 0 is that of +0.0: sign(0) = 0
-          if (MAG) t = key[i] == 0x7fffffffu ? 0.0f : ((id[i] & 1u) ? -t : t);
-        }
-        payload = __float_as_uint(t);
-      }
-      idx[slot + before + pos[i]] = payload;
+      idx[slot + before + pos[i]] = recompact_payload<TAU, MAG>(key[i], id[i], row_base, tangent);
     }
   }
   if (threadIdx.x == 0) {
-    tcnt[row * tiles + tile] = total;
-    tabove[row * tiles + tile] += above;
+    *tcnt_p = total;
+    *tabove_p += above;
+  }
+  __syncthreads();                         // (wave_cand, wave_above are used again for the next tile)
+}
+
+template <bool TAU = false, bool MAG = false>
+__global__ __launch_bounds__(kThreads) void select_recompact_kernel(
+    const RowSel* __restrict__ sel, uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
+    uint32_t* __restrict__ tcnt, uint32_t* __restrict__ tabove, int64_t n, int tiles, int groups,
+    const float* __restrict__ tangent = nullptr) {
+  __shared__ uint32_t wave_cand[kWaves], wave_above[kWaves];
+  const int64_t row = blockIdx.x / groups;
+  const int tile0 = (blockIdx.x % groups) * kWaves;
+  const int w = threadIdx.x / kWave;
+  const uint32_t klo = sel[row].klo, khi = sel[row].khi;
+  const int64_t row_base = row * n;
+  const int mine = tile0 + w;
+  const int nv = mine < tiles ? int(tcnt[row * tiles + mine]) : 0;
+  if (!__syncthreads_or(nv > kWaveSlot)) {
+    if (nv > 0)
+      recompact_tile_wave<TAU, MAG>(klo, khi, keys, idx, tcnt + row * tiles + mine,
+                                    tabove + row * tiles + mine, row_base + int64_t(mine) * kTile,
+                                    row_base, nv, tangent);
+    return;
+  }
+  for (int q = 0; q < kWaves && tile0 + q < tiles; ++q) {
+    const int tile = tile0 + q;
+    const int nvalid = int(tcnt[row * tiles + tile]);
+    if (nvalid == 0) continue;
+    recompact_tile_block<TAU, MAG>(klo, khi, keys, idx, tcnt + row * tiles + tile,
+                                   tabove + row * tiles + tile, row_base + int64_t(tile) * kTile,
+                                   row_base, nvalid, tangent, wave_cand, wave_above);
   }
 }
 
@@ -774,8 +857,10 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
                      B.keys_b, B.idx_b, B.tcnt, B.tabove, B.bins2, n, tiles);
   hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
                      B.bins2, B.sel, kSelSlices, R, cubic);
-  hipLaunchKernelGGL((select_recompact_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, st,
-                     B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles, nullptr);
+  const int groups = (tiles + kWaves - 1) / kWaves;
+  hipLaunchKernelGGL((select_recompact_kernel<false, false>), dim3(unsigned(rows * groups)),
+                     dim3(kThreads), 0, st, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles,
+                     groups, nullptr);
   hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
                      B.tabove, B.toff, B.taboff, B.sel, tiles);
   hipLaunchKernelGGL(select_gather_kernel, dim3(blocks), dim3(kThreads), 0, st, B.tcnt, B.toff,
@@ -815,8 +900,10 @@ void wide_select(const float* x, const float* tangent, int64_t rows, int64_t n, 
                      x, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, B.bins2, n, tiles, nullptr);
   hipLaunchKernelGGL((select_refine_kernel<MAG>), dim3(unsigned(rows)), dim3(kThreads), 0, st,
                      B.bins2, B.sel, kSelSlices, R, cubic);
-  hipLaunchKernelGGL((select_recompact_kernel<true, MAG>), dim3(blocks), dim3(kThreads), 0, st,
-                     B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles, tangent);
+  const int groups = (tiles + kWaves - 1) / kWaves;
+  hipLaunchKernelGGL((select_recompact_kernel<true, MAG>), dim3(unsigned(rows * groups)),
+                     dim3(kThreads), 0, st, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles,
+                     groups, tangent);
 }
 
 }  // namespace
