@@ -95,7 +95,9 @@ __global__ __launch_bounds__(kThreads) void long_window_kernel(
 // value: above the block's value window the literal 1 (mask) or its own singleton solution
 // (magnitude), below it 0, inside it (lo_incl <= value <= hi_incl: exactly the block, elements of
 // equal value pool together) the pooled formula with the row's gamma and d gamma.
-template <bool MAG, int PC>
+// VEC (rows that start 16-byte aligned in all four arrays, n a multiple of 4): 16-byte loads and
+// stores, element i of a thread is first + ((i / 4) * kThreads + thread) * 4 + i % 4.
+template <bool MAG, int PC, bool VEC>
 __global__ __launch_bounds__(kThreads) void wide_dense_kernel(
     const float* __restrict__ x_all, const float* __restrict__ tangent_all,
     const RowInfo* __restrict__ info, float* __restrict__ out_all, float* __restrict__ jvp_all,
@@ -110,17 +112,38 @@ __global__ __launch_bounds__(kThreads) void wide_dense_kernel(
   float* out = out_all != nullptr ? out_all + base : nullptr;
   float* jvp = jvp_all != nullptr ? jvp_all + base : nullptr;
   const bool have_block = ri.a <= ri.b;
+  auto elem = [&](int i) -> int64_t {
+    return VEC ? first + (int64_t(i / 4) * kThreads + threadIdx.x) * 4 + (i % 4)
+               : first + int64_t(i) * kThreads + threadIdx.x;
+  };
   float xv[8], tv[8];
+  // (the mask's JVP is zero outside the block: only the magnitude operator streams the tangent)
+  const bool stream_t = MAG && jvp != nullptr;
+  if (VEC) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
-    xv[i] = e < n ? load_stream(x_all + base + e) : 0.0f;
-    // the mask's JVP is zero outside the block: only the magnitude operator streams the tangent
-    tv[i] = (MAG && e < n && jvp != nullptr) ? load_stream(tangent + e) : 0.0f;
+    for (int q = 0; q < 2; ++q) {
+      const int64_t e = elem(4 * q);
+      float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+      if (e < n) {
+        a = load4_stream(x_all + base + e);
+        if (stream_t) b = load4_stream(tangent + e);
+      }
+      xv[4 * q] = a.x; xv[4 * q + 1] = a.y; xv[4 * q + 2] = a.z; xv[4 * q + 3] = a.w;
+      tv[4 * q] = b.x; tv[4 * q + 1] = b.y; tv[4 * q + 2] = b.z; tv[4 * q + 3] = b.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t e = elem(i);
+      xv[i] = e < n ? load_stream(x_all + base + e) : 0.0f;
+      tv[i] = (stream_t && e < n) ? load_stream(tangent + e) : 0.0f;
+    }
   }
+  float yo[8], dout[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int64_t e = first + int64_t(i) * kThreads + threadIdx.x;
+    const int64_t e = elem(i);
+    yo[i] = dout[i] = 0.0f;
     if (e >= n) continue;
     const float v = MAG ? fabsf(xv[i]) : xv[i];
     const bool above = v > ri.hi_incl;
@@ -155,8 +178,27 @@ __global__ __launch_bounds__(kThreads) void wide_dense_kernel(
         y = 1.0f;
       }
     }
-    if (out != nullptr) store_stream(out + e, y);
-    if (jvp != nullptr) store_stream(jvp + e, d);
+    yo[i] = y;
+    dout[i] = d;
+  }
+  if (VEC) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int64_t e = elem(4 * q);
+      if (e >= n) continue;
+      if (out != nullptr)
+        store4_stream(out + e, make_float4(yo[4 * q], yo[4 * q + 1], yo[4 * q + 2], yo[4 * q + 3]));
+      if (jvp != nullptr)
+        store4_stream(jvp + e, make_float4(dout[4 * q], dout[4 * q + 1], dout[4 * q + 2], dout[4 * q + 3]));
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t e = elem(i);
+      if (e >= n) continue;
+      if (out != nullptr) store_stream(out + e, yo[i]);
+      if (jvp != nullptr) store_stream(jvp + e, dout[i]);
+    }
   }
 }
 
@@ -164,8 +206,15 @@ template <bool MAG, int PC>
 void launch_wide_dense_t(const SortBuffers& B, const float* x, const float* tangent, float* out,
                          float* jvp, int64_t rows, int64_t n, const Reg& R, hipStream_t st) {
   const int chunks = int((n + kThreads * 8 - 1) / (kThreads * 8));
-  hipLaunchKernelGGL((wide_dense_kernel<MAG, PC>), dim3(unsigned(rows * chunks)), dim3(kThreads), 0,
-                     st, x, jvp ? tangent : nullptr, B.info, out, jvp, n, chunks, R);
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(out) |
+                         reinterpret_cast<uintptr_t>(jvp) |
+                         reinterpret_cast<uintptr_t>(jvp ? tangent : nullptr);
+  if ((bits & 15u) == 0 && n % 4 == 0)
+    hipLaunchKernelGGL((wide_dense_kernel<MAG, PC, true>), dim3(unsigned(rows * chunks)),
+                       dim3(kThreads), 0, st, x, jvp ? tangent : nullptr, B.info, out, jvp, n, chunks, R);
+  else
+    hipLaunchKernelGGL((wide_dense_kernel<MAG, PC, false>), dim3(unsigned(rows * chunks)),
+                       dim3(kThreads), 0, st, x, jvp ? tangent : nullptr, B.info, out, jvp, n, chunks, R);
 }
 
 template <bool MAG, int PC>
