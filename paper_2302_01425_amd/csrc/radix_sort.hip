@@ -292,6 +292,21 @@ __global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const float* _
       }
     }
   }
+  if (vec) {                                   // what is left in whole chunks: four 16-byte loads
+    for (; c0 + kSelChunk <= last; c0 += kSelChunk) {
+      float4 v[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        v[i] = load4_stream(xr + c0 + (int64_t(i) * kSelThreads + threadIdx.x) * 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        atomicAdd(&mine[first_key<MAG>(v[i].x) >> kSelShift], 1u);
+        atomicAdd(&mine[first_key<MAG>(v[i].y) >> kSelShift], 1u);
+        atomicAdd(&mine[first_key<MAG>(v[i].z) >> kSelShift], 1u);
+        atomicAdd(&mine[first_key<MAG>(v[i].w) >> kSelShift], 1u);
+      }
+    }
+  }
   for (; c0 < last; c0 += kSelChunk) {
     float v[16];
 #pragma unroll
