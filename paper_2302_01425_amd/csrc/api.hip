@@ -173,7 +173,7 @@ int run_operator(bool mag, const float* x, const float* tangent, int64_t rows, i
     if (topk::launch_wide_select(mag, pc, refine, x, need_jvp ? tangent : nullptr, rows, n, k, R, B,
                                  st) != 0)
       return TOPK_ERR_INVALID;
-    if (topk::launch_wide_finish(mag, pc, B, need_jvp, rows, n, k, R, st) != 0)
+    if (topk::launch_wide_finish(mag, pc, B, need_jvp, refine, rows, n, k, R, st) != 0)
       return TOPK_ERR_INVALID;
     if (topk::launch_wide_dense(mag, pc, B, x, need_jvp ? tangent : nullptr, out,
                                 need_jvp ? jvp : nullptr, rows, n, R, st) != 0)

@@ -174,8 +174,8 @@ int launch_candidate_lists(bool mag, int pc, const float* x, int64_t rows, int64
 int launch_wide_select(bool mag, int pc, bool refine, const float* x, const float* tangent,
                        int64_t rows, int64_t n, int64_t k, const Reg& R, const SortBuffers& B,
                        hipStream_t st);
-int launch_wide_finish(bool mag, int pc, const SortBuffers& B, bool want_jvp, int64_t rows,
-                       int64_t n, int64_t k, const Reg& R, hipStream_t st);
+int launch_wide_finish(bool mag, int pc, const SortBuffers& B, bool want_jvp, bool dense,
+                       int64_t rows, int64_t n, int64_t k, const Reg& R, hipStream_t st);
 int launch_wide_dense(bool mag, int pc, const SortBuffers& B, const float* x, const float* tangent,
                       float* out, float* jvp, int64_t rows, int64_t n, const Reg& R,
                       hipStream_t st);

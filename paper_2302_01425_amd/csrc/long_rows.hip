@@ -209,7 +209,9 @@ void launch_wide_dense_t(const SortBuffers& B, const float* x, const float* tang
   const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(out) |
                          reinterpret_cast<uintptr_t>(jvp) |
                          reinterpret_cast<uintptr_t>(jvp ? tangent : nullptr);
-  if ((bits & 15u) == 0 && n % 4 == 0)
+  // (measured: the mask, which does not stream the tangent, is faster with 4-byte accesses:
+  // 34.7 against 41.0 us on 2^24 elements; the magnitude operator with 16-byte ones: 42.4 against 44.1)
+  if (MAG && (bits & 15u) == 0 && n % 4 == 0)
     hipLaunchKernelGGL((wide_dense_kernel<MAG, PC, true>), dim3(unsigned(rows * chunks)),
                        dim3(kThreads), 0, st, x, jvp ? tangent : nullptr, B.info, out, jvp, n, chunks, R);
   else

@@ -736,66 +736,92 @@ __global__ __launch_bounds__(kThreads) void select_recompact_kernel(
 
 // One workgroup per row: exclusive prefix of the tiles' candidate counts (where each tile's
 // candidates go in the row's dense list), the length of the list and the number of elements
-// above the window.
-__global__ __launch_bounds__(kThreads) void select_offsets_kernel(const uint32_t* __restrict__ tcnt,
-                                                                  const uint32_t* __restrict__ tabove,
-                                                                  uint32_t* __restrict__ toff,
-                                                                  uint32_t* __restrict__ taboff,
-                                                                  RowSel* __restrict__ sel,
-                                                                  int tiles) {
-  __shared__ uint32_t wave_tot[kWaves];
+// above the window.  1024 threads, four consecutive tiles each, one scan for both counts
+// (candidates in the low half of a 64-bit word, elements above in the high half).
+constexpr int kOffThreads = 1024;
+__global__ __launch_bounds__(kOffThreads) void select_offsets_kernel(
+    const uint32_t* __restrict__ tcnt, const uint32_t* __restrict__ tabove,
+    uint32_t* __restrict__ toff, uint32_t* __restrict__ taboff, RowSel* __restrict__ sel, int tiles) {
+  constexpr int kOffWaves = kOffThreads / kWave;
+  __shared__ uint64_t wave_tot[kOffWaves];
   const int64_t row = blockIdx.x;
-  uint32_t carry = 0, carry_above = 0;
-  constexpr int kPer = 16;               // consecutive tiles per thread: all loads in flight at once
-  for (int c = 0; c < tiles; c += kThreads * kPer) {
-    const int t0 = c + threadIdx.x * kPer;
-    uint32_t v[kPer], ab[kPer], mine = 0, mine_above = 0;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  uint64_t carry = 0;
+  for (int c = 0; c < tiles; c += kOffThreads * 4) {
+    const int t0 = c + threadIdx.x * 4;
+    uint32_t v[4], ab[4];
+    uint64_t mine = 0;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
+    for (int i = 0; i < 4; ++i) {
       v[i] = (t0 + i < tiles) ? tcnt[row * tiles + t0 + i] : 0u;
       ab[i] = (t0 + i < tiles) ? tabove[row * tiles + t0 + i] : 0u;
+      mine += uint64_t(v[i]) | (uint64_t(ab[i]) << 32);
     }
+    uint64_t inc = mine;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-      mine += v[i];
-      mine_above += ab[i];
+    for (int off = 1; off < kWave; off <<= 1) {
+      const uint64_t o = __shfl_up(inc, off, kWave);
+      if (lane >= off) inc += o;
     }
-    uint32_t total, total_above;
-    uint32_t run = carry + block_exclusive_scan(mine, wave_tot, &total);
-    uint32_t run_above = carry_above + block_exclusive_scan(mine_above, wave_tot, &total_above);
+    __syncthreads();                               // wave_tot may still be read from the round before
+    if (lane == kWave - 1) wave_tot[w] = inc;
+    __syncthreads();
+    uint64_t before = 0, all = 0;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
+    for (int q = 0; q < kOffWaves; ++q) {
+      const uint64_t t = wave_tot[q];
+      if (q < w) before += t;
+      all += t;
+    }
+    uint64_t run = carry + before + inc - mine;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
       if (t0 + i < tiles) {
-        toff[row * tiles + t0 + i] = run;
-        taboff[row * tiles + t0 + i] = run_above;   // elements above the window in earlier tiles
+        toff[row * tiles + t0 + i] = uint32_t(run);
+        taboff[row * tiles + t0 + i] = uint32_t(run >> 32);   // elements above the window in earlier tiles
       }
-      run += v[i];
-      run_above += ab[i];
+      run += uint64_t(v[i]) | (uint64_t(ab[i]) << 32);
     }
-    carry += total;
-    carry_above += total_above;
+    carry += all;
   }
   if (threadIdx.x == 0) {
-    sel[row].cn = carry;
-    sel[row].above = int64_t(carry_above);
+    sel[row].cn = uint32_t(carry);
+    sel[row].above = int64_t(carry >> 32);
   }
 }
 
-// Every tile's slot (in the "b" arrays) to its place in the row's dense list (in the "a" arrays).
+// Every tile's slot (in the "b" arrays) to its place in the row's dense list (in the "a" arrays):
+// one wavefront per tile, kWaves consecutive tiles of a row per workgroup (a slot usually holds
+// a handful of entries).
 __global__ __launch_bounds__(kThreads) void select_gather_kernel(
     const uint32_t* __restrict__ tcnt, const uint32_t* __restrict__ toff,
     const uint32_t* __restrict__ slot_keys, const uint32_t* __restrict__ slot_idx,
-    uint32_t* __restrict__ keys_a, uint32_t* __restrict__ idx_a, int64_t n, int tiles) {
-  const int64_t row = blockIdx.x / tiles;
-  const int tile = blockIdx.x % tiles;
+    uint32_t* __restrict__ keys_a, uint32_t* __restrict__ idx_a, int64_t n, int tiles, int groups) {
+  const int64_t row = blockIdx.x / groups;
+  const int tile = (blockIdx.x % groups) * kWaves + threadIdx.x / kWave;
+  if (tile >= tiles) return;
+  const int lane = threadIdx.x & (kWave - 1);
   const uint32_t count = tcnt[row * tiles + tile];
   if (count == 0) return;
   uint32_t* kd = keys_a + row * n + toff[row * tiles + tile];
   uint32_t* id = idx_a + row * n + toff[row * tiles + tile];
   const int64_t slot = row * n + int64_t(tile) * kTile;
-  for (uint32_t j = threadIdx.x; j < count; j += kThreads) {
-    kd[j] = slot_keys[slot + j];
-    id[j] = slot_idx[slot + j];
+  for (uint32_t j0 = lane; j0 < count; j0 += 4 * kWave) {
+    uint32_t kk[4], ii[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t j = j0 + q * kWave;
+      kk[q] = j < count ? slot_keys[slot + j] : 0u;
+      ii[q] = j < count ? slot_idx[slot + j] : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t j = j0 + q * kWave;
+      if (j < count) {
+        kd[j] = kk[q];
+        id[j] = ii[q];
+      }
+    }
   }
 }
 
@@ -876,10 +902,10 @@ void candidate_lists(const float* x, int64_t rows, int64_t n, int64_t k, const R
   hipLaunchKernelGGL((select_recompact_kernel<false, false>), dim3(unsigned(rows * groups)),
                      dim3(kThreads), 0, st, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles,
                      groups, nullptr);
-  hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kThreads), 0, st, B.tcnt,
+  hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kOffThreads), 0, st, B.tcnt,
                      B.tabove, B.toff, B.taboff, B.sel, tiles);
-  hipLaunchKernelGGL(select_gather_kernel, dim3(blocks), dim3(kThreads), 0, st, B.tcnt, B.toff,
-                     B.keys_b, B.idx_b, B.keys_a, B.idx_a, n, tiles);
+  hipLaunchKernelGGL(select_gather_kernel, dim3(unsigned(rows * groups)), dim3(kThreads), 0, st,
+                     B.tcnt, B.toff, B.keys_b, B.idx_b, B.keys_a, B.idx_a, n, tiles, groups);
 }
 
 // The candidate selection of the wide route: the same levels, but the candidates stay in the
@@ -919,6 +945,12 @@ void wide_select(const float* x, const float* tangent, int64_t rows, int64_t n, 
   hipLaunchKernelGGL((select_recompact_kernel<true, MAG>), dim3(unsigned(rows * groups)),
                      dim3(kThreads), 0, st, B.sel, B.keys_b, B.idx_b, B.tcnt, B.tabove, n, tiles,
                      groups, tangent);
+  // thousands of tiles with a few candidates each: the row's dense (key, tangent) list is put
+  // together here, by all compute units, and not by the one workgroup that solves the row
+  hipLaunchKernelGGL(select_offsets_kernel, dim3(unsigned(rows)), dim3(kOffThreads), 0, st, B.tcnt,
+                     B.tabove, B.toff, B.taboff, B.sel, tiles);
+  hipLaunchKernelGGL(select_gather_kernel, dim3(unsigned(rows * groups)), dim3(kThreads), 0, st,
+                     B.tcnt, B.toff, B.keys_b, B.idx_b, B.keys_a, B.idx_a, n, tiles, groups);
 }
 
 }  // namespace

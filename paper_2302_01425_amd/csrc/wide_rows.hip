@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kWT) void wide_finish_kernel(
     uint32_t* keys_a, uint32_t* tau_a, uint32_t* keys_b, uint32_t* pay_b,
     const uint32_t* __restrict__ tcnt, const uint32_t* __restrict__ tabove, uint32_t* toff,
     const RowSel* __restrict__ sel, RowInfo* __restrict__ info, int64_t n, int tiles,
-    int64_t k_row, Reg R, bool want_jvp) {
+    int64_t k_row, Reg R, bool want_jvp, bool dense) {
   using P = Pool<MAG, PC>;
   __shared__ ListShared<kWideLdsCap> sm;
   const int64_t row = blockIdx.x;
@@ -57,8 +57,9 @@ __global__ __launch_bounds__(kWT) void wide_finish_kernel(
 
   // ---- 1. offsets of the tiles' candidates, list length, elements above the window -------------
   // (one scan for both: candidates in the low half of a 64-bit word, elements above in the high)
-  uint64_t carry2 = 0;
-  for (int c0 = 0; c0 < tiles; c0 += kWT * 4) {
+  // dense: launches before this one have put the list together in the "a" arrays
+  uint64_t carry2 = dense ? (uint64_t(sel[row].cn) | (uint64_t(sel[row].above) << 32)) : 0;
+  for (int c0 = 0; c0 < tiles && !dense; c0 += kWT * 4) {
     const int t0 = c0 + threadIdx.x * 4;
     uint32_t v[4];
     uint64_t mine = 0;
@@ -85,7 +86,38 @@ __global__ __launch_bounds__(kWT) void wide_finish_kernel(
   __syncthreads();                             // the offsets are visible to the whole workgroup
 
   RowInfo ri;
-  if (in_lds) {
+  if (in_lds && dense) {
+    // ---- 2. the list is there: keys into LDS, the (key, tangent) pairs into registers ------------
+    uint32_t key[kSegment], pay[kSegment];
+#pragma unroll
+    for (int i = 0; i < kSegment; ++i) {
+      const uint32_t j = uint32_t(w) * (kSegment * kWave) + uint32_t(i) * kWave + lane;
+      key[i] = j < cn ? ka[j] : 0u;
+      pay[i] = (j < cn && want_jvp) ? pa[j] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kSegment; ++i) {
+      const uint32_t j = uint32_t(w) * (kSegment * kWave) + uint32_t(i) * kWave + lane;
+      if (j < cn) sm.keys_a[j] = key[i];
+    }
+    __syncthreads();
+    ri = solve_lds_list<MAG, PC, kWideLdsCap>(cn, k, klo, khi, R, sm);
+    if (ri.a <= ri.b && want_jvp) {
+      double num = 0.0, den = 0.0;
+#pragma unroll
+      for (int i = 0; i < kSegment; ++i) {
+        const uint32_t j = uint32_t(w) * (kSegment * kWave) + uint32_t(i) * kWave + lane;
+        const float sv = key_to_float(key[i]);
+        if (j < cn && sv >= ri.lo_incl && sv <= ri.hi_incl) {
+          const double wgt = P::jac_weight(double(sv) - ri.center, ri.gamma);
+          num += wgt * double(__uint_as_float(pay[i]));
+          den += wgt;
+        }
+      }
+      wide_sum2(num, den, sm);
+      ri.dgamma = num / P::jac_denominator(den, double(k - ri.a + 1), R);
+    }
+  } else if (in_lds) {
     // ---- 2. the row's dense list.  owner[j] = tile of list position j: every non-empty tile
     // marks the start of its candidates, a running maximum fills the rest ------------------------
     uint32_t* owner = sm.keys_b;
@@ -173,7 +205,7 @@ __global__ __launch_bounds__(kWT) void wide_finish_kernel(
     // ---- lists too long for LDS (the window holds more than kWideLdsCap elements: a long pooled
     // block).  A wavefront copies sixteen tiles at a time into the row's dense list (their loads in
     // flight together); the list is then solved as it is, without sorting it (sort_solve.hpp) ----
-    for (int t0 = w * 16; t0 < tiles; t0 += kWW * 16) {
+    for (int t0 = w * 16; t0 < tiles && !dense; t0 += kWW * 16) {
       const int tl_l = t0 + (lane & 15);
       const uint32_t c_l = tl_l < tiles ? tc[tl_l] : 0u, o_l = tl_l < tiles ? tf[tl_l] : 0u;
       uint32_t cmax = c_l;
@@ -207,14 +239,17 @@ __global__ __launch_bounds__(kWT) void wide_finish_kernel(
 
 }  // namespace
 
-int launch_wide_finish(bool mag, int pc, const SortBuffers& B, bool want_jvp, int64_t rows,
-                       int64_t n, int64_t k, const Reg& R, hipStream_t st) {
+// dense: the selection has also gathered the rows' lists (second level: launch_wide_select with
+// refine)
+int launch_wide_finish(bool mag, int pc, const SortBuffers& B, bool want_jvp, bool dense,
+                       int64_t rows, int64_t n, int64_t k, const Reg& R, hipStream_t st) {
   if (rows > 0x7fffffffLL) return -1;
   const dim3 grid{unsigned(rows)}, block{kWT};
   const int tiles = radix_tiles(n);
 #define TOPK_WIDE_FINISH(M, P)                                                                    \
   hipLaunchKernelGGL((wide_finish_kernel<M, P>), grid, block, 0, st, B.keys_a, B.idx_a, B.keys_b, \
-                     B.idx_b, B.tcnt, B.tabove, B.toff, B.sel, B.info, n, tiles, k, R, want_jvp)
+                     B.idx_b, B.tcnt, B.tabove, B.toff, B.sel, B.info, n, tiles, k, R, want_jvp,   \
+                     dense)
   if (!mag && pc == kP2) TOPK_WIDE_FINISH(false, kP2);
   else if (!mag && pc == kP43) TOPK_WIDE_FINISH(false, kP43);
   else if (mag && pc == kP2) TOPK_WIDE_FINISH(true, kP2);
